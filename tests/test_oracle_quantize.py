@@ -1,0 +1,333 @@
+"""Pins of the oracle's rotation and quantizers: orthogonality and explicit Sylvester matrix,
+exact round trips, a library cast for the scale bytes, brute-force nearest codes, the paper's
+Table 1, the no-clipping property of Q_SR, the literal EDEN factor of Algorithm 1 in double,
+and the unbiasedness corollary (error of the B-sample mean falls as 1/B)."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_22813_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+E2M1 = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0, -0.0, -0.5, -1.0, -1.5, -2.0, -3.0, -4.0, -6.0])
+S_RTN, S_SR, S_EDEN = 6.0, 96.0 / 17.0, 96.0 / 17.0 / 0.93
+
+
+def sylvester(n=128):
+    i = np.arange(n)
+    pc = np.vectorize(lambda v: bin(v).count("1"))(i[:, None] & i[None, :])
+    return np.where(pc % 2 == 0, 1.0, -1.0)
+
+
+def unpack(codes):
+    lo, hi = codes & 15, codes >> 4
+    return np.stack([lo, hi], axis=-1).reshape(codes.shape[0], -1)
+
+
+def e4m3_values(bytes_):
+    return torch.from_numpy(np.ascontiguousarray(bytes_)).view(torch.float8_e4m3fn).float().numpy()
+
+
+def dequant_f64(q):
+    c = E2M1[unpack(q.codes)]
+    s = np.repeat(e4m3_values(q.scales).astype(np.float64), 16, axis=1)
+    return c * s * float(q.tensor_scale[0])
+
+
+def inverse_rht(y, signs):
+    """RHT^-1 of rows of y (chunks of 128): x = d .* (H^T y) / sqrt(128)."""
+    H = sylvester()
+    R, C = y.shape
+    z = y.reshape(R, C // 128, 128) @ H / np.sqrt(128.0)   # H is symmetric
+    return (z * signs).reshape(R, C)
+
+
+# ---------------------------------------------------------------------------- rotation
+
+def test_sylvester_is_orthogonal():
+    H = sylvester().astype(np.int64)
+    assert np.array_equal(H @ H.T, 128 * np.eye(128, dtype=np.int64))
+
+
+def test_rht_equals_explicit_matrix(oracle):
+    seed = 11
+    d = oracle.rht_signs(seed)
+    H = sylvester()
+    eye = np.eye(128, dtype=np.float32)
+    y, amax = oracle.rht(eye, seed_rht=seed)
+    # row j of the input is e_j, so row j of the output is column j of H diag(d) / sqrt(128)
+    want = (H * d[None, :]).T / np.sqrt(128.0)
+    assert np.allclose(y, want, rtol=0, atol=1e-8)
+    assert amax == pytest.approx(2.0 ** -3.5, rel=1e-7)
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((8, 384)).astype(np.float32)
+    y, amax = oracle.rht(x, seed_rht=seed)
+    want = ((x.astype(np.float64).reshape(8, 3, 128) * d) @ H.T / np.sqrt(128.0)).reshape(8, 384)
+    assert np.allclose(y, want, rtol=0, atol=2e-6)
+    assert amax == np.abs(y).max()
+    assert np.allclose((y.astype(np.float64) ** 2).sum(1), (x.astype(np.float64) ** 2).sum(1), rtol=1e-6)
+    # group 0 = no rotation
+    y0, _ = oracle.rht(x, rht_group=0)
+    assert np.array_equal(y0, x)
+    # different seeds give different rotations
+    assert not np.array_equal(oracle.rht(x, seed_rht=1)[0], oracle.rht(x, seed_rht=2)[0])
+
+
+def test_rht_transpose_and_bf16(oracle):
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((256, 48)).astype(np.float32)
+    yt, at = oracle.rht(x, transpose=True, seed_rht=5)
+    y, a = oracle.rht(np.ascontiguousarray(x.T), seed_rht=5)
+    assert yt.shape == (48, 256) and np.array_equal(yt, y) and at == a
+    xb = synth.f32_to_bf16_bits(x)
+    yb, _ = oracle.rht(xb, transpose=True, seed_rht=5)
+    yf, _ = oracle.rht(synth.bf16_bits_to_f32(xb), transpose=True, seed_rht=5)
+    assert np.array_equal(yb, yf)
+
+
+def test_rotation_cancels_on_the_inner_dimension(oracle):
+    # Sec. 3.3 (after the corollary): RHT^-1 is never applied because it cancels in the GEMM
+    rng = np.random.default_rng(2)
+    a = rng.standard_normal((16, 256)).astype(np.float32)
+    b = rng.standard_normal((24, 256)).astype(np.float32)
+    ya, _ = oracle.rht(a, seed_rht=9)
+    yb, _ = oracle.rht(b, seed_rht=9)
+    assert np.allclose(ya.astype(np.float64) @ yb.astype(np.float64).T,
+                       a.astype(np.float64) @ b.astype(np.float64).T, atol=1e-4)
+    assert np.allclose(inverse_rht(ya.astype(np.float64), oracle.rht_signs(9)), a, atol=1e-5)
+
+
+# ---------------------------------------------------------------------------- RTN / SR
+
+def test_rtn_exact_round_trip_of_representable_tensors(oracle):
+    rng = np.random.default_rng(3)
+    for x32 in (2.0 ** -3, 0.375, 1.0):
+        R, G = 32, 12
+        codes = rng.integers(0, 16, size=(R, G * 16))
+        codes[:, ::16] = 7                               # a 6 in every group
+        scales = rng.integers(0x20, 0x7F, size=(R, G)).astype(np.uint8)
+        scales[3, 5] = 0x7E                              # one group at the cap 448
+        x = (E2M1[codes] * np.repeat(e4m3_values(scales).astype(np.float64), 16, 1) * x32)
+        x = x.astype(np.float32)
+        assert np.array_equal(x.astype(np.float64), E2M1[codes] *
+                              np.repeat(e4m3_values(scales).astype(np.float64), 16, 1) * x32)
+        q = oracle.quantize(x, oracle.RTN, rht_group=0)
+        assert q.tensor_scale[0] == np.float32(x32)
+        assert np.array_equal(q.scales, scales)
+        got = unpack(q.codes)
+        assert np.array_equal(E2M1[got], E2M1[codes])    # -0 and +0 compare equal
+        assert np.array_equal(oracle.dequantize(q), x)
+
+
+@pytest.mark.parametrize("mode,s,cap", [(0, S_RTN, 448.0), (1, S_SR, 448.0), (2, S_EDEN, 256.0)])
+def test_scales_and_codes_against_library_cast_and_brute_force(oracle, mode, s, cap):
+    """Recompute x^FP32, the RTN_FP8 scale bytes (torch's float8 cast) and the nearest FP4 codes
+    (brute force over the grid) for every group and compare with the oracle."""
+    rng = np.random.default_rng(4)
+    x = (rng.standard_t(3, size=(48, 256)) * 0.1).astype(np.float32)
+    seed_rht, seed_sr = 21, 22
+    q = oracle.quantize(x, mode, seed_rht=seed_rht, seed_sr=seed_sr)
+    y, amax = oracle.rht(x, seed_rht=seed_rht)
+    x32 = np.float32(amax) / (np.float32(s) * np.float32(cap))
+    assert q.tensor_scale[0] == x32
+    gmax = np.abs(y).reshape(48, 16, 16).max(-1)
+    r = gmax / (x32 * np.float32(s))
+    assert r.max() <= cap * (1 + 1e-6)
+    want_bytes = torch.from_numpy(r.astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    if mode != 2:
+        assert np.array_equal(q.scales, want_bytes)
+    x8 = e4m3_values(want_bytes)
+    qn = y.astype(np.float64) / np.repeat(x8.astype(np.float64) * np.float64(x32), 16, 1)
+    got = unpack(q.codes)
+    if mode == 1:
+        # Q_SR never clips (Sec. 3.1) and each code is one of the two grid neighbours
+        assert np.abs(qn).max() <= 6.0 * (1 + 1e-6)
+        mags = np.abs(E2M1[got])
+        grid = E2M1[:8]
+        lo = grid[np.searchsorted(grid, np.minimum(np.abs(qn), 6.0) * (1 - 1e-7), side="right") - 1]
+        hi = grid[np.minimum(np.searchsorted(grid, np.abs(qn) * (1 + 1e-7), side="left"), 7)]
+        assert np.all((mags >= lo) & (mags <= hi))
+        assert np.array_equal((got >> 3) == 1, np.signbit(y))
+    else:
+        nearest = np.abs(np.abs(qn)[..., None] - E2M1[:8]).argmin(-1)
+        dist_got = np.abs(np.abs(qn) - np.abs(E2M1[got]))
+        dist_best = np.abs(np.abs(qn) - E2M1[nearest])
+        assert np.all(dist_got <= dist_best + 1e-6)      # equal up to exact ties
+        assert (np.abs(E2M1[got]) != E2M1[nearest]).mean() < 1e-4
+        assert np.array_equal((got >> 3) == 1, np.signbit(y))
+        if mode == 2:
+            assert (np.abs(qn) > 6.0).any()               # s* clips some values
+
+
+def test_table1_mse_on_standard_normal(oracle):
+    rows = {l.split()[0]: float(l.split()[2]) for l in open(os.path.join(GOLDEN, "table1_mse.txt"))
+            if l.strip() and not l.startswith("#")}
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((512, 2048)).astype(np.float32)
+    got = {}
+    for name, mode in [("RTN", 0), ("SR", 1), ("MS_EDEN", 2)]:
+        q = oracle.quantize(x, mode, seed_rht=1, seed_sr=2)
+        y, _ = oracle.rht(x, seed_rht=1)
+        got[name] = np.mean((dequant_f64(q) - y) ** 2) * 1e3
+        assert got[name] == pytest.approx(rows[name], rel=0.03)
+    # the abstract: more than 2x lower quantization error than SR
+    assert got["SR"] / got["MS_EDEN"] > 2.0
+
+
+def test_eden_grid_max_minimises_mse(oracle):
+    # Sec. 3.3: s = (1/0.93) * 6 * 16/17 minimises the expected MSE over N(0,1)
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((256, 2048)).astype(np.float32)
+    y, _ = oracle.rht(x, seed_rht=1)
+
+    def mse(s):
+        q = oracle.quantize(x, oracle.MS_EDEN, seed_rht=1, seed_sr=2, s_override=s)
+        return np.mean((dequant_f64(q) - y) ** 2)
+
+    base = mse(0.0)
+    assert base == mse(float(np.float32(S_EDEN)))
+    for factor in (0.90, 0.95, 1.05, 1.10):
+        assert mse(float(np.float32(S_EDEN * factor))) > base
+
+
+# ---------------------------------------------------------------------------- MS-EDEN
+
+def test_ms_eden_is_algorithm_1_in_double(oracle):
+    rng = np.random.default_rng(7)
+    x = synth.bf16_bits_to_f32(synth.student_t_bf16((32, 512), 3, 0.1, 7))
+    seed_rht = 31
+    y, amax = oracle.rht(x, seed_rht=seed_rht)
+    y = y.astype(np.float64)
+    q_a = oracle.quantize(x, oracle.MS_EDEN, seed_rht=seed_rht, seed_sr=100)
+    q_b = oracle.quantize(x, oracle.MS_EDEN, seed_rht=seed_rht, seed_sr=101)
+    # only the scales are stochastic
+    assert np.array_equal(q_a.codes, q_b.codes)
+    assert q_a.tensor_scale[0] == q_b.tensor_scale[0]
+    assert not np.array_equal(q_a.scales, q_b.scales)
+    # Q_RTN(x, s) with cap 256: recompute the un-corrected scales with the library cast
+    x32 = np.float32(amax) / (np.float32(S_EDEN) * np.float32(256.0))
+    assert q_a.tensor_scale[0] == x32
+    gmax = np.abs(y).reshape(32, 32, 16).max(-1).astype(np.float32)
+    b0 = torch.from_numpy(gmax / (x32 * np.float32(S_EDEN))).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    x8 = e4m3_values(b0).astype(np.float64)
+    c = E2M1[unpack(q_a.codes)]
+    x_rtn = c * np.repeat(x8, 16, 1) * np.float64(x32)
+    yy = (y * y).reshape(32, 32, 16).sum(-1)
+    yr = (y * x_rtn).reshape(32, 32, 16).sum(-1)
+    S = yy / yr
+    # the paper quotes [0.94, 1.06] as the practical range of the correction
+    assert 0.85 < S.min() and S.max() < 1.25 and 0.94 < np.median(S) < 1.06
+    target = S * x8
+    grid = e4m3_values(np.arange(127, dtype=np.uint8)).astype(np.float64)
+    for qq in (q_a, q_b):
+        got = e4m3_values(qq.scales).astype(np.float64)
+        lo = grid[np.searchsorted(grid, target * (1 - 1e-6), side="right") - 1]
+        hi = grid[np.minimum(np.searchsorted(grid, target * (1 + 1e-6), side="left"), 126)]
+        assert np.all((got >= lo) & (got <= hi))
+    # over many rounding seeds the scale equals S * x8 in expectation
+    B = 400
+    acc = np.zeros_like(target)
+    for sd in range(B):
+        acc += e4m3_values(oracle.quantize(x, oracle.MS_EDEN, seed_rht=seed_rht, seed_sr=1000 + sd).scales)
+    mean = acc / B
+    step = 0.125 * target            # an E4M3 step is at most 1/8 of the value
+    z = (mean - target) / (step / 2 / np.sqrt(B))
+    assert np.abs(z).max() < 6 and abs(z.mean()) < 0.2
+
+
+def test_ms_eden_scale_draw_is_the_documented_one(oracle):
+    # the byte of group (row, cg) is SR_FP8(t) with the 20-bit draw of (seed_sr, row, cg)
+    x = synth.bf16_bits_to_f32(synth.normal_bf16((8, 128), 1.0, 9))
+    seed_rht, seed_sr = 3, 4
+    q = oracle.quantize(x, oracle.MS_EDEN, seed_rht=seed_rht, seed_sr=seed_sr)
+    y, amax = oracle.rht(x, seed_rht=seed_rht)
+    x32 = q.tensor_scale[0]
+    c = E2M1[unpack(q.codes)]
+    for r in range(8):
+        for g in range(8):
+            yg = y[r, g * 16:(g + 1) * 16].astype(np.float64)
+            t = (yg * yg).sum() / ((yg * c[r, g * 16:(g + 1) * 16]).sum() * float(x32))
+            want = oracle.e4m3_sr(float(np.float32(t)), oracle.scale_draw(seed_sr, r, g))
+            # t is recomputed in double here, so allow the neighbouring byte only when the
+            # draw sits within 1e-5 of the rounding threshold
+            assert abs(int(q.scales[r, g]) - want) <= 1
+    agree = np.mean([[q.scales[r, g] == oracle.e4m3_sr(
+        float(np.float32((y[r, g*16:(g+1)*16].astype(np.float64) ** 2).sum() /
+                         ((y[r, g*16:(g+1)*16].astype(np.float64) * c[r, g*16:(g+1)*16]).sum() * float(x32)))),
+        oracle.scale_draw(seed_sr, r, g)) for g in range(8)] for r in range(8)])
+    assert agree > 0.95
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_unbiasedness_error_of_the_mean_falls_as_one_over_B(oracle, mode):
+    """Corollary of Sec. 3.3 / App. A: E RHT^-1(x_hat) = x, so the relative quadratic error of
+    the mean of B independent quantizations is MSE_1 / B; a biased scheme plateaus."""
+    x = synth.bf16_bits_to_f32(synth.student_t_bf16((64, 128), 3, 0.1, 1))
+    B = 1000
+    acc = np.zeros(x.shape)
+    mse1 = 0.0
+    xn = (x.astype(np.float64) ** 2).sum()
+    for b in range(B):
+        q = oracle.quantize(x, mode, seed_rht=10_000 + b, seed_sr=20_000 + b)
+        xh = inverse_rht(dequant_f64(q), oracle.rht_signs(10_000 + b))
+        acc += xh
+        mse1 += ((xh - x) ** 2).sum() / xn
+    mse1 /= B
+    err_mean = ((acc / B - x) ** 2).sum() / xn
+    ratio = err_mean * B / mse1
+    print("mode", mode, "MSE_1", mse1, "error of the mean x B / MSE_1", ratio)
+    if mode == 0:
+        # RTN is biased: even with a fresh rotation per sample (which turns part of the bias
+        # into noise) the error of the mean stays well above MSE_1 / B, and without a rotation
+        # every sample is the same and nothing averages out
+        assert ratio > 2.5
+        q = oracle.quantize(x, 0, rht_group=0)
+        assert ((dequant_f64(q) - x) ** 2).sum() / xn > 100 * mse1 / B
+    else:
+        assert ratio < 1.5
+
+
+# ---------------------------------------------------------------------------- layouts, edges
+
+def test_transpose_bf16_amax_and_requantize_are_consistent(oracle):
+    xb = synth.student_t_bf16((256, 64), 3, 0.1, 2)
+    xf = synth.bf16_bits_to_f32(xb)
+    for mode in (0, 1, 2):
+        qt = oracle.quantize(xb, mode, transpose=True, seed_rht=5, seed_sr=6)
+        q = oracle.quantize(np.ascontiguousarray(xf.T), mode, seed_rht=5, seed_sr=6)
+        assert qt.codes.shape == (64, 128) and qt.scales.shape == (64, 16)
+        assert np.array_equal(qt.codes, q.codes) and np.array_equal(qt.scales, q.scales)
+        assert qt.tensor_scale[0] == q.tensor_scale[0]
+    # a supplied amax replaces the measured one
+    y, amax = oracle.rht(xf, transpose=True, seed_rht=5)
+    q1 = oracle.quantize(xf, oracle.MS_EDEN, transpose=True, seed_rht=5, seed_sr=6, amax=amax)
+    q2 = oracle.quantize(xf, oracle.MS_EDEN, transpose=True, seed_rht=5, seed_sr=6)
+    assert np.array_equal(q1.codes, q2.codes) and np.array_equal(q1.scales, q2.scales)
+    q3 = oracle.quantize(xf, oracle.RTN, rht_group=0, amax=2 * float(np.abs(xf).max()))
+    assert q3.tensor_scale[0] == np.float32(2 * np.abs(xf).max()) / np.float32(2688.0)
+    # re-quantization = dequantize, transpose, quantize
+    saved = oracle.quantize(xf, oracle.RTN, rht_group=0)
+    rq = oracle.requantize(saved, oracle.MS_EDEN, transpose=True, seed_rht=8, seed_sr=9)
+    direct = oracle.quantize(np.ascontiguousarray(oracle.dequantize(saved).T), oracle.MS_EDEN,
+                             seed_rht=8, seed_sr=9)
+    assert np.array_equal(rq.codes, direct.codes) and np.array_equal(rq.scales, direct.scales)
+    assert np.allclose(oracle.dequantize(saved), dequant_f64(saved), rtol=1e-7)
+
+
+def test_degenerate_inputs(oracle):
+    z = np.zeros((4, 128), dtype=np.float32)
+    for mode in (0, 1, 2):
+        q = oracle.quantize(z, mode)
+        assert q.tensor_scale[0] == 1.0 and not q.codes.any() and not q.scales.any()
+    # one huge value: every other group under-flows the E4M3 scale and is emitted as zeros
+    x = np.full((2, 256), 1e-9, dtype=np.float32)
+    x[0, 0] = 1e6
+    q = oracle.quantize(x, oracle.RTN, rht_group=0)
+    assert q.scales[0, 0] == 0x7E and not q.scales[1].any() and not q.codes[1].any()
+    with pytest.raises(ValueError):
+        oracle.quantize(np.zeros((4, 24), np.float32), 0, rht_group=0)
+    with pytest.raises(ValueError):
+        oracle.quantize(np.zeros((4, 64), np.float32), 0, rht_group=128)
+    assert oracle.quantize(np.zeros((0, 128), np.float32), 2).codes.shape == (0, 64)
