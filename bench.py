@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the NVFP4 linear-layer hot path on one MI355X.
+
+One step = one pass of the whole path over synthetic inputs already resident in HBM:
+  A. the MS-EDEN quantizer on the quantize-only configuration (8192 x 8192 bf16,
+     0.1 * Student-t(3), rotation groups of 128), blocks along rows and then along columns,
+     each as the literal two kernels of Algorithm 1 (rotated abs-max, then quantize);
+  B. one linear layer forward + backward (tokens 16384, d_in 2048 -> d_out 8192, bf16):
+     qii_linear_fwd + qii_linear_bwd = six quantizations and three block-scaled GEMMs.
+`value` is the quantizer's algorithmic GB/s over part A (the benchmark's first metric, on
+configs[1]); the layer's TFLOP/s over part B is reported beside it.  Inputs rotate over more
+than 512 MiB of distinct buffers so that the 256 MiB Infinity Cache does not serve them.
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBPS = 8000.0
+MFMA_F16_PEAK_TFLOPS = 2500.0
+BYTES_PER_ELEM_QUANT = 2 + 0.5 + 0.0625      # bf16 in, packed FP4 + E4M3 scale out
+BYTES_PER_ELEM_ABSMAX = 2.0                  # bf16 in
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--quant-rows", type=int, default=8192)
+    ap.add_argument("--quant-cols", type=int, default=8192)
+    ap.add_argument("--tokens", type=int, default=16384)
+    ap.add_argument("--d-in", type=int, default=2048)
+    ap.add_argument("--d-out", type=int, default=8192)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2601_22813_amd import binding as qii
+    from paper_2601_22813_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    qii.lib()  # fail loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    def to_dev(bits: np.ndarray) -> torch.Tensor:
+        return torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+
+    # ------------------------------------------------------------------ part A buffers
+    R, C = args.quant_rows, args.quant_cols
+    x_np = synth.student_t_bf16((R, C), 3, 0.1, seed=1)
+    n_rot = max(2, int(np.ceil(768 * 2 ** 20 / (R * C * 2))))
+    xs = [to_dev(x_np)]
+    for i in range(1, n_rot):
+        xs.append(torch.roll(xs[0], shifts=17 * i, dims=0).contiguous())
+    out_rows = qii.NVFP4Tensor.empty(R, C)
+    out_cols = qii.NVFP4Tensor.empty(C, R)
+    amax = torch.zeros(1, dtype=torch.float32, device=dev)
+
+    # ------------------------------------------------------------------ part B buffers
+    T, d_in, d_out = args.tokens, args.d_in, args.d_out
+    X_np, W_np, E_np = synth.linear_layer_bf16(T, d_in, d_out, seed=2)
+    Xs, Ws, Es = [to_dev(X_np)], [to_dev(W_np)], [to_dev(E_np)]
+    for i in range(1, 3):
+        Xs.append(torch.roll(Xs[0], 5 * i, 0).contiguous())
+        Ws.append(torch.roll(Ws[0], 5 * i, 0).contiguous())
+        Es.append(torch.roll(Es[0], 5 * i, 0).contiguous())
+    Xq, Wq = qii.NVFP4Tensor.empty(T, d_in), qii.NVFP4Tensor.empty(d_out, d_in)
+    Y = torch.empty((T, d_out), dtype=torch.bfloat16, device=dev)
+    dX = torch.empty((T, d_in), dtype=torch.bfloat16, device=dev)
+    dW = torch.empty((d_out, d_in), dtype=torch.bfloat16, device=dev)
+    ws_f = torch.empty(qii.qii_linear_fwd_workspace_bytes(T, d_in, d_out), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(qii.qii_linear_bwd_workspace_bytes(T, d_in, d_out), dtype=torch.uint8, device=dev)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    kernel_ms = {"absmax_rows": [], "quant_rows": [], "absmax_cols": [], "quant_cols": [],
+                 "part_a": [], "linear_fwd": [], "linear_bwd": []}
+
+    def step(i: int, record: bool):
+        x = xs[i % n_rot]
+        e = [ev() for _ in range(8)]
+        e[0].record()
+        qii.qii_absmax(x, False, 128, 0, amax)
+        e[1].record()
+        qii.qii_quantize_nvfp4(x, False, qii.MS_EDEN, 128, 0, i, amax, out_rows, None)
+        e[2].record()
+        qii.qii_absmax(x, True, 128, 0, amax)
+        e[3].record()
+        qii.qii_quantize_nvfp4(x, True, qii.MS_EDEN, 128, 0, i, amax, out_cols, None)
+        e[4].record()
+        j = i % 3
+        qii.qii_linear_fwd(Xs[j], Ws[j], Y, Xq, Wq, ws_f)
+        e[5].record()
+        qii.qii_linear_bwd(Es[j], Xq, Wq, i, dX, dW, ws_b)
+        e[6].record()
+        return e if record else None
+
+    for i in range(args.warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    events = [step(args.warmup + i, True) for i in range(args.steps)]
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for e in events:
+        kernel_ms["absmax_rows"].append(e[0].elapsed_time(e[1]))
+        kernel_ms["quant_rows"].append(e[1].elapsed_time(e[2]))
+        kernel_ms["absmax_cols"].append(e[2].elapsed_time(e[3]))
+        kernel_ms["quant_cols"].append(e[3].elapsed_time(e[4]))
+        kernel_ms["part_a"].append(e[0].elapsed_time(e[4]))
+        kernel_ms["linear_fwd"].append(e[4].elapsed_time(e[5]))
+        kernel_ms["linear_bwd"].append(e[5].elapsed_time(e[6]))
+    avg = {k: float(np.mean(v)) for k, v in kernel_ms.items()}
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    n = R * C
+    bytes_part_a = 2 * n * (BYTES_PER_ELEM_ABSMAX + BYTES_PER_ELEM_QUANT)
+    value = bytes_part_a / (avg["part_a"] * 1e-3) / 1e9
+    quant_kernel_gbps = n * BYTES_PER_ELEM_QUANT / (avg["quant_rows"] * 1e-3) / 1e9
+    flops = 3 * 2.0 * T * d_in * d_out
+    lin_ms = avg["linear_fwd"] + avg["linear_bwd"]
+    tflops = flops / (lin_ms * 1e-3) / 1e12
+
+    result = {
+        "metric": "MS-EDEN quantize HBM GB/s; NVFP4 linear fwd+bwd TFLOP/s (% of MFMA peak)",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {
+            "workload": f"MS-EDEN quantize of {R}x{C} bf16 0.1*Student-t(3), RHT-128, blocks along "
+                        f"rows then columns, abs-max pass + quantize pass each "
+                        f"(value); plus linear fwd+bwd T={T} d_in={d_in} d_out={d_out} bf16 (linear_fwd_bwd)",
+            "quantize_bytes_per_element": {"absmax_pass": BYTES_PER_ELEM_ABSMAX, "quantize_pass": BYTES_PER_ELEM_QUANT},
+            "rotating_input_buffers": n_rot,
+        },
+        "quantize": {
+            "absmax_rows_ms": round(avg["absmax_rows"], 4), "quantize_rows_ms": round(avg["quant_rows"], 4),
+            "absmax_cols_ms": round(avg["absmax_cols"], 4), "quantize_cols_ms": round(avg["quant_cols"], 4),
+            "quantize_rows_single_pass_GBps": round(quant_kernel_gbps, 1),
+            "quantize_cols_single_pass_GBps": round(n * BYTES_PER_ELEM_QUANT / (avg["quant_cols"] * 1e-3) / 1e9, 1),
+        },
+        "linear_fwd_bwd": {
+            "value": round(tflops, 1), "unit": "TFLOP/s", "ms": round(lin_ms, 4),
+            "fwd_ms": round(avg["linear_fwd"], 4), "bwd_ms": round(avg["linear_bwd"], 4),
+            "flop": flops, "mfma": "v_mfma_f32_32x32x16_f16", "peak_TFLOPs": MFMA_F16_PEAK_TFLOPS,
+            "frac_of_peak": round(tflops / MFMA_F16_PEAK_TFLOPS, 4),
+            "paper_context": "up to 4.2x over BF16 on Blackwell (abstract); another machine, not a target",
+        },
+        "roofline": {
+            "kernel": "quantize_kernel<bf16 rows, MS_EDEN, RHT> (amax supplied)",
+            "bound": "hbm",
+            "achieved": round(quant_kernel_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(quant_kernel_gbps / HBM_PEAK_GBPS, 4),
+            "traffic": None,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        t0 = time.perf_counter()
+        for transpose in (False, True):
+            oracle.quantize(x_np, oracle.MS_EDEN, transpose=transpose, seed_rht=0, seed_sr=0)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {
+            "value": round(bytes_part_a / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.max_threads(),
+            "kind": "oracle",
+            "sample": f"the whole part-A workload once ({R}x{C}, rows then columns, abs-max + quantize), "
+                      f"{dt:.2f} s of wall time",
+        }
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

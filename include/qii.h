@@ -1,0 +1,165 @@
+/*
+ * qii.h -- C ABI of libqii: the NVFP4-quantized linear layer of Quartet II on one
+ * AMD MI355X (gfx950).
+ *
+ * Conventions shared by every entry point
+ *   - All data pointers are DEVICE pointers (HBM) unless a comment says "host".  The
+ *     caller owns every buffer, including the workspace; the library never allocates,
+ *     frees or synchronises.  Kernels are enqueued on `stream` (a hipStream_t passed
+ *     as void*; NULL = the default stream); outputs are valid once the stream reaches
+ *     that point.  Scalars that the device produces (tensor scale, amax) stay on the
+ *     device as float*.
+ *   - Every function returns a qii_status.  On any status other than QII_OK nothing
+ *     has been enqueued.  qii_last_error() (host string, thread local) explains the
+ *     last failure.  Nothing throws, aborts or prints.
+ *   - Matrices are row-major.  An NVFP4 tensor (Sec. 3.1 of the paper: FP4 E2M1
+ *     elements, one FP8 E4M3 scale per 16 consecutive elements of a row, one FP32
+ *     scale per tensor) is described by qii_nvfp4.  Its value is
+ *         x_hat[r][c] = e2m1(codes[r][c]) * e4m3(scales[r][c/16]) * tensor_scale.
+ *   - Randomness (omega_RHT, omega_SR of Algorithm 1) is counter based: outputs are a
+ *     pure function of the seeds and the element / group index, never of the launch
+ *     geometry.  Generator: Philox4x32-10 keyed by the 64-bit seed.
+ *       rotation signs : counter (0, 0, 0, 0x52485400); sign j = bit (j mod 32) of
+ *                        word (j div 32); a set bit means -1.
+ *       scale rounding : group (row, cg) of the OUTPUT tensor uses counter
+ *                        (cg, row div 4, 0, 0x53434C00), word (row mod 4), top 20 bits.
+ *       element rounding (mode SR): element (row, col) uses counter
+ *                        (col div 8, row, 0, 0x454C4D00), word ((col mod 8) div 2),
+ *                        low 16 bits for even col, high 16 bits for odd col.
+ *       backward sub-seed i : counter (i, 0, 0, 0x44525600), words 0 (low) and 1 (high).
+ *   - Inputs must be finite.  An all-zero tensor quantizes to all-zero bytes with
+ *     tensor_scale = 1.
+ */
+#ifndef QII_H
+#define QII_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QII_OK = 0,
+    QII_INVALID_ARG = 1,         /* null pointer, bad enum, misaligned buffer          */
+    QII_BAD_SHAPE = 2,           /* a dimension violates the divisibility rules below   */
+    QII_UNSUPPORTED = 3,         /* combination not implemented                         */
+    QII_WORKSPACE_TOO_SMALL = 4, /* ws_bytes below the matching *_workspace_bytes query */
+    QII_HIP_ERROR = 5            /* a launch failed; text in qii_last_error()           */
+} qii_status;
+
+/* Rounding scheme of the quantizer.
+ *   QII_RTN     round to nearest, grid max 6, scale cap 448 (Table 1, row "RTN 1x16";
+ *               the forward pass of Sec. 5 without the 4/6 heuristic).
+ *   QII_SR      Q_SR of Sec. 3.1: grid max 6*16/17, cap 448, element-wise stochastic
+ *               rounding to FP4; never clips; unbiased.
+ *   QII_MS_EDEN Algorithm 1 (Sec. 3.3): Q_RTN(x, s) with s = 6*16/17/0.93 and cap 256,
+ *               then the per-16 EDEN factor merged into the E4M3 scale by stochastic
+ *               rounding; unbiased after the inverse rotation. */
+typedef enum { QII_RTN = 0, QII_SR = 1, QII_MS_EDEN = 2 } qii_mode;
+
+typedef enum { QII_F32 = 0, QII_BF16 = 1 } qii_dtype;
+
+/* One NVFP4 tensor of `rows` x `cols` (cols % 16 == 0).
+ *   codes        rows*cols/2 bytes; element 2j of a row in the low nibble of byte j,
+ *                element 2j+1 in the high nibble; 8-byte aligned.
+ *   scales       rows*cols/16 bytes, E4M3 (bias 7, no infinities, 0x7F never written),
+ *                plain row-major [rows][cols/16]; 4-byte aligned.
+ *   tensor_scale one float.                                                           */
+typedef struct {
+    uint8_t *codes;
+    uint8_t *scales;
+    float *tensor_scale;
+    int64_t rows;
+    int64_t cols;
+} qii_nvfp4;
+
+/* Randomized Hadamard transform of Algorithm 1 (first loop), as a stand-alone op:
+ *   y = RHT(x) or RHT(x^T), in f32, chunks of 128 along the rows of the logical
+ *   matrix: y = H (d .* v) / sqrt(128), H[i][j] = (-1)^popcount(i & j), d from seed_rht.
+ *   x: rows x cols, leading dimension ld (elements), dtype dt.  transpose != 0 works on
+ *   x^T (y is cols x rows, contiguous); the rotated dimension must be a multiple of 128.
+ *   amax (nullable): receives max |y| (Sec. 3.3, numerator of x^FP32).                */
+qii_status qii_rht(const void *x, qii_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                   int transpose, uint64_t seed_rht, float *y, float *amax, void *stream);
+
+/* max |RHT(x)| (or of x itself when rht_group == 0) into *amax: the global reduction
+ * that Sec. 7 ("Fused Re-Quantization Kernel") names as the barrier before any scale
+ * can be computed.  Same argument rules as qii_quantize_nvfp4.                        */
+qii_status qii_absmax(const void *x, qii_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                      int transpose, int rht_group, uint64_t seed_rht, float *amax, void *stream);
+
+/* Q(x) or Q(x^T) -> NVFP4 (Sec. 3.1 equations for QII_SR, Sec. 3.3 equations and
+ * Algorithm 1 for QII_MS_EDEN, Table 1 "RTN 1x16" for QII_RTN).
+ *   x          rows x cols, leading dimension ld >= cols (elements); with transpose == 0
+ *              every row must start 16-byte aligned.
+ *   transpose  0: quantize x, groups along cols;  out is rows x cols.
+ *              1: quantize x^T, groups along rows of x;  out is cols x rows.
+ *   rht_group  128: rotate chunks of 128 of the quantized dimension first (it must be
+ *              a multiple of 128); 0: no rotation (it must be a multiple of 16).
+ *   seed_rht, seed_sr  omega_RHT, omega_SR.  The output lives in ROTATED space and is
+ *              meaningful only against a tensor rotated with the same seed_rht on the
+ *              same inner dimension (the rotations cancel in the GEMM).
+ *   amax_in    nullable.  Non-null: device float holding max|.| of the rotated tensor,
+ *              supplied by the caller (App. D assumes this); the tensor is then read
+ *              once.  Null: the library measures it first (a second read of x) and
+ *              needs 256 bytes of workspace.
+ *   out        caller-allocated; out.rows/out.cols must equal the shape stated above. */
+qii_status qii_quantize_nvfp4(const void *x, qii_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                              int transpose, qii_mode mode, int rht_group, uint64_t seed_rht,
+                              uint64_t seed_sr, const float *amax_in, const qii_nvfp4 *out,
+                              void *ws, size_t ws_bytes, void *stream);
+
+/* Backward-pass re-quantization of a saved forward tensor (Sec. 5, "Backward Pass"):
+ * dequantize `in` ((code*scale)*tensor_scale in f32), optionally transpose, quantize
+ * as above.  in and out must not overlap.                                             */
+qii_status qii_requantize_nvfp4(const qii_nvfp4 *in, int transpose, qii_mode mode, int rht_group,
+                                uint64_t seed_rht, uint64_t seed_sr, const float *amax_in,
+                                const qii_nvfp4 *out, void *ws, size_t ws_bytes, void *stream);
+
+/* y[r][c] = (e2m1 * e4m3) * tensor_scale as f32, rows x cols contiguous.              */
+qii_status qii_dequantize_nvfp4(const qii_nvfp4 *in, float *y, void *stream);
+
+/* Block-scaled GEMM of Sec. 5:  C = A_hat * B_hat^T  with A (M x K) and B (N x K) both
+ * K-contiguous NVFP4, products accumulated in f32.  C is M x N, leading dimension ldc,
+ * dtype QII_F32 or QII_BF16 (rounded to nearest even from the f32 accumulator).
+ * K = A.cols = B.cols must be a multiple of 32.                                        */
+qii_status qii_gemm_nvfp4(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_dtype c_dt,
+                          int64_t ldc, void *ws, size_t ws_bytes, void *stream);
+
+/* Forward pass of one linear layer (Sec. 5): Xq = RTN(X) and Wq = RTN(W) with 1x16
+ * scales along d_in and no rotation, Y = Xq * Wq^T.  X is T x d_in, W is d_out x d_in,
+ * Y is T x d_out (contiguous, dtype y_dt).  Xq_saved (T x d_in) and Wq_saved
+ * (d_out x d_in) are caller-allocated and are the state kept for the backward pass.   */
+qii_status qii_linear_fwd(const void *X, const void *W, qii_dtype dt, int64_t T, int64_t d_in,
+                          int64_t d_out, void *Y, qii_dtype y_dt, const qii_nvfp4 *Xq_saved,
+                          const qii_nvfp4 *Wq_saved, void *ws, size_t ws_bytes, void *stream);
+
+/* Backward pass of one linear layer (Sec. 5): with six sub-seeds derived from `seed`
+ * (0: rotation of the dX GEMM, 1: rotation of the dW GEMM, 2..5: rounding seeds of
+ * Q(E), Q(W^T), Q(E^T), Q(X^T)), all quantizers MS-EDEN:
+ *   dX = Q(E) * Q(W^T)^T   (T x d_in,    inner dimension d_out)
+ *   dW = Q(E^T) * Q(X^T)^T (d_out x d_in, inner dimension T)
+ * dY is T x d_out (dtype dt).  T and d_out must be multiples of 128.
+ * dX, dW contiguous, dtype g_dt.                                                       */
+qii_status qii_linear_bwd(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq_saved,
+                          const qii_nvfp4 *Wq_saved, uint64_t seed, void *dX, void *dW,
+                          qii_dtype g_dt, void *ws, size_t ws_bytes, void *stream);
+
+/* Workspace sizes in bytes (host computations, no device work).                       */
+size_t qii_quantize_workspace_bytes(void);
+size_t qii_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+size_t qii_linear_fwd_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out);
+size_t qii_linear_bwd_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out);
+
+/* Host helpers.                                                                        */
+uint64_t qii_derive_seed(uint64_t seed, uint32_t i); /* backward sub-seed i (0..5)      */
+const char *qii_status_string(qii_status s);
+const char *qii_last_error(void);
+int qii_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QII_H */

@@ -1,0 +1,202 @@
+"""Thin ctypes binding of libqii (the C ABI declared in include/qii.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.  torch is
+used for device memory and the current stream, nothing else.  Importing works without
+the built library; the first call raises if ``libqii.so`` is missing (there is no CPU
+fallback).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqii.so")
+
+RTN, SR, MS_EDEN = 0, 1, 2
+F32, BF16 = 0, 1
+
+EXPORTS = [
+    "qii_rht", "qii_absmax", "qii_quantize_nvfp4", "qii_requantize_nvfp4", "qii_dequantize_nvfp4",
+    "qii_gemm_nvfp4", "qii_linear_fwd", "qii_linear_bwd", "qii_quantize_workspace_bytes",
+    "qii_gemm_workspace_bytes", "qii_linear_fwd_workspace_bytes", "qii_linear_bwd_workspace_bytes",
+    "qii_derive_seed", "qii_status_string", "qii_last_error", "qii_version",
+]
+
+
+class _NVFP4(ctypes.Structure):
+    _fields_ = [("codes", ctypes.c_void_p), ("scales", ctypes.c_void_p),
+                ("tensor_scale", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64)]
+
+
+class QiiError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise QiiError(f"{LIB_PATH} is not built: run `python -m paper_2601_22813_amd.build` "
+                           "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        c = ctypes
+        vp, i64, u64, sz = c.c_void_p, c.c_int64, c.c_uint64, c.c_size_t
+        nv = c.POINTER(_NVFP4)
+        L.qii_rht.argtypes = [vp, c.c_int, i64, i64, i64, c.c_int, u64, vp, vp, vp]
+        L.qii_absmax.argtypes = [vp, c.c_int, i64, i64, i64, c.c_int, c.c_int, u64, vp, vp]
+        L.qii_quantize_nvfp4.argtypes = [vp, c.c_int, i64, i64, i64, c.c_int, c.c_int, c.c_int, u64,
+                                         u64, vp, nv, vp, sz, vp]
+        L.qii_requantize_nvfp4.argtypes = [nv, c.c_int, c.c_int, c.c_int, u64, u64, vp, nv, vp, sz, vp]
+        L.qii_dequantize_nvfp4.argtypes = [nv, vp, vp]
+        L.qii_gemm_nvfp4.argtypes = [nv, nv, vp, c.c_int, i64, vp, sz, vp]
+        L.qii_linear_fwd.argtypes = [vp, vp, c.c_int, i64, i64, i64, vp, c.c_int, nv, nv, vp, sz, vp]
+        L.qii_linear_bwd.argtypes = [vp, c.c_int, nv, nv, u64, vp, vp, c.c_int, vp, sz, vp]
+        for name in ("qii_rht", "qii_absmax", "qii_quantize_nvfp4", "qii_requantize_nvfp4",
+                     "qii_dequantize_nvfp4", "qii_gemm_nvfp4", "qii_linear_fwd", "qii_linear_bwd"):
+            getattr(L, name).restype = c.c_int
+        L.qii_quantize_workspace_bytes.argtypes = []
+        L.qii_quantize_workspace_bytes.restype = sz
+        for name in ("qii_gemm_workspace_bytes", "qii_linear_fwd_workspace_bytes",
+                     "qii_linear_bwd_workspace_bytes"):
+            getattr(L, name).argtypes = [i64, i64, i64]
+            getattr(L, name).restype = sz
+        L.qii_derive_seed.argtypes = [u64, c.c_uint32]
+        L.qii_derive_seed.restype = u64
+        L.qii_status_string.argtypes = [c.c_int]
+        L.qii_status_string.restype = c.c_char_p
+        L.qii_last_error.argtypes = []
+        L.qii_last_error.restype = c.c_char_p
+        L.qii_version.argtypes = []
+        L.qii_version.restype = c.c_int
+        _lib = L
+    return _lib
+
+
+def _check(status: int):
+    if status != 0:
+        L = lib()
+        raise QiiError(f"{L.qii_status_string(status).decode()}: {L.qii_last_error().decode()}")
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+@dataclass
+class NVFP4Tensor:
+    """Device buffers of one NVFP4 tensor (caller-owned, see qii_nvfp4 in include/qii.h)."""
+    codes: torch.Tensor         # uint8 [rows, cols // 2]
+    scales: torch.Tensor        # uint8 [rows, cols // 16]
+    tensor_scale: torch.Tensor  # float32 [1]
+    rows: int
+    cols: int
+
+    @staticmethod
+    def empty(rows: int, cols: int, device="cuda") -> "NVFP4Tensor":
+        return NVFP4Tensor(torch.empty((rows, cols // 2), dtype=torch.uint8, device=device),
+                           torch.empty((rows, cols // 16), dtype=torch.uint8, device=device),
+                           torch.empty(1, dtype=torch.float32, device=device), rows, cols)
+
+    def c_struct(self) -> _NVFP4:
+        return _NVFP4(self.codes.data_ptr(), self.scales.data_ptr(), self.tensor_scale.data_ptr(),
+                      self.rows, self.cols)
+
+
+def qii_version() -> int:
+    return lib().qii_version()
+
+
+def qii_derive_seed(seed: int, i: int) -> int:
+    return int(lib().qii_derive_seed(seed, i))
+
+
+def qii_quantize_workspace_bytes() -> int:
+    return int(lib().qii_quantize_workspace_bytes())
+
+
+def qii_linear_fwd_workspace_bytes(T: int, d_in: int, d_out: int) -> int:
+    return int(lib().qii_linear_fwd_workspace_bytes(T, d_in, d_out))
+
+
+def qii_linear_bwd_workspace_bytes(T: int, d_in: int, d_out: int) -> int:
+    return int(lib().qii_linear_bwd_workspace_bytes(T, d_in, d_out))
+
+
+def qii_rht(x: torch.Tensor, transpose: bool, seed_rht: int, y: torch.Tensor, amax: torch.Tensor | None):
+    rows, cols = x.shape
+    _check(lib().qii_rht(x.data_ptr(), _dt(x), rows, cols, x.stride(0), int(transpose), seed_rht,
+                         y.data_ptr(), _ptr(amax), _stream()))
+
+
+def qii_absmax(x: torch.Tensor, transpose: bool, rht_group: int, seed_rht: int, amax: torch.Tensor):
+    rows, cols = x.shape
+    _check(lib().qii_absmax(x.data_ptr(), _dt(x), rows, cols, x.stride(0), int(transpose), rht_group,
+                            seed_rht, amax.data_ptr(), _stream()))
+
+
+def qii_quantize_nvfp4(x: torch.Tensor, transpose: bool, mode: int, rht_group: int, seed_rht: int,
+                       seed_sr: int, amax_in: torch.Tensor | None, out: NVFP4Tensor,
+                       ws: torch.Tensor | None):
+    rows, cols = x.shape
+    s = out.c_struct()
+    _check(lib().qii_quantize_nvfp4(x.data_ptr(), _dt(x), rows, cols, x.stride(0), int(transpose), mode,
+                                    rht_group, seed_rht, seed_sr, _ptr(amax_in), ctypes.byref(s),
+                                    _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                                    _stream()))
+
+
+def qii_requantize_nvfp4(inp: NVFP4Tensor, transpose: bool, mode: int, rht_group: int, seed_rht: int,
+                         seed_sr: int, amax_in: torch.Tensor | None, out: NVFP4Tensor,
+                         ws: torch.Tensor | None):
+    si, so = inp.c_struct(), out.c_struct()
+    _check(lib().qii_requantize_nvfp4(ctypes.byref(si), int(transpose), mode, rht_group, seed_rht,
+                                      seed_sr, _ptr(amax_in), ctypes.byref(so), _ptr(ws),
+                                      0 if ws is None else ws.numel() * ws.element_size(), _stream()))
+
+
+def qii_dequantize_nvfp4(inp: NVFP4Tensor, y: torch.Tensor):
+    si = inp.c_struct()
+    _check(lib().qii_dequantize_nvfp4(ctypes.byref(si), y.data_ptr(), _stream()))
+
+
+def qii_gemm_nvfp4(A: NVFP4Tensor, B: NVFP4Tensor, C: torch.Tensor):
+    sa, sb = A.c_struct(), B.c_struct()
+    _check(lib().qii_gemm_nvfp4(ctypes.byref(sa), ctypes.byref(sb), C.data_ptr(), _dt(C), C.stride(0),
+                                None, 0, _stream()))
+
+
+def qii_linear_fwd(X: torch.Tensor, W: torch.Tensor, Y: torch.Tensor, Xq: NVFP4Tensor,
+                   Wq: NVFP4Tensor, ws: torch.Tensor):
+    T, d_in = X.shape
+    d_out = W.shape[0]
+    sx, sw = Xq.c_struct(), Wq.c_struct()
+    _check(lib().qii_linear_fwd(X.data_ptr(), W.data_ptr(), _dt(X), T, d_in, d_out, Y.data_ptr(), _dt(Y),
+                                ctypes.byref(sx), ctypes.byref(sw), ws.data_ptr(),
+                                ws.numel() * ws.element_size(), _stream()))
+
+
+def qii_linear_bwd(dY: torch.Tensor, Xq: NVFP4Tensor, Wq: NVFP4Tensor, seed: int, dX: torch.Tensor,
+                   dW: torch.Tensor, ws: torch.Tensor):
+    sx, sw = Xq.c_struct(), Wq.c_struct()
+    _check(lib().qii_linear_bwd(dY.data_ptr(), _dt(dY), ctypes.byref(sx), ctypes.byref(sw), seed,
+                                dX.data_ptr(), dW.data_ptr(), _dt(dX), ws.data_ptr(),
+                                ws.numel() * ws.element_size(), _stream()))

@@ -1,0 +1,338 @@
+// C ABI of libqii (see include/qii.h): argument validation, workspace carving and the
+// kernel sequences of the layer's forward and backward pass (paper Sec. 5).
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "qii_device.h"
+#include "qii_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+qii_status fail(qii_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+qii_status hip_fail(hipError_t e, const char *what)
+{
+    return fail(QII_HIP_ERROR, "%s: %s", what, hipGetErrorString(e));
+}
+
+constexpr size_t kSlot = 256;  // bytes reserved per device scalar in a workspace
+size_t align_up(size_t v) { return (v + kSlot - 1) / kSlot * kSlot; }
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+qii_status check_nvfp4(const qii_nvfp4 *t, const char *name)
+{
+    if (!t) return fail(QII_INVALID_ARG, "%s: null descriptor", name);
+    if (t->rows < 0 || t->cols < 0 || t->cols % 16 != 0)
+        return fail(QII_BAD_SHAPE, "%s: %lld x %lld (cols must be a multiple of 16)", name,
+                    (long long)t->rows, (long long)t->cols);
+    if (t->rows * t->cols > 0) {
+        if (!t->codes || !t->scales || !t->tensor_scale)
+            return fail(QII_INVALID_ARG, "%s: null buffer", name);
+        if (!aligned(t->codes, 8) || !aligned(t->scales, 4) || !aligned(t->tensor_scale, 4))
+            return fail(QII_INVALID_ARG, "%s: misaligned buffer (codes 8, scales 4, tensor_scale 4)", name);
+    }
+    return QII_OK;
+}
+
+// checks the dense source and fills a Source descriptor plus the logical shape
+qii_status dense_source(const void *x, qii_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                        int transpose, int rht_group, qii::Source *src, int64_t *R, int64_t *C)
+{
+    if (dt != QII_F32 && dt != QII_BF16) return fail(QII_INVALID_ARG, "bad dtype %d", (int)dt);
+    if (rows < 0 || cols < 0 || ld < cols) return fail(QII_BAD_SHAPE, "rows %lld cols %lld ld %lld", (long long)rows, (long long)cols, (long long)ld);
+    if (rht_group != 0 && rht_group != 128) return fail(QII_INVALID_ARG, "rht_group must be 0 or 128");
+    *R = transpose ? cols : rows;
+    *C = transpose ? rows : cols;
+    const int64_t need = rht_group == 128 ? 128 : 16;
+    if (*C % need != 0)
+        return fail(QII_BAD_SHAPE, "quantized dimension %lld is not a multiple of %lld", (long long)*C, (long long)need);
+    if (rows * cols > 0) {
+        if (!x) return fail(QII_INVALID_ARG, "null input");
+        const size_t esz = dt == QII_F32 ? 4 : 2;
+        if (!aligned(x, esz)) return fail(QII_INVALID_ARG, "misaligned input");
+        if (!transpose && (!aligned(x, 16) || (ld * esz) % 16 != 0))
+            return fail(QII_INVALID_ARG, "input rows must be 16-byte aligned");
+    }
+    src->kind = dt == QII_F32 ? qii::kSrcF32 : qii::kSrcBF16;
+    src->transpose = transpose ? 1 : 0;
+    src->x = x;
+    src->scales = nullptr;
+    src->ts = nullptr;
+    src->ld = ld;
+    return QII_OK;
+}
+
+qii_status nvfp4_source(const qii_nvfp4 *in, int transpose, int rht_group, qii::Source *src,
+                        int64_t *R, int64_t *C)
+{
+    qii_status st = check_nvfp4(in, "in");
+    if (st != QII_OK) return st;
+    if (rht_group != 0 && rht_group != 128) return fail(QII_INVALID_ARG, "rht_group must be 0 or 128");
+    *R = transpose ? in->cols : in->rows;
+    *C = transpose ? in->rows : in->cols;
+    const int64_t need = rht_group == 128 ? 128 : 16;
+    if (*C % need != 0)
+        return fail(QII_BAD_SHAPE, "quantized dimension %lld is not a multiple of %lld", (long long)*C, (long long)need);
+    src->kind = qii::kSrcNVFP4;
+    src->transpose = transpose ? 1 : 0;
+    src->x = in->codes;
+    src->scales = in->scales;
+    src->ts = in->tensor_scale;
+    src->ld = in->cols;
+    return QII_OK;
+}
+
+// measure (if needed) and quantize one logical R x C source
+qii_status quantize_source(const qii::Source &src, int64_t R, int64_t C, qii_mode mode, int rht_group,
+                           uint64_t seed_rht, uint64_t seed_sr, const float *amax_in,
+                           const qii_nvfp4 *out, float *amax_slot, hipStream_t s)
+{
+    if (mode != QII_RTN && mode != QII_SR && mode != QII_MS_EDEN) return fail(QII_INVALID_ARG, "bad mode %d", (int)mode);
+    qii_status st = check_nvfp4(out, "out");
+    if (st != QII_OK) return st;
+    if (out->rows != R || out->cols != C)
+        return fail(QII_BAD_SHAPE, "out is %lld x %lld, expected %lld x %lld", (long long)out->rows,
+                    (long long)out->cols, (long long)R, (long long)C);
+    if (R * C == 0) return QII_OK;
+    const float *amax = amax_in;
+    if (!amax) {
+        if (!amax_slot) return fail(QII_WORKSPACE_TOO_SMALL, "workspace needed to measure the abs-max");
+        hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(amax_slot), 0u, s);
+        if (e != hipSuccess) return hip_fail(e, "fill");
+        e = qii::launch_absmax(src, R, C, rht_group == 128, seed_rht, amax_slot, s);
+        if (e != hipSuccess) return hip_fail(e, "absmax");
+        amax = amax_slot;
+    }
+    qii::QuantizeArgs a;
+    a.src = src; a.R = R; a.C = C; a.mode = (int)mode; a.rht = rht_group == 128;
+    a.seed_rht = seed_rht; a.seed_sr = seed_sr; a.amax = amax;
+    a.codes = out->codes; a.scales = out->scales; a.tensor_scale = out->tensor_scale;
+    hipError_t e = qii::launch_quantize(a, s);
+    if (e != hipSuccess) return hip_fail(e, "quantize");
+    return QII_OK;
+}
+
+size_t nvfp4_bytes(int64_t rows, int64_t cols)
+{
+    return align_up((size_t)(rows * cols / 2)) + align_up((size_t)(rows * cols / 16)) + kSlot;
+}
+
+qii_nvfp4 carve_nvfp4(uint8_t *&p, int64_t rows, int64_t cols)
+{
+    qii_nvfp4 t;
+    t.codes = p; p += align_up((size_t)(rows * cols / 2));
+    t.scales = p; p += align_up((size_t)(rows * cols / 16));
+    t.tensor_scale = reinterpret_cast<float *>(p); p += kSlot;
+    t.rows = rows; t.cols = cols;
+    return t;
+}
+
+}  // namespace
+
+extern "C" {
+
+int qii_version(void) { return 1; }
+
+const char *qii_last_error(void) { return g_err; }
+
+const char *qii_status_string(qii_status s)
+{
+    switch (s) {
+        case QII_OK: return "QII_OK";
+        case QII_INVALID_ARG: return "QII_INVALID_ARG";
+        case QII_BAD_SHAPE: return "QII_BAD_SHAPE";
+        case QII_UNSUPPORTED: return "QII_UNSUPPORTED";
+        case QII_WORKSPACE_TOO_SMALL: return "QII_WORKSPACE_TOO_SMALL";
+        case QII_HIP_ERROR: return "QII_HIP_ERROR";
+    }
+    return "QII_UNKNOWN";
+}
+
+uint64_t qii_derive_seed(uint64_t seed, uint32_t i)
+{
+    const qii::U4 w = qii::philox_seeded(seed, i, 0, 0, qii::kStreamDerive);
+    return ((uint64_t)w.y << 32) | w.x;
+}
+
+size_t qii_quantize_workspace_bytes(void) { return kSlot; }
+
+size_t qii_gemm_workspace_bytes(int64_t, int64_t, int64_t) { return 0; }
+
+size_t qii_linear_fwd_workspace_bytes(int64_t, int64_t, int64_t) { return 2 * kSlot; }
+
+size_t qii_linear_bwd_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out)
+{
+    return 4 * kSlot + nvfp4_bytes(T, d_out) + nvfp4_bytes(d_in, d_out) + nvfp4_bytes(d_out, T) +
+           nvfp4_bytes(d_in, T);
+}
+
+qii_status qii_rht(const void *x, qii_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                   int transpose, uint64_t seed_rht, float *y, float *amax, void *stream)
+{
+    qii::Source src;
+    int64_t R, C;
+    qii_status st = dense_source(x, dt, rows, cols, ld, transpose, 128, &src, &R, &C);
+    if (st != QII_OK) return st;
+    if (R * C == 0) return QII_OK;
+    if (!y || !aligned(y, 16)) return fail(QII_INVALID_ARG, "y must be non-null and 16-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    if (amax) {
+        hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(amax), 0u, s);
+        if (e != hipSuccess) return hip_fail(e, "fill");
+    }
+    hipError_t e = qii::launch_rht(src, R, C, seed_rht, y, amax, s);
+    if (e != hipSuccess) return hip_fail(e, "rht");
+    return QII_OK;
+}
+
+qii_status qii_absmax(const void *x, qii_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                      int transpose, int rht_group, uint64_t seed_rht, float *amax, void *stream)
+{
+    qii::Source src;
+    int64_t R, C;
+    qii_status st = dense_source(x, dt, rows, cols, ld, transpose, rht_group, &src, &R, &C);
+    if (st != QII_OK) return st;
+    if (!amax) return fail(QII_INVALID_ARG, "null amax");
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(amax), 0u, s);
+    if (e != hipSuccess) return hip_fail(e, "fill");
+    e = qii::launch_absmax(src, R, C, rht_group == 128, seed_rht, amax, s);
+    if (e != hipSuccess) return hip_fail(e, "absmax");
+    return QII_OK;
+}
+
+qii_status qii_quantize_nvfp4(const void *x, qii_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                              int transpose, qii_mode mode, int rht_group, uint64_t seed_rht,
+                              uint64_t seed_sr, const float *amax_in, const qii_nvfp4 *out,
+                              void *ws, size_t ws_bytes, void *stream)
+{
+    qii::Source src;
+    int64_t R, C;
+    qii_status st = dense_source(x, dt, rows, cols, ld, transpose, rht_group, &src, &R, &C);
+    if (st != QII_OK) return st;
+    float *slot = nullptr;
+    if (!amax_in) {
+        if (!ws || ws_bytes < kSlot || !aligned(ws, 4))
+            return fail(QII_WORKSPACE_TOO_SMALL, "need %zu bytes of workspace without amax_in", kSlot);
+        slot = reinterpret_cast<float *>(ws);
+    }
+    return quantize_source(src, R, C, mode, rht_group, seed_rht, seed_sr, amax_in, out, slot,
+                           (hipStream_t)stream);
+}
+
+qii_status qii_requantize_nvfp4(const qii_nvfp4 *in, int transpose, qii_mode mode, int rht_group,
+                                uint64_t seed_rht, uint64_t seed_sr, const float *amax_in,
+                                const qii_nvfp4 *out, void *ws, size_t ws_bytes, void *stream)
+{
+    qii::Source src;
+    int64_t R, C;
+    qii_status st = nvfp4_source(in, transpose, rht_group, &src, &R, &C);
+    if (st != QII_OK) return st;
+    float *slot = nullptr;
+    if (!amax_in) {
+        if (!ws || ws_bytes < kSlot || !aligned(ws, 4))
+            return fail(QII_WORKSPACE_TOO_SMALL, "need %zu bytes of workspace without amax_in", kSlot);
+        slot = reinterpret_cast<float *>(ws);
+    }
+    return quantize_source(src, R, C, mode, rht_group, seed_rht, seed_sr, amax_in, out, slot,
+                           (hipStream_t)stream);
+}
+
+qii_status qii_dequantize_nvfp4(const qii_nvfp4 *in, float *y, void *stream)
+{
+    qii_status st = check_nvfp4(in, "in");
+    if (st != QII_OK) return st;
+    if (in->rows * in->cols == 0) return QII_OK;
+    if (!y || !aligned(y, 16)) return fail(QII_INVALID_ARG, "y must be non-null and 16-byte aligned");
+    hipError_t e = qii::launch_dequantize(in->codes, in->scales, in->tensor_scale, in->rows, in->cols,
+                                          y, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, "dequantize");
+    return QII_OK;
+}
+
+qii_status qii_gemm_nvfp4(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_dtype c_dt,
+                          int64_t ldc, void *, size_t, void *stream)
+{
+    qii_status st = check_nvfp4(A, "A");
+    if (st != QII_OK) return st;
+    st = check_nvfp4(B, "B");
+    if (st != QII_OK) return st;
+    if (A->cols != B->cols) return fail(QII_BAD_SHAPE, "inner dimensions differ: %lld vs %lld", (long long)A->cols, (long long)B->cols);
+    if (A->cols % 32 != 0) return fail(QII_BAD_SHAPE, "K = %lld must be a multiple of 32", (long long)A->cols);
+    if (c_dt != QII_F32 && c_dt != QII_BF16) return fail(QII_INVALID_ARG, "bad output dtype");
+    if (ldc < B->rows) return fail(QII_BAD_SHAPE, "ldc %lld < N %lld", (long long)ldc, (long long)B->rows);
+    if (A->rows * B->rows == 0) return QII_OK;
+    if (!C) return fail(QII_INVALID_ARG, "null C");
+    if (A->cols == 0) return fail(QII_BAD_SHAPE, "K = 0");
+    if (!aligned(A->codes, 16) || !aligned(B->codes, 16) || !aligned(A->scales, 8) || !aligned(B->scales, 8))
+        return fail(QII_INVALID_ARG, "GEMM operands need 16-byte aligned codes and 8-byte aligned scales");
+    hipError_t e = qii::launch_gemm(*A, *B, C, c_dt == QII_BF16, ldc, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, "gemm");
+    return QII_OK;
+}
+
+qii_status qii_linear_fwd(const void *X, const void *W, qii_dtype dt, int64_t T, int64_t d_in,
+                          int64_t d_out, void *Y, qii_dtype y_dt, const qii_nvfp4 *Xq,
+                          const qii_nvfp4 *Wq, void *ws, size_t ws_bytes, void *stream)
+{
+    if (d_in % 32 != 0) return fail(QII_BAD_SHAPE, "d_in must be a multiple of 32");
+    if (!ws || ws_bytes < qii_linear_fwd_workspace_bytes(T, d_in, d_out) || !aligned(ws, kSlot))
+        return fail(QII_WORKSPACE_TOO_SMALL, "linear_fwd needs %zu bytes of 256-byte aligned workspace",
+                    qii_linear_fwd_workspace_bytes(T, d_in, d_out));
+    uint8_t *p = reinterpret_cast<uint8_t *>(ws);
+    qii_status st = qii_quantize_nvfp4(X, dt, T, d_in, d_in, 0, QII_RTN, 0, 0, 0, nullptr, Xq, p, kSlot, stream);
+    if (st != QII_OK) return st;
+    st = qii_quantize_nvfp4(W, dt, d_out, d_in, d_in, 0, QII_RTN, 0, 0, 0, nullptr, Wq, p + kSlot, kSlot, stream);
+    if (st != QII_OK) return st;
+    return qii_gemm_nvfp4(Xq, Wq, Y, y_dt, d_out, nullptr, 0, stream);
+}
+
+qii_status qii_linear_bwd(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq, const qii_nvfp4 *Wq,
+                          uint64_t seed, void *dX, void *dW, qii_dtype g_dt, void *ws,
+                          size_t ws_bytes, void *stream)
+{
+    qii_status st = check_nvfp4(Xq, "Xq_saved");
+    if (st != QII_OK) return st;
+    st = check_nvfp4(Wq, "Wq_saved");
+    if (st != QII_OK) return st;
+    const int64_t T = Xq->rows, d_in = Xq->cols, d_out = Wq->rows;
+    if (Wq->cols != d_in) return fail(QII_BAD_SHAPE, "Xq is %lld x %lld but Wq is %lld x %lld", (long long)T, (long long)d_in, (long long)d_out, (long long)Wq->cols);
+    if (T % 128 != 0 || d_out % 128 != 0) return fail(QII_BAD_SHAPE, "T and d_out must be multiples of 128");
+    const size_t need = qii_linear_bwd_workspace_bytes(T, d_in, d_out);
+    if (!ws || ws_bytes < need || !aligned(ws, kSlot))
+        return fail(QII_WORKSPACE_TOO_SMALL, "linear_bwd needs %zu bytes of 256-byte aligned workspace", need);
+    uint8_t *p = reinterpret_cast<uint8_t *>(ws);
+    float *slots = reinterpret_cast<float *>(p);
+    p += 4 * kSlot;
+    qii_nvfp4 Eq = carve_nvfp4(p, T, d_out);
+    qii_nvfp4 WTq = carve_nvfp4(p, d_in, d_out);
+    qii_nvfp4 ETq = carve_nvfp4(p, d_out, T);
+    qii_nvfp4 XTq = carve_nvfp4(p, d_in, T);
+    uint64_t sd[6];
+    for (uint32_t i = 0; i < 6; ++i) sd[i] = qii_derive_seed(seed, i);
+    const size_t slot_floats = kSlot / sizeof(float);
+    // dX = Q(E) Q(W^T)^T : rotation sd[0] on the inner dimension d_out
+    st = qii_quantize_nvfp4(dY, dt, T, d_out, d_out, 0, QII_MS_EDEN, 128, sd[0], sd[2], nullptr, &Eq, slots, kSlot, stream);
+    if (st != QII_OK) return st;
+    st = qii_requantize_nvfp4(Wq, 1, QII_MS_EDEN, 128, sd[0], sd[3], nullptr, &WTq, slots + slot_floats, kSlot, stream);
+    if (st != QII_OK) return st;
+    st = qii_gemm_nvfp4(&Eq, &WTq, dX, g_dt, d_in, nullptr, 0, stream);
+    if (st != QII_OK) return st;
+    // dW = Q(E^T) Q(X^T)^T : rotation sd[1] on the inner dimension T
+    st = qii_quantize_nvfp4(dY, dt, T, d_out, d_out, 1, QII_MS_EDEN, 128, sd[1], sd[4], nullptr, &ETq, slots + 2 * slot_floats, kSlot, stream);
+    if (st != QII_OK) return st;
+    st = qii_requantize_nvfp4(Xq, 1, QII_MS_EDEN, 128, sd[1], sd[5], nullptr, &XTq, slots + 3 * slot_floats, kSlot, stream);
+    if (st != QII_OK) return st;
+    return qii_gemm_nvfp4(&ETq, &XTq, dW, g_dt, d_in, nullptr, 0, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,49 @@
+// Host-side interfaces between the translation units of libqii.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/qii.h"
+
+namespace qii {
+
+// Where the quantizer reads its logical R x C matrix from.
+//   kind F32 / BF16: element (r, c) = x[r*ld + c]            (transpose == 0)
+//                                     x[c*ld + r]            (transpose == 1)
+//   kind NVFP4     : element (r, c) = dequantized in[r][c] or in[c][r]; in_cols is the
+//                    number of columns of the stored tensor.
+enum SourceKind { kSrcF32 = 0, kSrcBF16 = 1, kSrcNVFP4 = 2 };
+
+struct Source {
+    int kind;
+    int transpose;
+    const void *x;           // f32 / bf16 data, or the FP4 codes
+    const uint8_t *scales;   // NVFP4 only
+    const float *ts;         // NVFP4 only (device scalar)
+    int64_t ld;              // elements (f32/bf16) or stored columns (NVFP4)
+};
+
+struct QuantizeArgs {
+    Source src;
+    int64_t R, C;            // logical shape: groups of 16 run along C
+    int mode;                // qii_mode
+    int rht;                 // 0 or 1
+    uint64_t seed_rht, seed_sr;
+    const float *amax;       // device scalar: max |rotated tensor|
+    uint8_t *codes;
+    uint8_t *scales;
+    float *tensor_scale;
+};
+
+hipError_t launch_fill_u32(uint32_t *p, uint32_t v, hipStream_t s);
+hipError_t launch_absmax(const Source &src, int64_t R, int64_t C, int rht, uint64_t seed_rht,
+                         float *amax /* must hold 0 */, hipStream_t s);
+hipError_t launch_rht(const Source &src, int64_t R, int64_t C, uint64_t seed_rht, float *y,
+                      float *amax /* nullable, must hold 0 */, hipStream_t s);
+hipError_t launch_quantize(const QuantizeArgs &a, hipStream_t s);
+hipError_t launch_dequantize(const uint8_t *codes, const uint8_t *scales, const float *ts,
+                             int64_t rows, int64_t cols, float *y, hipStream_t s);
+hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is_bf16, int64_t ldc,
+                       hipStream_t s);
+
+}  // namespace qii

@@ -1,0 +1,84 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol that
+include/qii.h declares, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def libqii():
+    from paper_2601_22813_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build(force=True)
+    return binding
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "qii.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qii_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(libqii):
+    names = declared_symbols()
+    assert len(names) >= 16
+    L = libqii.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(libqii.EXPORTS) == names
+
+
+def test_host_helpers(libqii, oracle):
+    assert libqii.qii_version() >= 1
+    for seed in (0, 7, 2 ** 63 + 5):
+        for i in range(6):
+            assert libqii.qii_derive_seed(seed, i) == oracle.derive_seed(seed, i)
+    assert libqii.qii_quantize_workspace_bytes() == 256
+    need = libqii.qii_linear_bwd_workspace_bytes(256, 128, 384)
+    payload = (256 * 384 + 128 * 384 + 384 * 256 + 128 * 256) * 9 // 16
+    assert payload <= need <= payload + 16 * 256
+    L = libqii.lib()
+    assert L.qii_status_string(0) == b"QII_OK" and L.qii_status_string(2) == b"QII_BAD_SHAPE"
+
+
+def test_bad_arguments_are_rejected_without_a_device(libqii):
+    L = libqii.lib()
+    out = libqii.binding._NVFP4(8, 8, 8, 4, 120) if hasattr(libqii, "binding") else None
+    from paper_2601_22813_amd.binding import _NVFP4
+    out = _NVFP4(0x1000, 0x1000, 0x1000, 4, 120)
+    # quantized dimension not a multiple of 16
+    st = L.qii_quantize_nvfp4(0x1000, 1, 4, 120, 120, 0, 0, 0, 0, 0, None, ctypes.byref(out), None, 0, None)
+    assert st == 2 and b"multiple" in L.qii_last_error()
+    # rotation needs multiples of 128
+    out = _NVFP4(0x1000, 0x1000, 0x1000, 4, 64)
+    st = L.qii_quantize_nvfp4(0x1000, 1, 4, 64, 64, 0, 2, 128, 0, 0, None, ctypes.byref(out), None, 0, None)
+    assert st == 2
+    # bad mode, bad dtype, null input, misaligned input
+    out = _NVFP4(0x1000, 0x1000, 0x1000, 4, 128)
+    assert L.qii_quantize_nvfp4(0x1000, 1, 4, 128, 128, 0, 9, 128, 0, 0, 0x2000, ctypes.byref(out), None, 0, None) == 1
+    assert L.qii_quantize_nvfp4(0x1000, 5, 4, 128, 128, 0, 2, 128, 0, 0, 0x2000, ctypes.byref(out), None, 0, None) == 1
+    assert L.qii_quantize_nvfp4(None, 1, 4, 128, 128, 0, 2, 128, 0, 0, 0x2000, ctypes.byref(out), None, 0, None) == 1
+    assert L.qii_quantize_nvfp4(0x1002, 1, 4, 128, 128, 0, 2, 128, 0, 0, 0x2000, ctypes.byref(out), None, 0, None) == 1
+    assert L.qii_quantize_nvfp4(0x1001, 1, 128, 4, 4, 1, 2, 128, 0, 0, 0x2000, ctypes.byref(out), None, 0, None) == 1
+    # output shape mismatch (transpose swaps it)
+    assert L.qii_quantize_nvfp4(0x1000, 1, 4, 128, 128, 1, 0, 0, 0, 0, 0x2000, ctypes.byref(out), None, 0, None) == 2
+    # no amax and no workspace
+    assert L.qii_quantize_nvfp4(0x1000, 1, 4, 128, 128, 0, 2, 128, 0, 0, None, ctypes.byref(out), None, 0, None) == 4
+    # GEMM: inner dimensions differ / K not a multiple of 32
+    a = _NVFP4(0x1000, 0x1000, 0x1000, 8, 64)
+    b = _NVFP4(0x1000, 0x1000, 0x1000, 8, 128)
+    assert L.qii_gemm_nvfp4(ctypes.byref(a), ctypes.byref(b), 0x3000, 0, 8, None, 0, None) == 2
+    a = _NVFP4(0x1000, 0x1000, 0x1000, 8, 48)
+    b = _NVFP4(0x1000, 0x1000, 0x1000, 8, 48)
+    assert L.qii_gemm_nvfp4(ctypes.byref(a), ctypes.byref(b), 0x3000, 0, 8, None, 0, None) == 2
+    # linear_bwd: workspace too small
+    xq = _NVFP4(0x1000, 0x1000, 0x1000, 256, 128)
+    wq = _NVFP4(0x1000, 0x1000, 0x1000, 384, 128)
+    assert L.qii_linear_bwd(0x1000, 1, ctypes.byref(xq), ctypes.byref(wq), 0, 0x1000, 0x1000, 1, 0x1000, 16, None) == 4
+    # empty tensors are accepted and do nothing
+    out = _NVFP4(None, None, None, 0, 128)
+    assert L.qii_quantize_nvfp4(None, 1, 0, 128, 128, 0, 2, 128, 0, 0, 0x2000, ctypes.byref(out), None, 0, None) == 0

@@ -1,0 +1,115 @@
+"""GPU parity of the block-scaled GEMM and of the layer passes against the CPU oracle.
+
+Tolerance (GEMM): the kernel forms every product e2m1*e4m3 x e2m1*e4m3 exactly and
+accumulates in f32, so |C_gpu - C_ref| <= 1e-5 * sum_k |A_hat B_hat| covers the f32
+accumulation (K <= 16384 terms added in blocks of 16 by the matrix unit, relative error per
+addition 2^-24) plus the one rounding of the epilogue scaling; bf16 outputs add one bf16
+rounding, 2^-8 |C_ref|."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_22813_amd import binding as qii
+from paper_2601_22813_amd import synth
+
+from gpu_util import assert_nv_equal, bf16_to_f64, nv_to_dev, to_dev, ws
+
+pytestmark = pytest.mark.gpu
+
+E2M1 = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0, -0.0, -0.5, -1.0, -1.5, -2.0, -3.0, -4.0, -6.0])
+
+
+def gemm_gpu(qa, qb, dtype, ldc=None):
+    M, N = qa.rows, qb.rows
+    ldc = ldc or N
+    C = torch.full((M, ldc), float("nan"), dtype=dtype, device="cuda")
+    qii.qii_gemm_nvfp4(nv_to_dev(qa), nv_to_dev(qb), C)
+    torch.cuda.synchronize()
+    return C[:, :N].float().cpu().numpy().astype(np.float64)
+
+
+def check(C, ref, absum, bf16):
+    tol = 1e-5 * absum + (2.0 ** -8 * np.abs(ref) if bf16 else 0.0) + 1e-30
+    err = np.abs(C - ref)
+    worst = np.unravel_index(np.argmax(err - tol), err.shape)
+    assert np.all(err <= tol), f"worst at {worst}: gpu {C[worst]} ref {ref[worst]} tol {tol[worst] if np.ndim(tol) else tol}"
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_gemm_256_cubed_config(oracle, dtype):
+    X = synth.normal_f32((256, 256), 1.0, 0)
+    W = synth.normal_f32((256, 256), 0.02, 1)
+    for mode in (oracle.RTN, oracle.SR, oracle.MS_EDEN):
+        qa = oracle.quantize(X, mode, seed_rht=0, seed_sr=0)
+        qb = oracle.quantize(W, mode, seed_rht=0, seed_sr=1)
+        ref, absum = oracle.gemm(qa, qb, with_abs=True)
+        check(gemm_gpu(qa, qb, dtype), ref, absum, dtype == torch.bfloat16)
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 200, 160), (1, 1, 32), (513, 257, 384), (64, 700, 1024),
+                                   (256, 256, 96)])
+def test_gemm_ragged_shapes(oracle, M, N, K):
+    rng = np.random.default_rng(M + N + K)
+    a = (rng.standard_t(3, size=(M, K)) * 0.1).astype(np.float32)
+    b = rng.standard_normal((N, K)).astype(np.float32)
+    qa = oracle.quantize(a, oracle.RTN, rht_group=0)
+    qb = oracle.quantize(b, oracle.SR, rht_group=0, seed_sr=4)
+    ref, absum = oracle.gemm(qa, qb, with_abs=True)
+    print(f"gemm {M}x{N}x{K}", flush=True)
+    check(gemm_gpu(qa, qb, torch.float32, ldc=N + 8), ref, absum, False)
+    check(gemm_gpu(qa, qb, torch.bfloat16), ref, absum, True)
+
+
+def test_gemm_unit_scales_is_exact(oracle):
+    # every scale byte 1.0 and tensor scale 1: all partial sums are multiples of 1/4 below 2^24,
+    # so the f32 result must equal the integer result exactly whatever the accumulation order
+    rng = np.random.default_rng(8)
+    M, N, K = 320, 288, 2048
+    qa = oracle.NVFP4(rng.integers(0, 256, (M, K // 2)).astype(np.uint8), np.full((M, K // 16), 0x38, np.uint8), np.ones(1, np.float32))
+    qb = oracle.NVFP4(rng.integers(0, 256, (N, K // 2)).astype(np.uint8), np.full((N, K // 16), 0x38, np.uint8), np.ones(1, np.float32))
+    C = gemm_gpu(qa, qb, torch.float32)
+    unpack = lambda c: np.stack([c & 15, c >> 4], -1).reshape(c.shape[0], -1)
+    ia = np.rint(E2M1[unpack(qa.codes)] * 2).astype(np.int64)
+    ib = np.rint(E2M1[unpack(qb.codes)] * 2).astype(np.int64)
+    assert np.array_equal(C * 4, (ia @ ib.T).astype(np.float64))
+
+
+def test_gemm_all_scale_bytes_and_codes(oracle):
+    # every E4M3 byte (subnormals included) against every FP4 code: dequantization is exact
+    K = 128
+    scales = np.arange(0, 127, dtype=np.uint8)
+    M = 127
+    a_codes = np.tile(np.array([0x10, 0x32, 0x54, 0x76, 0x98, 0xBA, 0xDC, 0xFE], np.uint8), (M, K // 16))
+    qa = oracle.NVFP4(a_codes, np.repeat(scales[:, None], K // 16, 1), np.array([1.0], np.float32))
+    b_codes = np.zeros((16, K // 2), np.uint8)
+    for n in range(16):      # B row n picks element n of every group with value 1.0 (code 2)
+        for g in range(K // 16):
+            b_codes[n, (g * 16 + n) // 2] = 2 << (4 * (n & 1))
+    qb = oracle.NVFP4(b_codes, np.full((16, K // 16), 0x38, np.uint8), np.array([1.0], np.float32))
+    C = gemm_gpu(qa, qb, torch.float32)
+    ref = oracle.gemm(qa, qb)
+    assert np.array_equal(C, ref)
+
+
+def test_linear_forward_and_backward(oracle):
+    T, d_in, d_out = 512, 256, 384
+    Xb, Wb, Eb = synth.linear_layer_bf16(T, d_in, d_out, seed=2)
+    X, W, E = to_dev(Xb), to_dev(Wb), to_dev(Eb)
+    Xq, Wq = qii.NVFP4Tensor.empty(T, d_in), qii.NVFP4Tensor.empty(d_out, d_in)
+    Y = torch.empty((T, d_out), dtype=torch.bfloat16, device="cuda")
+    qii.qii_linear_fwd(X, W, Y, Xq, Wq, ws(qii.qii_linear_fwd_workspace_bytes(T, d_in, d_out)))
+    oXq, oWq = oracle.linear_fwd(Xb, Wb)
+    assert_nv_equal(Xq, oXq, "saved X")
+    assert_nv_equal(Wq, oWq, "saved W")
+    ref, absum = oracle.gemm(oXq, oWq, with_abs=True)
+    check(bf16_to_f64(Y), ref, absum, True)
+    for seed in (0, 12345):
+        dX = torch.empty((T, d_in), dtype=torch.float32, device="cuda")
+        dW = torch.empty((d_out, d_in), dtype=torch.float32, device="cuda")
+        qii.qii_linear_bwd(E, Xq, Wq, seed, dX, dW, ws(qii.qii_linear_bwd_workspace_bytes(T, d_in, d_out)))
+        Eq, WTq, ETq, XTq = oracle.linear_bwd_operands(Eb, oXq, oWq, seed)
+        ref, absum = oracle.gemm(Eq, WTq, with_abs=True)
+        torch.cuda.synchronize()
+        check(dX.cpu().numpy().astype(np.float64), ref, absum, False)
+        ref, absum = oracle.gemm(ETq, XTq, with_abs=True)
+        check(dW.cpu().numpy().astype(np.float64), ref, absum, False)

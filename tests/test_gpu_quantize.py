@@ -1,0 +1,164 @@
+"""GPU parity of the quantizer family against the CPU oracle: every code byte, scale byte
+and the tensor scale must be bit-identical for identical seeds (called through the C ABI)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_22813_amd import binding as qii
+from paper_2601_22813_amd import synth
+
+from gpu_util import assert_nv_equal, nv_to_dev, to_dev, ws
+
+pytestmark = pytest.mark.gpu
+
+MODES = [qii.RTN, qii.SR, qii.MS_EDEN]
+
+
+def make(kind, shape, seed):
+    if kind == "normal_f32":
+        return synth.normal_f32(shape, 1.0, seed)
+    if kind == "weights_f32":
+        return synth.normal_f32(shape, 0.02, seed)
+    if kind == "t3_bf16":
+        return synth.student_t_bf16(shape, 3, 0.1, seed)
+    if kind == "grad_bf16":
+        return synth.normal_bf16(shape, 1e-3, seed)
+    raise KeyError(kind)
+
+
+def run_quantize(x_np, mode, transpose, rht_group, seed_rht, seed_sr, supply_amax=False, oracle=None):
+    x = to_dev(x_np)
+    rows, cols = x_np.shape
+    R, C = (cols, rows) if transpose else (rows, cols)
+    out = qii.NVFP4Tensor.empty(R, C)
+    out.codes.fill_(0xAB); out.scales.fill_(0xCD)
+    amax = None
+    if supply_amax:
+        amax = torch.empty(1, dtype=torch.float32, device="cuda")
+        qii.qii_absmax(x, transpose, rht_group, seed_rht, amax)
+    qii.qii_quantize_nvfp4(x, transpose, mode, rht_group, seed_rht, seed_sr, amax, out,
+                           None if supply_amax else ws(256))
+    return out
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("transpose", [False, True])
+@pytest.mark.parametrize("kind,shape", [("normal_f32", (256, 256)), ("weights_f32", (256, 256)),
+                                        ("t3_bf16", (384, 640)), ("grad_bf16", (128, 1152))])
+def test_quantize_matches_oracle_bit_for_bit(oracle, mode, transpose, kind, shape):
+    x = make(kind, shape, seed=3)
+    print(f"quantize mode={mode} transpose={transpose} {kind} {shape}", flush=True)
+    out = run_quantize(x, mode, transpose, 128, seed_rht=11, seed_sr=12)
+    ref = oracle.quantize(x, mode, transpose=transpose, rht_group=128, seed_rht=11, seed_sr=12)
+    assert_nv_equal(out, ref, f"mode {mode} transpose {transpose} {kind}")
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("rht_group,shape,transpose", [
+    (128, (37, 384), False),     # rows not a multiple of 4, three chunks per row
+    (128, (128, 50), True),      # transposed: 50 logical rows of 128
+    (0, (5, 48), False),         # no rotation: 3 groups per row, partial octet
+    (0, (64, 18), True),         # transposed, 18 logical rows of 64
+    (0, (1, 16), False),         # a single group
+    (128, (1, 128), False),      # a single chunk
+    (0, (100, 2064), False),     # 129 groups per row: ragged last octet
+])
+def test_ragged_shapes(oracle, mode, rht_group, shape, transpose):
+    x = synth.student_t_bf16(shape, 3, 0.1, seed=5)
+    if shape[1] % 8:   # bf16 rows must be 16-byte aligned: use f32 for the odd widths
+        x = synth.bf16_bits_to_f32(x)
+    print(f"ragged mode={mode} rht={rht_group} shape={shape} transpose={transpose}", flush=True)
+    out = run_quantize(x, mode, transpose, rht_group, seed_rht=21, seed_sr=22)
+    ref = oracle.quantize(x, mode, transpose=transpose, rht_group=rht_group, seed_rht=21, seed_sr=22)
+    assert_nv_equal(out, ref, f"ragged {shape}")
+
+
+def test_supplied_amax_and_absmax(oracle):
+    x = make("t3_bf16", (256, 512), seed=7)
+    for transpose in (False, True):
+        for rht_group in (0, 128):
+            xd = to_dev(x)
+            amax = torch.zeros(1, dtype=torch.float32, device="cuda")
+            qii.qii_absmax(xd, transpose, rht_group, 31, amax)
+            _, want = oracle.rht(x, transpose=transpose, rht_group=rht_group, seed_rht=31)
+            assert amax.item() == want
+            out = run_quantize(x, qii.MS_EDEN, transpose, rht_group, 31, 32, supply_amax=True)
+            ref = oracle.quantize(x, qii.MS_EDEN, transpose=transpose, rht_group=rht_group, seed_rht=31, seed_sr=32)
+            assert_nv_equal(out, ref, "supplied amax")
+    # a caller-chosen amax (twice the real one) is honoured
+    xd = to_dev(x)
+    amax = torch.tensor([0.75], dtype=torch.float32, device="cuda")
+    out = qii.NVFP4Tensor.empty(256, 512)
+    qii.qii_quantize_nvfp4(xd, False, qii.RTN, 0, 0, 0, amax, out, None)
+    ref = oracle.quantize(x, qii.RTN, rht_group=0, amax=0.75)
+    assert_nv_equal(out, ref, "caller amax")
+
+
+def test_rht_matches_oracle_bit_for_bit(oracle):
+    for kind, shape in [("normal_f32", (64, 256)), ("t3_bf16", (256, 128))]:
+        x = make(kind, shape, seed=9)
+        for transpose in (False, True):
+            R, C = (shape[1], shape[0]) if transpose else shape
+            y = torch.empty((R, C), dtype=torch.float32, device="cuda")
+            amax = torch.empty(1, dtype=torch.float32, device="cuda")
+            qii.qii_rht(to_dev(x), transpose, 41, y, amax)
+            want, want_amax = oracle.rht(x, transpose=transpose, seed_rht=41)
+            torch.cuda.synchronize()
+            assert np.array_equal(y.cpu().numpy().view(np.uint32), want.view(np.uint32))
+            assert amax.item() == want_amax
+
+
+def test_requantize_and_dequantize_match_oracle(oracle):
+    x = make("t3_bf16", (256, 384), seed=13)
+    saved = oracle.quantize(x, oracle.RTN, rht_group=0)
+    dev_saved = nv_to_dev(saved)
+    y = torch.empty((256, 384), dtype=torch.float32, device="cuda")
+    qii.qii_dequantize_nvfp4(dev_saved, y)
+    torch.cuda.synchronize()
+    assert np.array_equal(y.cpu().numpy().view(np.uint32), oracle.dequantize(saved).view(np.uint32))
+    for transpose in (True, False):
+        for mode in MODES:
+            R, C = (384, 256) if transpose else (256, 384)
+            out = qii.NVFP4Tensor.empty(R, C)
+            qii.qii_requantize_nvfp4(dev_saved, transpose, mode, 128, 51, 52, None, out, ws(256))
+            ref = oracle.requantize(saved, mode, transpose=transpose, seed_rht=51, seed_sr=52)
+            assert_nv_equal(out, ref, f"requantize transpose {transpose} mode {mode}")
+
+
+def test_degenerate_tensors(oracle):
+    z = np.zeros((8, 256), dtype=np.float32)
+    for mode in MODES:
+        out = run_quantize(z, mode, False, 128, 1, 2)
+        assert_nv_equal(out, oracle.quantize(z, mode, seed_rht=1, seed_sr=2), "zeros")
+    x = np.full((4, 256), 1e-9, dtype=np.float32)
+    x[0, 0] = 1e6
+    out = run_quantize(x, qii.RTN, False, 0, 0, 0)
+    assert_nv_equal(out, oracle.quantize(x, qii.RTN, rht_group=0), "underflowing groups")
+    # empty input: nothing is launched, nothing is written
+    out = qii.NVFP4Tensor.empty(0, 128)
+    qii.qii_quantize_nvfp4(torch.empty((0, 128), dtype=torch.bfloat16, device="cuda"), False,
+                           qii.MS_EDEN, 128, 0, 0, None, out, ws(256))
+    with pytest.raises(qii.QiiError):
+        qii.qii_quantize_nvfp4(torch.empty((4, 120), dtype=torch.float32, device="cuda"), False,
+                               qii.RTN, 0, 0, 0, None, qii.NVFP4Tensor.empty(4, 128), ws(256))
+
+
+def test_same_seed_same_bytes_and_seed_sensitivity(oracle):
+    x = make("grad_bf16", (256, 256), seed=17)
+    a = run_quantize(x, qii.MS_EDEN, False, 128, 5, 6)
+    b = run_quantize(x, qii.MS_EDEN, False, 128, 5, 6)
+    c = run_quantize(x, qii.MS_EDEN, False, 128, 5, 7)
+    torch.cuda.synchronize()
+    assert torch.equal(a.codes, b.codes) and torch.equal(a.scales, b.scales)
+    assert torch.equal(a.codes, c.codes) and not torch.equal(a.scales, c.scales)
+
+
+def test_full_size_config_matches_oracle(oracle):
+    """The benchmark configuration: 8192 x 8192 bf16, 0.1 * Student-t(3), MS-EDEN with
+    rotation groups of 128, blocks along rows and along columns."""
+    x = synth.student_t_bf16((8192, 8192), 3, 0.1, seed=1)
+    for transpose in (False, True):
+        print(f"full size transpose={transpose}", flush=True)
+        out = run_quantize(x, qii.MS_EDEN, transpose, 128, 0, 0)
+        ref = oracle.quantize(x, qii.MS_EDEN, transpose=transpose, seed_rht=0, seed_sr=0)
+        assert_nv_equal(out, ref, f"8192^2 transpose {transpose}")
