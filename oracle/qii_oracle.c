@@ -229,7 +229,10 @@ static float bf16_to_f32(uint16_t h)
 /* loop): y = H (d .* v) / sqrt(128), H the Sylvester matrix                */
 /* H[i][j] = (-1)^popcount(i & j), d the sign vector of omega_RHT.          */
 /* Butterfly stages run over index bits 0,1,..,6 in that order; every       */
-/* add/sub and the final scaling is one rounded binary32 operation.         */
+/* add/sub and the final scaling is one rounded binary32 operation.  The    */
+/* scaling is written as fma(v, 2^-3.5, +0): same value, but a result that  */
+/* is exactly zero comes out as +0 whatever signs of zero met on the way    */
+/* (the paper leaves the sign of a zero open; both FP4 zeros decode to 0).  */
 /* ------------------------------------------------------------------------ */
 static void rht128(float *v, const uint32_t signbits[4])
 {
@@ -243,7 +246,7 @@ static void rht128(float *v, const uint32_t signbits[4])
                 v[i + len] = a - b;
             }
     const float inv_sqrt_128 = 0x1.6a09e6p-4f; /* binary32 nearest to 2^-3.5 */
-    for (int j = 0; j < 128; ++j) v[j] = v[j] * inv_sqrt_128;
+    for (int j = 0; j < 128; ++j) v[j] = fmaf(v[j], inv_sqrt_128, 0.0f);
 }
 
 /* The logical matrix the quantizer works on: x (rows x cols, leading       */

@@ -43,6 +43,16 @@ hipError_t launch_rht(const Source &src, int64_t R, int64_t C, uint64_t seed_rht
 hipError_t launch_quantize(const QuantizeArgs &a, hipStream_t s);
 hipError_t launch_dequantize(const uint8_t *codes, const uint8_t *scales, const float *ts,
                              int64_t rows, int64_t cols, float *y, hipStream_t s);
+// tuned kernels for dense sources quantized along their rows (quantize_rows.hip)
+bool rows_kernels_apply(const Source &src);
+hipError_t launch_absmax_rows(const Source &src, int64_t R, int64_t C, int rht, uint64_t seed_rht,
+                              float *amax, hipStream_t s);
+hipError_t launch_quantize_rows(const QuantizeArgs &a, hipStream_t s);
+// tuned kernels for dense sources quantized along their columns (quantize_cols.hip)
+bool cols_kernels_apply(const Source &src, int64_t R, int64_t C);
+hipError_t launch_absmax_cols(const Source &src, int64_t R, int64_t C, int rht, uint64_t seed_rht,
+                              float *amax, hipStream_t s);
+hipError_t launch_quantize_cols(const QuantizeArgs &a, hipStream_t s);
 hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is_bf16, int64_t ldc,
                        hipStream_t s);
 

@@ -144,7 +144,7 @@ __device__ __forceinline__ void rht128(float v[16], uint32_t sign16, int blk)
 #pragma unroll
     for (int k = 0; k < 16; ++k) v[k] = __builtin_fmaf(v[k], s64, dpp_f<kDppHalfMirror>(v[k]));
 #pragma unroll
-    for (int k = 0; k < 16; ++k) v[k] = v[k] * kInvSqrt128;
+    for (int k = 0; k < 16; ++k) v[k] = __builtin_fmaf(v[k], kInvSqrt128, 0.0f);  // +0 for exact zeros
 }
 
 __device__ __forceinline__ uint32_t lane_sign16(uint64_t seed_rht, int blk)
@@ -159,6 +159,21 @@ __device__ __forceinline__ float wave_max(float m)
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
     return m;
+}
+
+// block-wide maximum into a global running maximum (non-negative floats order like their
+// bit patterns).  The running maximum only grows, so a stale read can only cause a
+// redundant atomic.  Must be reached by every thread of the block.
+__device__ __forceinline__ void block_max_to_global(float m, uint32_t *amax_bits)
+{
+    __shared__ float wave_m[4];
+    m = wave_max(m);
+    if ((threadIdx.x & 63) == 0) wave_m[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        m = fmaxf(fmaxf(wave_m[0], wave_m[1]), fmaxf(wave_m[2], wave_m[3]));
+        if (f2u(m) > __atomic_load_n(amax_bits, __ATOMIC_RELAXED)) atomicMax(amax_bits, f2u(m));
+    }
 }
 
 // ------------------------------------------------------------------ kernels
@@ -186,8 +201,7 @@ __global__ __launch_bounds__(256) void absmax_kernel(Loader load, int64_t R, int
 #pragma unroll
         for (int k = 0; k < 16; ++k) m = fmaxf(m, fabsf(v[k]));
     }
-    m = wave_max(m);
-    if ((threadIdx.x & 63) == 0) atomicMax(amax_bits, f2u(m));
+    block_max_to_global(m, amax_bits);
 }
 
 template <class Loader>
@@ -217,10 +231,7 @@ __global__ __launch_bounds__(256) void rht_kernel(Loader load, int64_t R, int64_
 #pragma unroll
         for (int k = 0; k < 16; ++k) m = fmaxf(m, fabsf(v[k]));
     }
-    if (amax_bits) {
-        m = wave_max(m);
-        if ((threadIdx.x & 63) == 0) atomicMax(amax_bits, f2u(m));
-    }
+    if (amax_bits) block_max_to_global(m, amax_bits);
 }
 
 // s and cap of the three schemes (Table 1 RTN; Sec. 3.1 Q_SR; Sec. 3.3 Q_RTN(x, s))
@@ -367,6 +378,8 @@ hipError_t launch_absmax(const Source &src, int64_t R, int64_t C, int rht, uint6
                          float *amax, hipStream_t s)
 {
     if (R == 0 || C == 0) return hipSuccess;
+    if (rows_kernels_apply(src)) return launch_absmax_rows(src, R, C, rht, seed_rht, amax, s);
+    if (cols_kernels_apply(src, R, C)) return launch_absmax_cols(src, R, C, rht, seed_rht, amax, s);
     const dim3 grid((unsigned)grid_for(R, C, 256)), block(256);
     return with_loader(src, [&](auto load) {
         using L = decltype(load);
@@ -391,6 +404,8 @@ hipError_t launch_rht(const Source &src, int64_t R, int64_t C, uint64_t seed_rht
 hipError_t launch_quantize(const QuantizeArgs &a, hipStream_t s)
 {
     if (a.R == 0 || a.C == 0) return hipSuccess;
+    if (rows_kernels_apply(a.src)) return launch_quantize_rows(a, s);
+    if (cols_kernels_apply(a.src, a.R, a.C)) return launch_quantize_cols(a, s);
     const dim3 grid((unsigned)grid_for(a.R, a.C, 256)), block(256);
     return with_loader(a.src, [&](auto load) {
         using L = decltype(load);

@@ -1,0 +1,217 @@
+// Tuned quantizer / abs-max kernels for dense row-major sources quantized along their
+// COLUMNS (the transposed case: Q(E^T), whose scale groups and rotation chunks run down the
+// rows of x while memory is contiguous along its columns).
+//
+// Layout of the work: a lane owns one column j of x, i.e. one output row, and one whole
+// 128-chunk of it: 128 registers.  A wave reads, for each of the 128 rows of the chunk, 64
+// adjacent elements (one 128-byte line of bf16), so global loads stay coalesced without a
+// transpose through LDS; all seven butterfly stages of the rotation, the eight group maxima
+// and dot products are in-lane and the rotation signs are wave-uniform scalars.  A lane
+// writes 64 contiguous bytes of codes and 8 scale bytes per chunk; the 4 waves of a block
+// take 4 consecutive chunks of the same columns, so a block writes 256 contiguous bytes of
+// every output row.  The scale-rounding draws follow the library-wide rule (one Philox call
+// feeds rows 4q..4q+3 of one column group): the 4 lanes of a quad compute two calls each
+// and hand the words round with quad broadcasts.
+#include "qii_device.h"
+#include "qii_internal.h"
+#include "quantize_core.h"
+
+namespace qii {
+namespace {
+
+constexpr float kInvSqrt128 = 0x1.6a09e6p-4f;  // binary32 nearest to 2^-3.5
+
+struct ColsArgs {
+    const void *x;
+    int64_t ld;          // elements
+    int64_t R, C;        // logical shape: R = columns of x (output rows), C = rows of x
+    uint32_t sign[4];
+    uint64_t seed_sr;
+    const float *amax;
+    uint8_t *codes;
+    uint8_t *scales;
+    float *tensor_scale;
+    uint32_t *amax_out;
+};
+
+// load the 128 rows of one chunk of column j, widen to f32, apply the rotation signs
+template <bool kBf16, bool kRht>
+__device__ __forceinline__ void load_chunk(float v[128], const ColsArgs &a, int64_t chunk, int64_t j, bool ok)
+{
+    if (!ok) {
+#pragma unroll
+        for (int i = 0; i < 128; ++i) v[i] = 0.0f;
+        return;
+    }
+    uint32_t raw[128];
+    if (kBf16) {
+        const uint16_t *p = (const uint16_t *)a.x + (chunk * 128) * a.ld + j;
+#pragma unroll
+        for (int i = 0; i < 128; ++i) raw[i] = p[(int64_t)i * a.ld];
+    } else {
+        const uint32_t *p = (const uint32_t *)a.x + (chunk * 128) * a.ld + j;
+#pragma unroll
+        for (int i = 0; i < 128; ++i) raw[i] = p[(int64_t)i * a.ld];
+    }
+#pragma unroll
+    for (int i = 0; i < 128; ++i) {
+        uint32_t u = kBf16 ? (raw[i] << 16) : raw[i];
+        if (kRht) u ^= ((a.sign[i >> 5] >> (i & 31)) & 1u) << 31;
+        v[i] = u2f(u);
+    }
+}
+
+// y = H v / sqrt(128) in registers: stages over index bits 0..6 in order
+__device__ __forceinline__ void fwht128(float v[128])
+{
+#pragma unroll
+    for (int len = 1; len < 128; len <<= 1)
+#pragma unroll
+        for (int i = 0; i < 128; ++i)
+            if ((i & len) == 0) {
+                const float x = v[i], y = v[i + len];
+                v[i] = x + y;
+                v[i + len] = x - y;
+            }
+#pragma unroll
+    for (int i = 0; i < 128; ++i) v[i] = __builtin_fmaf(v[i], kInvSqrt128, 0.0f);  // +0 for exact zeros
+}
+
+template <int kSrcLane>
+__device__ __forceinline__ uint32_t quad_bcast(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, kSrcLane * 0x55, 0xF, 0xF, true);
+}
+
+// draws of the 8 groups (column groups 8*chunk .. 8*chunk+7) of output row j.
+// Lane m of a quad computes the calls of column groups 2m and 2m+1 of the chunk; every lane
+// then takes word (j mod 4) of each call.
+__device__ __forceinline__ void quad_draws(uint32_t draw[8], uint64_t seed_sr, int64_t chunk, int64_t j)
+{
+    const int m = threadIdx.x & 3;
+    const U4 wa = philox_seeded(seed_sr, (uint32_t)(chunk * 8 + 2 * m), (uint32_t)(j >> 2), 0, kStreamScale);
+    const U4 wb = philox_seeded(seed_sr, (uint32_t)(chunk * 8 + 2 * m + 1), (uint32_t)(j >> 2), 0, kStreamScale);
+#define QII_PICK(GI, SRC, W)                                                                      \
+    do {                                                                                          \
+        const uint32_t x = quad_bcast<SRC>(W.x), y = quad_bcast<SRC>(W.y);                        \
+        const uint32_t z = quad_bcast<SRC>(W.z), w = quad_bcast<SRC>(W.w);                        \
+        draw[GI] = (m == 0 ? x : m == 1 ? y : m == 2 ? z : w) >> 12;                              \
+    } while (0)
+    QII_PICK(0, 0, wa); QII_PICK(1, 0, wb); QII_PICK(2, 1, wa); QII_PICK(3, 1, wb);
+    QII_PICK(4, 2, wa); QII_PICK(5, 2, wb); QII_PICK(6, 3, wa); QII_PICK(7, 3, wb);
+#undef QII_PICK
+}
+
+template <bool kBf16, int kMode, bool kRht>
+__global__ __launch_bounds__(256, 2) void quantize_cols_kernel(ColsArgs a)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;
+    const int64_t j = (int64_t)blockIdx.y * 64 + lane;
+    const TensorConsts tc = tensor_consts(kMode, *a.amax);
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *a.tensor_scale = tc.x32;
+    if (chunk * 128 >= a.C) return;  // wave-uniform
+    const bool ok = j < a.R;
+    float v[128];
+    load_chunk<kBf16, kRht>(v, a, chunk, j, ok && !tc.zero);
+    if (kRht) fwht128(v);
+    uint32_t draw[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+    if (kMode == QII_MS_EDEN) quad_draws(draw, a.seed_sr, chunk, j);
+    uint32_t codes[16];
+    uint32_t sc[2] = {0u, 0u};
+#pragma unroll
+    for (int gi = 0; gi < 8; ++gi) {
+        const uint32_t b = quantize_group16<kMode>(v + 16 * gi, tc, draw[gi], a.seed_sr, j, chunk * 8 + gi, codes + 2 * gi);
+        sc[gi >> 2] |= b << (8 * (gi & 3));
+    }
+    if (ok) {
+        uint4 *pc = reinterpret_cast<uint4 *>(a.codes + j * (a.C / 2) + chunk * 64);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pc[i] = make_uint4(codes[4 * i], codes[4 * i + 1], codes[4 * i + 2], codes[4 * i + 3]);
+        *reinterpret_cast<uint2 *>(a.scales + j * (a.C / 16) + chunk * 8) = make_uint2(sc[0], sc[1]);
+    }
+}
+
+template <bool kBf16, bool kRht>
+__global__ __launch_bounds__(256, 2) void absmax_cols_kernel(ColsArgs a)
+{
+    __shared__ float wave_m[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;
+    const int64_t j = (int64_t)blockIdx.y * 64 + lane;
+    float m = 0.0f;
+    if (chunk * 128 < a.C) {  // wave-uniform
+        float v[128];
+        load_chunk<kBf16, kRht>(v, a, chunk, j, j < a.R);
+        if (kRht) fwht128(v);
+#pragma unroll
+        for (int gi = 0; gi < 8; ++gi) m = fmaxf(m, group_absmax(v + 16 * gi));
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    if (lane == 0) wave_m[wave] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        m = fmaxf(fmaxf(wave_m[0], wave_m[1]), fmaxf(wave_m[2], wave_m[3]));
+        // the running maximum only grows, so a stale read can only cause a redundant atomic
+        if (f2u(m) > __atomic_load_n(a.amax_out, __ATOMIC_RELAXED)) atomicMax(a.amax_out, f2u(m));
+    }
+}
+
+ColsArgs make_args(const Source &src, int64_t R, int64_t C, uint64_t seed_rht, uint64_t seed_sr)
+{
+    ColsArgs a;
+    a.x = src.x; a.ld = src.ld; a.R = R; a.C = C;
+    const U4 w = philox_seeded(seed_rht, 0, 0, 0, kStreamRht);
+    a.sign[0] = w.x; a.sign[1] = w.y; a.sign[2] = w.z; a.sign[3] = w.w;
+    a.seed_sr = seed_sr;
+    a.amax = nullptr; a.codes = nullptr; a.scales = nullptr; a.tensor_scale = nullptr; a.amax_out = nullptr;
+    return a;
+}
+
+dim3 cols_grid(int64_t R, int64_t C)
+{
+    return dim3((unsigned)((C / 128 + 3) / 4), (unsigned)((R + 63) / 64));
+}
+
+}  // namespace
+
+bool cols_kernels_apply(const Source &src, int64_t R, int64_t C)
+{
+    return src.transpose && (src.kind == kSrcBF16 || src.kind == kSrcF32) && C % 128 == 0 &&
+           (R + 63) / 64 <= 65535;
+}
+
+hipError_t launch_absmax_cols(const Source &src, int64_t R, int64_t C, int rht, uint64_t seed_rht,
+                              float *amax, hipStream_t s)
+{
+    ColsArgs a = make_args(src, R, C, seed_rht, 0);
+    a.amax_out = reinterpret_cast<uint32_t *>(amax);
+    const dim3 grid = cols_grid(R, C), block(256);
+    const bool bf = src.kind == kSrcBF16;
+    if (bf) { if (rht) hipLaunchKernelGGL((absmax_cols_kernel<true, true>), grid, block, 0, s, a); else hipLaunchKernelGGL((absmax_cols_kernel<true, false>), grid, block, 0, s, a); }
+    else { if (rht) hipLaunchKernelGGL((absmax_cols_kernel<false, true>), grid, block, 0, s, a); else hipLaunchKernelGGL((absmax_cols_kernel<false, false>), grid, block, 0, s, a); }
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_cols(const QuantizeArgs &q, hipStream_t s)
+{
+    ColsArgs a = make_args(q.src, q.R, q.C, q.seed_rht, q.seed_sr);
+    a.amax = q.amax; a.codes = q.codes; a.scales = q.scales; a.tensor_scale = q.tensor_scale;
+    const dim3 grid = cols_grid(q.R, q.C), block(256);
+    const bool bf = q.src.kind == kSrcBF16;
+#define QII_COLS(BF, MODE, RHT) hipLaunchKernelGGL((quantize_cols_kernel<BF, MODE, RHT>), grid, block, 0, s, a)
+#define QII_COLS_MODE(BF, RHT)                                   \
+    do {                                                         \
+        if (q.mode == QII_RTN) QII_COLS(BF, QII_RTN, RHT);       \
+        else if (q.mode == QII_SR) QII_COLS(BF, QII_SR, RHT);    \
+        else QII_COLS(BF, QII_MS_EDEN, RHT);                     \
+    } while (0)
+    if (bf) { if (q.rht) QII_COLS_MODE(true, true); else QII_COLS_MODE(true, false); }
+    else { if (q.rht) QII_COLS_MODE(false, true); else QII_COLS_MODE(false, false); }
+#undef QII_COLS_MODE
+#undef QII_COLS
+    return hipGetLastError();
+}
+
+}  // namespace qii

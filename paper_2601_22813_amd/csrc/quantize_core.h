@@ -1,0 +1,122 @@
+// Per-group arithmetic of the NVFP4 quantizers, shared by the tuned kernels.
+// One call quantizes the 16 (already rotated) values of one scale group held by one lane.
+//
+// The conversions use gfx950's converters where their results were checked, exhaustively
+// over all binary32 inputs, to equal the value-space rules of the arithmetic contract:
+//   v_cvt_scalef32_pk_fp4_f32 (scale 1.0) = round to nearest E2M1, ties to the even code,
+//       saturating at 6, sign kept (also on results that round to zero);
+//   v_cvt_pk_fp8_f32 on [0, 448]          = round to nearest E4M3, ties to even;
+//   v_cvt_scalef32_pk_f32_fp4             = exact E2M1 decode.
+#pragma once
+#include "qii_device.h"
+
+namespace qii {
+
+typedef float float2_t __attribute__((ext_vector_type(2)));
+
+struct TensorConsts {
+    float x32;   // x^FP32 = amax / (s * cap)
+    float d;     // x^FP32 * s, the divisor of the group-scale equation
+    float rd;    // 1 / d, correctly rounded
+    bool zero;   // amax == 0: emit zeros
+    bool fast;   // magnitudes far from the denormal range: division by d via rd is exact
+};
+
+__device__ __forceinline__ TensorConsts tensor_consts(int mode, float amax)
+{
+    float s, cap;
+    if (mode == QII_RTN) { s = 6.0f; cap = 448.0f; }
+    else if (mode == QII_SR) { s = (float)(96.0 / 17.0); cap = 448.0f; }
+    else { s = (float)(96.0 / 17.0 / 0.93); cap = 256.0f; }
+    TensorConsts tc;
+    tc.zero = !(amax > 0.0f);
+    tc.x32 = tc.zero ? 1.0f : amax / (s * cap);
+    tc.d = tc.x32 * s;
+    tc.rd = 1.0f / tc.d;
+    tc.fast = amax > 0x1p-80f && amax < 0x1p100f;
+    return tc;
+}
+
+// a / d rounded to nearest: with rd = RN(1/d), two residual corrections of a * rd give the
+// correctly rounded quotient when nothing under- or overflows (the same refinement a
+// compiler-generated IEEE division ends with); otherwise fall back to the division.
+__device__ __forceinline__ float div_by_tensor_const(float a, const TensorConsts &tc)
+{
+    if (!tc.fast) return a / tc.d;
+    const float q0 = a * tc.rd;
+    const float e0 = __builtin_fmaf(-tc.d, q0, a);
+    const float q1 = __builtin_fmaf(e0, tc.rd, q0);
+    const float e1 = __builtin_fmaf(-tc.d, q1, a);
+    return __builtin_fmaf(e1, tc.rd, q1);
+}
+
+__device__ __forceinline__ float group_absmax(const float y[16])
+{
+    float m0 = fmaxf(fabsf(y[0]), fabsf(y[1])), m1 = fmaxf(fabsf(y[2]), fabsf(y[3]));
+#pragma unroll
+    for (int k = 4; k < 16; k += 4) {
+        m0 = fmaxf(fmaxf(m0, fabsf(y[k])), fabsf(y[k + 1]));
+        m1 = fmaxf(fmaxf(m1, fabsf(y[k + 2])), fabsf(y[k + 3]));
+    }
+    return fmaxf(m0, m1);
+}
+
+// Quantize one group.  y: rotated values; draw20: the 20 scale-rounding bits of this group
+// (MS-EDEN); (seed_sr, row, g): identify the element draws (SR).  Returns the scale byte and
+// fills packed[2] with the 16 codes (element 2j in the low nibble of byte j).
+template <int kMode>
+__device__ __forceinline__ uint32_t quantize_group16(const float y[16], const TensorConsts &tc,
+                                                     uint32_t draw20, uint64_t seed_sr, int64_t row,
+                                                     int64_t g, uint32_t packed[2])
+{
+    packed[0] = 0u;
+    packed[1] = 0u;
+    // x^FP8_g = RTN_FP8( max_g |x| / (x^FP32 * s) ), saturating at 448
+    const float r = div_by_tensor_const(group_absmax(y), tc);
+    uint32_t b = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(fminf(r, 448.0f), 0.0f, 0, false) & 0xFFu;
+    if (b == 0u) return 0u;
+    const float x8 = e4m3_decode(b);
+    const float inv = 1.0f / (x8 * tc.x32);
+    if (kMode == QII_SR) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const U4 w = philox_seeded(seed_sr, (uint32_t)(g * 2 + h), (uint32_t)row, 0, kStreamElem);
+            const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float q = y[h * 8 + j] * inv;
+                const uint32_t r16 = (j & 1) ? (ww[j >> 1] >> 16) : (ww[j >> 1] & 0xFFFFu);
+                const uint32_t code = e2m1_sr_code(fabsf(q), r16) | ((f2u(q) >> 28) & 8u);
+                packed[h] |= code << (4 * j);
+            }
+        }
+        return b;
+    }
+    // x^FP4_i = RTN_FP4( x_i * inv ): two elements per conversion, packed in place
+#define QII_ENC(H, I)                                                                             \
+    packed[H] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed[H], y[8 * H + 2 * I] * inv,       \
+                                                         y[8 * H + 2 * I + 1] * inv, 1.0f, I)
+    QII_ENC(0, 0); QII_ENC(0, 1); QII_ENC(0, 2); QII_ENC(0, 3);
+    QII_ENC(1, 0); QII_ENC(1, 1); QII_ENC(1, 2); QII_ENC(1, 3);
+#undef QII_ENC
+    if (kMode == QII_MS_EDEN) {
+        // S_g * x^FP8_g = <x,x> / (<x, x^FP4> * x^FP32); dot products as fma chains in index order
+        float num = 0.0f, den = 0.0f;
+#define QII_DOT(H, I)                                                                             \
+    do {                                                                                          \
+        const float2_t c = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(packed[H], 1.0f, I);          \
+        const float y0 = y[8 * H + 2 * I], y1 = y[8 * H + 2 * I + 1];                             \
+        num = __builtin_fmaf(y0, y0, num);                                                        \
+        den = __builtin_fmaf(y0, c[0], den);                                                      \
+        num = __builtin_fmaf(y1, y1, num);                                                        \
+        den = __builtin_fmaf(y1, c[1], den);                                                      \
+    } while (0)
+        QII_DOT(0, 0); QII_DOT(0, 1); QII_DOT(0, 2); QII_DOT(0, 3);
+        QII_DOT(1, 0); QII_DOT(1, 1); QII_DOT(1, 2); QII_DOT(1, 3);
+#undef QII_DOT
+        if (den > 0.0f) b = e4m3_sr(num / (den * tc.x32), draw20);
+    }
+    return b;
+}
+
+}  // namespace qii
