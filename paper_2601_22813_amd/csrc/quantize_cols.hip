@@ -1,6 +1,8 @@
 // Tuned quantizer / abs-max kernels for dense row-major sources quantized along their
 // COLUMNS (the transposed case: Q(E^T), whose scale groups and rotation chunks run down the
-// rows of x while memory is contiguous along its columns).
+// rows of x while memory is contiguous along its columns), and for the backward pass's
+// re-quantization of a saved NVFP4 tensor with transposition (Q(W^T), Q(X^T)), where the
+// source element is dequantized on load: (e2m1 * e4m3) * tensor_scale.
 //
 // Layout of the work: a lane owns one column j of x, i.e. one output row, and one whole
 // 128-chunk of it: 128 registers.  A wave reads, for each of the 128 rows of the chunk, 64
@@ -22,8 +24,10 @@ namespace {
 constexpr float kInvSqrt128 = 0x1.6a09e6p-4f;  // binary32 nearest to 2^-3.5
 
 struct ColsArgs {
-    const void *x;
-    int64_t ld;          // elements
+    const void *x;       // f32 / bf16 data, or the FP4 codes of an NVFP4 source
+    const uint8_t *in_scales;  // NVFP4 source only
+    const float *in_ts;        // NVFP4 source only
+    int64_t ld;          // elements (stored columns for an NVFP4 source)
     int64_t R, C;        // logical shape: R = columns of x (output rows), C = rows of x
     uint32_t sign[4];
     uint64_t seed_sr;
@@ -35,12 +39,41 @@ struct ColsArgs {
 };
 
 // load the 128 rows of one chunk of column j, widen to f32, apply the rotation signs
-template <bool kBf16, bool kRht>
+template <int kSrc, bool kRht>
 __device__ __forceinline__ void load_chunk(float v[128], const ColsArgs &a, int64_t chunk, int64_t j, bool ok)
 {
+    constexpr bool kBf16 = kSrc == kSrcBF16;
     if (!ok) {
 #pragma unroll
         for (int i = 0; i < 128; ++i) v[i] = 0.0f;
+        return;
+    }
+    if (kSrc == kSrcNVFP4) {
+        // two lanes share a code byte, sixteen a scale byte; batches of 32 rows bound the
+        // number of loads (and registers) in flight
+        const int64_t cstride = a.ld / 2, sstride = a.ld / 16;
+        const uint8_t *pc = (const uint8_t *)a.x + (chunk * 128) * cstride + j / 2;
+        const uint8_t *ps = a.in_scales + (chunk * 128) * sstride + j / 16;
+        const uint32_t shift = (uint32_t)(j & 1) * 4u;
+        const float x32 = *a.in_ts;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            uint32_t rc[32], rs[32];
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+                rc[i] = pc[(int64_t)(32 * b + i) * cstride];
+                rs[i] = ps[(int64_t)(32 * b + i) * sstride];
+            }
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+                const int k = 32 * b + i;
+                const float2_t c = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(rc[i] >> shift, 1.0f, 0);
+                const float m = c[0] * e4m3_decode(rs[i]);   // exact
+                const uint32_t flip = kRht ? (((a.sign[k >> 5] >> (k & 31)) & 1u) << 31) : 0u;
+                v[k] = m * u2f(f2u(x32) ^ flip);
+            }
+            asm volatile("" ::: "memory");
+        }
         return;
     }
     uint32_t raw[128];
@@ -102,7 +135,7 @@ __device__ __forceinline__ void quad_draws(uint32_t draw[8], uint64_t seed_sr, i
 #undef QII_PICK
 }
 
-template <bool kBf16, int kMode, bool kRht>
+template <int kSrc, int kMode, bool kRht>
 __global__ __launch_bounds__(256, 2) void quantize_cols_kernel(ColsArgs a)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -113,7 +146,7 @@ __global__ __launch_bounds__(256, 2) void quantize_cols_kernel(ColsArgs a)
     if (chunk * 128 >= a.C) return;  // wave-uniform
     const bool ok = j < a.R;
     float v[128];
-    load_chunk<kBf16, kRht>(v, a, chunk, j, ok && !tc.zero);
+    load_chunk<kSrc, kRht>(v, a, chunk, j, ok && !tc.zero);
     if (kRht) fwht128(v);
     uint32_t draw[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
     if (kMode == QII_MS_EDEN) quad_draws(draw, a.seed_sr, chunk, j);
@@ -132,7 +165,7 @@ __global__ __launch_bounds__(256, 2) void quantize_cols_kernel(ColsArgs a)
     }
 }
 
-template <bool kBf16, bool kRht>
+template <int kSrc, bool kRht>
 __global__ __launch_bounds__(256, 2) void absmax_cols_kernel(ColsArgs a)
 {
     __shared__ float wave_m[4];
@@ -142,7 +175,7 @@ __global__ __launch_bounds__(256, 2) void absmax_cols_kernel(ColsArgs a)
     float m = 0.0f;
     if (chunk * 128 < a.C) {  // wave-uniform
         float v[128];
-        load_chunk<kBf16, kRht>(v, a, chunk, j, j < a.R);
+        load_chunk<kSrc, kRht>(v, a, chunk, j, j < a.R);
         if (kRht) fwht128(v);
 #pragma unroll
         for (int gi = 0; gi < 8; ++gi) m = fmaxf(m, group_absmax(v + 16 * gi));
@@ -161,7 +194,7 @@ __global__ __launch_bounds__(256, 2) void absmax_cols_kernel(ColsArgs a)
 ColsArgs make_args(const Source &src, int64_t R, int64_t C, uint64_t seed_rht, uint64_t seed_sr)
 {
     ColsArgs a;
-    a.x = src.x; a.ld = src.ld; a.R = R; a.C = C;
+    a.x = src.x; a.in_scales = src.scales; a.in_ts = src.ts; a.ld = src.ld; a.R = R; a.C = C;
     const U4 w = philox_seeded(seed_rht, 0, 0, 0, kStreamRht);
     a.sign[0] = w.x; a.sign[1] = w.y; a.sign[2] = w.z; a.sign[3] = w.w;
     a.seed_sr = seed_sr;
@@ -178,8 +211,7 @@ dim3 cols_grid(int64_t R, int64_t C)
 
 bool cols_kernels_apply(const Source &src, int64_t R, int64_t C)
 {
-    return src.transpose && (src.kind == kSrcBF16 || src.kind == kSrcF32) && C % 128 == 0 &&
-           (R + 63) / 64 <= 65535;
+    return src.transpose && C % 128 == 0 && (R + 63) / 64 <= 65535;
 }
 
 hipError_t launch_absmax_cols(const Source &src, int64_t R, int64_t C, int rht, uint64_t seed_rht,
@@ -188,9 +220,15 @@ hipError_t launch_absmax_cols(const Source &src, int64_t R, int64_t C, int rht, 
     ColsArgs a = make_args(src, R, C, seed_rht, 0);
     a.amax_out = reinterpret_cast<uint32_t *>(amax);
     const dim3 grid = cols_grid(R, C), block(256);
-    const bool bf = src.kind == kSrcBF16;
-    if (bf) { if (rht) hipLaunchKernelGGL((absmax_cols_kernel<true, true>), grid, block, 0, s, a); else hipLaunchKernelGGL((absmax_cols_kernel<true, false>), grid, block, 0, s, a); }
-    else { if (rht) hipLaunchKernelGGL((absmax_cols_kernel<false, true>), grid, block, 0, s, a); else hipLaunchKernelGGL((absmax_cols_kernel<false, false>), grid, block, 0, s, a); }
+#define QII_AMAX(SRC)                                                                             \
+    do {                                                                                          \
+        if (rht) hipLaunchKernelGGL((absmax_cols_kernel<SRC, true>), grid, block, 0, s, a);       \
+        else hipLaunchKernelGGL((absmax_cols_kernel<SRC, false>), grid, block, 0, s, a);          \
+    } while (0)
+    if (src.kind == kSrcBF16) QII_AMAX(kSrcBF16);
+    else if (src.kind == kSrcF32) QII_AMAX(kSrcF32);
+    else QII_AMAX(kSrcNVFP4);
+#undef QII_AMAX
     return hipGetLastError();
 }
 
@@ -199,16 +237,22 @@ hipError_t launch_quantize_cols(const QuantizeArgs &q, hipStream_t s)
     ColsArgs a = make_args(q.src, q.R, q.C, q.seed_rht, q.seed_sr);
     a.amax = q.amax; a.codes = q.codes; a.scales = q.scales; a.tensor_scale = q.tensor_scale;
     const dim3 grid = cols_grid(q.R, q.C), block(256);
-    const bool bf = q.src.kind == kSrcBF16;
-#define QII_COLS(BF, MODE, RHT) hipLaunchKernelGGL((quantize_cols_kernel<BF, MODE, RHT>), grid, block, 0, s, a)
-#define QII_COLS_MODE(BF, RHT)                                   \
-    do {                                                         \
-        if (q.mode == QII_RTN) QII_COLS(BF, QII_RTN, RHT);       \
-        else if (q.mode == QII_SR) QII_COLS(BF, QII_SR, RHT);    \
-        else QII_COLS(BF, QII_MS_EDEN, RHT);                     \
+#define QII_COLS(SRC, MODE, RHT) hipLaunchKernelGGL((quantize_cols_kernel<SRC, MODE, RHT>), grid, block, 0, s, a)
+#define QII_COLS_MODE(SRC, RHT)                                   \
+    do {                                                          \
+        if (q.mode == QII_RTN) QII_COLS(SRC, QII_RTN, RHT);       \
+        else if (q.mode == QII_SR) QII_COLS(SRC, QII_SR, RHT);    \
+        else QII_COLS(SRC, QII_MS_EDEN, RHT);                     \
     } while (0)
-    if (bf) { if (q.rht) QII_COLS_MODE(true, true); else QII_COLS_MODE(true, false); }
-    else { if (q.rht) QII_COLS_MODE(false, true); else QII_COLS_MODE(false, false); }
+#define QII_COLS_SRC(SRC)                                         \
+    do {                                                          \
+        if (q.rht) QII_COLS_MODE(SRC, true);                      \
+        else QII_COLS_MODE(SRC, false);                           \
+    } while (0)
+    if (q.src.kind == kSrcBF16) QII_COLS_SRC(kSrcBF16);
+    else if (q.src.kind == kSrcF32) QII_COLS_SRC(kSrcF32);
+    else QII_COLS_SRC(kSrcNVFP4);
+#undef QII_COLS_SRC
 #undef QII_COLS_MODE
 #undef QII_COLS
     return hipGetLastError();

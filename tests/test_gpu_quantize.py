@@ -125,6 +125,21 @@ def test_requantize_and_dequantize_match_oracle(oracle):
             assert_nv_equal(out, ref, f"requantize transpose {transpose} mode {mode}")
 
 
+def test_requantize_every_scale_byte(oracle):
+    # a saved tensor that uses every E4M3 byte (subnormals included) and every FP4 code
+    rng = np.random.default_rng(3)
+    rows, cols = 256, 128
+    saved = oracle.NVFP4(rng.integers(0, 256, (rows, cols // 2)).astype(np.uint8),
+                         (np.arange(rows * cols // 16) % 127).astype(np.uint8).reshape(rows, cols // 16),
+                         np.array([0.0123], np.float32))
+    dev_saved = nv_to_dev(saved)
+    for transpose, shape in ((True, (cols, rows)), (False, (rows, cols))):
+        out = qii.NVFP4Tensor.empty(*shape)
+        qii.qii_requantize_nvfp4(dev_saved, transpose, qii.MS_EDEN, 128, 61, 62, None, out, ws(256))
+        ref = oracle.requantize(saved, oracle.MS_EDEN, transpose=transpose, seed_rht=61, seed_sr=62)
+        assert_nv_equal(out, ref, f"every scale byte, transpose {transpose}")
+
+
 def test_degenerate_tensors(oracle):
     z = np.zeros((8, 256), dtype=np.float32)
     for mode in MODES:
