@@ -180,6 +180,13 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const uint8_t *__restrict_
                         acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ti], fb[tj], acc[ti][tj], 0, 0, 0);
             }
         }
+        // ask the scheduler to slot the dequantization (VALU) of the next fragments under the
+        // matrix instructions: one MFMA, then five VALU ops, over the whole K tile
+#pragma unroll
+        for (int i = 0; i < 128; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+        }
         if (kt + 1 < ktiles) {
             store_tile(st, stage_ptr(smem, (int)((kt + 1) & 1)));
             __syncthreads();
