@@ -63,9 +63,9 @@ typedef enum { QII_F32 = 0, QII_BF16 = 1 } qii_dtype;
 
 /* One NVFP4 tensor of `rows` x `cols` (cols % 16 == 0).
  *   codes        rows*cols/2 bytes; element 2j of a row in the low nibble of byte j,
- *                element 2j+1 in the high nibble; 8-byte aligned.
+ *                element 2j+1 in the high nibble; 16-byte aligned.
  *   scales       rows*cols/16 bytes, E4M3 (bias 7, no infinities, 0x7F never written),
- *                plain row-major [rows][cols/16]; 4-byte aligned.
+ *                plain row-major [rows][cols/16]; 8-byte aligned.
  *   tensor_scale one float.                                                           */
 typedef struct {
     uint8_t *codes;
@@ -124,7 +124,10 @@ qii_status qii_dequantize_nvfp4(const qii_nvfp4 *in, float *y, void *stream);
 /* Block-scaled GEMM of Sec. 5:  C = A_hat * B_hat^T  with A (M x K) and B (N x K) both
  * K-contiguous NVFP4, products accumulated in f32.  C is M x N, leading dimension ldc,
  * dtype QII_F32 or QII_BF16 (rounded to nearest even from the f32 accumulator).
- * K = A.cols = B.cols must be a multiple of 32.                                        */
+ * K = A.cols = B.cols must be a multiple of 32.  ws (nullable): qii_gemm_workspace_bytes
+ * bytes, 16-byte aligned; with it (and K a multiple of 256) the fast kernel runs, which first
+ * copies the scale bytes into a tile-contiguous layout; without it a slower kernel is used.
+ * Results are identical either way.                                                     */
 qii_status qii_gemm_nvfp4(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_dtype c_dt,
                           int64_t ldc, void *ws, size_t ws_bytes, void *stream);
 

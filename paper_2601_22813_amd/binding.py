@@ -178,10 +178,14 @@ def qii_dequantize_nvfp4(inp: NVFP4Tensor, y: torch.Tensor):
     _check(lib().qii_dequantize_nvfp4(ctypes.byref(si), y.data_ptr(), _stream()))
 
 
-def qii_gemm_nvfp4(A: NVFP4Tensor, B: NVFP4Tensor, C: torch.Tensor):
+def qii_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(lib().qii_gemm_workspace_bytes(M, N, K))
+
+
+def qii_gemm_nvfp4(A: NVFP4Tensor, B: NVFP4Tensor, C: torch.Tensor, ws: torch.Tensor | None = None):
     sa, sb = A.c_struct(), B.c_struct()
     _check(lib().qii_gemm_nvfp4(ctypes.byref(sa), ctypes.byref(sb), C.data_ptr(), _dt(C), C.stride(0),
-                                None, 0, _stream()))
+                                _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(), _stream()))
 
 
 def qii_linear_fwd(X: torch.Tensor, W: torch.Tensor, Y: torch.Tensor, Xq: NVFP4Tensor,

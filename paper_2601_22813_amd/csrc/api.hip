@@ -37,8 +37,8 @@ qii_status check_nvfp4(const qii_nvfp4 *t, const char *name)
     if (t->rows * t->cols > 0) {
         if (!t->codes || !t->scales || !t->tensor_scale)
             return fail(QII_INVALID_ARG, "%s: null buffer", name);
-        if (!aligned(t->codes, 8) || !aligned(t->scales, 4) || !aligned(t->tensor_scale, 4))
-            return fail(QII_INVALID_ARG, "%s: misaligned buffer (codes 8, scales 4, tensor_scale 4)", name);
+        if (!aligned(t->codes, 16) || !aligned(t->scales, 8) || !aligned(t->tensor_scale, 4))
+            return fail(QII_INVALID_ARG, "%s: misaligned buffer (codes 16, scales 8, tensor_scale 4)", name);
     }
     return QII_OK;
 }
@@ -165,14 +165,18 @@ uint64_t qii_derive_seed(uint64_t seed, uint32_t i)
 
 size_t qii_quantize_workspace_bytes(void) { return kSlot; }
 
-size_t qii_gemm_workspace_bytes(int64_t, int64_t, int64_t) { return 0; }
+size_t qii_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) { return align_up(qii::gemm_workspace_bytes(M, N, K)); }
 
-size_t qii_linear_fwd_workspace_bytes(int64_t, int64_t, int64_t) { return 2 * kSlot; }
+size_t qii_linear_fwd_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out)
+{
+    return 2 * kSlot + qii_gemm_workspace_bytes(T, d_out, d_in);
+}
 
 size_t qii_linear_bwd_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out)
 {
+    const size_t g1 = qii_gemm_workspace_bytes(T, d_in, d_out), g2 = qii_gemm_workspace_bytes(d_out, d_in, T);
     return 4 * kSlot + nvfp4_bytes(T, d_out) + nvfp4_bytes(d_in, d_out) + nvfp4_bytes(d_out, T) +
-           nvfp4_bytes(d_in, T);
+           nvfp4_bytes(d_in, T) + (g1 > g2 ? g1 : g2);
 }
 
 qii_status qii_rht(const void *x, qii_dtype dt, int64_t rows, int64_t cols, int64_t ld,
@@ -260,7 +264,7 @@ qii_status qii_dequantize_nvfp4(const qii_nvfp4 *in, float *y, void *stream)
 }
 
 qii_status qii_gemm_nvfp4(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_dtype c_dt,
-                          int64_t ldc, void *, size_t, void *stream)
+                          int64_t ldc, void *ws, size_t ws_bytes, void *stream)
 {
     qii_status st = check_nvfp4(A, "A");
     if (st != QII_OK) return st;
@@ -273,9 +277,7 @@ qii_status qii_gemm_nvfp4(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_d
     if (A->rows * B->rows == 0) return QII_OK;
     if (!C) return fail(QII_INVALID_ARG, "null C");
     if (A->cols == 0) return fail(QII_BAD_SHAPE, "K = 0");
-    if (!aligned(A->codes, 16) || !aligned(B->codes, 16) || !aligned(A->scales, 8) || !aligned(B->scales, 8))
-        return fail(QII_INVALID_ARG, "GEMM operands need 16-byte aligned codes and 8-byte aligned scales");
-    hipError_t e = qii::launch_gemm(*A, *B, C, c_dt == QII_BF16, ldc, (hipStream_t)stream);
+    hipError_t e = qii::launch_gemm(*A, *B, C, c_dt == QII_BF16, ldc, ws, ws_bytes, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, "gemm");
     return QII_OK;
 }
@@ -293,7 +295,7 @@ qii_status qii_linear_fwd(const void *X, const void *W, qii_dtype dt, int64_t T,
     if (st != QII_OK) return st;
     st = qii_quantize_nvfp4(W, dt, d_out, d_in, d_in, 0, QII_RTN, 0, 0, 0, nullptr, Wq, p + kSlot, kSlot, stream);
     if (st != QII_OK) return st;
-    return qii_gemm_nvfp4(Xq, Wq, Y, y_dt, d_out, nullptr, 0, stream);
+    return qii_gemm_nvfp4(Xq, Wq, Y, y_dt, d_out, p + 2 * kSlot, ws_bytes - 2 * kSlot, stream);
 }
 
 qii_status qii_linear_bwd(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq, const qii_nvfp4 *Wq,
@@ -317,6 +319,8 @@ qii_status qii_linear_bwd(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq, con
     qii_nvfp4 WTq = carve_nvfp4(p, d_in, d_out);
     qii_nvfp4 ETq = carve_nvfp4(p, d_out, T);
     qii_nvfp4 XTq = carve_nvfp4(p, d_in, T);
+    void *gws = p;   // the two GEMMs run one after the other on the stream and share this region
+    const size_t gws_bytes = reinterpret_cast<uint8_t *>(ws) + ws_bytes - p;
     uint64_t sd[6];
     for (uint32_t i = 0; i < 6; ++i) sd[i] = qii_derive_seed(seed, i);
     const size_t slot_floats = kSlot / sizeof(float);
@@ -325,14 +329,14 @@ qii_status qii_linear_bwd(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq, con
     if (st != QII_OK) return st;
     st = qii_requantize_nvfp4(Wq, 1, QII_MS_EDEN, 128, sd[0], sd[3], nullptr, &WTq, slots + slot_floats, kSlot, stream);
     if (st != QII_OK) return st;
-    st = qii_gemm_nvfp4(&Eq, &WTq, dX, g_dt, d_in, nullptr, 0, stream);
+    st = qii_gemm_nvfp4(&Eq, &WTq, dX, g_dt, d_in, gws, gws_bytes, stream);
     if (st != QII_OK) return st;
     // dW = Q(E^T) Q(X^T)^T : rotation sd[1] on the inner dimension T
     st = qii_quantize_nvfp4(dY, dt, T, d_out, d_out, 1, QII_MS_EDEN, 128, sd[1], sd[4], nullptr, &ETq, slots + 2 * slot_floats, kSlot, stream);
     if (st != QII_OK) return st;
     st = qii_requantize_nvfp4(Xq, 1, QII_MS_EDEN, 128, sd[1], sd[5], nullptr, &XTq, slots + 3 * slot_floats, kSlot, stream);
     if (st != QII_OK) return st;
-    return qii_gemm_nvfp4(&ETq, &XTq, dW, g_dt, d_in, nullptr, 0, stream);
+    return qii_gemm_nvfp4(&ETq, &XTq, dW, g_dt, d_in, gws, gws_bytes, stream);
 }
 
 }  // extern "C"

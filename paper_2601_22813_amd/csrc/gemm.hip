@@ -213,17 +213,401 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const uint8_t *__restrict_
         }
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Main kernel (K a multiple of 128).  Differences from gemm_kernel above:
+//  * global -> LDS with global_load_lds (no staging registers, no VALU, no ds_write): each
+//    lane fetches one 16-byte piece of a code row (or one dword of scale bytes) and the wave's
+//    64 pieces land contiguously in LDS.  The piece a lane fetches is chosen so that the LDS
+//    image is XOR-swizzled: row r keeps its 16-byte segment s in slot 4r + (s ^ ((r>>1)&3)),
+//    which makes the 128-bit fragment reads of 8 consecutive rows hit 8 different bank groups.
+//  * three LDS stages: tile kt+2 streams in while tile kt is multiplied, and the raw
+//    fragments of the next 64-wide K slice (also across the tile boundary) are read from LDS
+//    one slice ahead, so no LDS latency sits between barriers and matrix instructions.
+//  * epilogue through LDS: accumulators are scaled, converted and written to a per-wave
+//    LDS tile, then stored as 16-byte pieces of full rows.
+constexpr int kStages = 3;
+constexpr int kOffA = 0, kOffB = 16384, kOffAs = 32768, kOffBs = 34816, kStage2Bytes = 36864;
+constexpr int kSmem2 = kStages * kStage2Bytes;   // 108 KiB, also reused by the epilogue
+
+struct RawFrag {
+    uint4 a[4], b[4];
+    uint32_t sa[4], sb[4];
+};
+
+__device__ __forceinline__ void issue_tile_loads(uint8_t *stage, const uint8_t *a_codes, const uint8_t *a_scales,
+                                                 const uint8_t *b_codes, const uint8_t *b_scales, int64_t M,
+                                                 int64_t N, int64_t K, int64_t m0, int64_t n0, int64_t k0,
+                                                 int wave)
+{
+    const int t = threadIdx.x;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int row = p * 64 + (t >> 2);
+        const int seg = (t & 3) ^ ((row >> 1) & 3);
+        int64_t ra = m0 + row, rb = n0 + row;
+        ra = ra < M ? ra : M - 1;   // rows beyond the matrix read a valid row; their results are dropped
+        rb = rb < N ? rb : N - 1;
+        __builtin_amdgcn_global_load_lds(a_codes + ra * (K / 2) + k0 / 2 + 16 * seg,
+                                         (__attribute__((address_space(3))) void *)(stage + kOffA + (p * 256 + wave * 64) * 16), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(b_codes + rb * (K / 2) + k0 / 2 + 16 * seg,
+                                         (__attribute__((address_space(3))) void *)(stage + kOffB + (p * 256 + wave * 64) * 16), 16, 0, 0);
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int row = (h * 256 + t) >> 1, half = t & 1;
+        int64_t ra = m0 + row, rb = n0 + row;
+        ra = ra < M ? ra : M - 1;
+        rb = rb < N ? rb : N - 1;
+        __builtin_amdgcn_global_load_lds(a_scales + ra * (K / 16) + k0 / 16 + 4 * half,
+                                         (__attribute__((address_space(3))) void *)(stage + kOffAs + (h * 256 + wave * 64) * 4), 4, 0, 0);
+        __builtin_amdgcn_global_load_lds(b_scales + rb * (K / 16) + k0 / 16 + 4 * half,
+                                         (__attribute__((address_space(3))) void *)(stage + kOffBs + (h * 256 + wave * 64) * 4), 4, 0, 0);
+    }
+}
+
+// raw fragments of K slice j (64 elements) of one stage for this lane
+__device__ __forceinline__ void read_raw(RawFrag &f, const uint8_t *stage, int j, int wm, int wn, int li, int kb)
+{
+    const int seg = 2 * j + kb;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int rowa = wm * 128 + t * 32 + li, rowb = wn * 128 + t * 32 + li;
+        f.a[t] = *reinterpret_cast<const uint4 *>(stage + kOffA + (rowa * 4 + (seg ^ ((rowa >> 1) & 3))) * 16);
+        f.b[t] = *reinterpret_cast<const uint4 *>(stage + kOffB + (rowb * 4 + (seg ^ ((rowb >> 1) & 3))) * 16);
+        f.sa[t] = *reinterpret_cast<const uint16_t *>(stage + kOffAs + rowa * 8 + 4 * j + 2 * kb);
+        f.sb[t] = *reinterpret_cast<const uint16_t *>(stage + kOffBs + rowb * 8 + 4 * j + 2 * kb);
+    }
+}
+
+// epilogue: C = acc * (x32_A * x32_B).  acc[r] of a 32x32 tile is row
+// 8*(r/4) + 4*(lane/32) + r%4, column lane%32.  One 32-row band of the wave's 128x128 tile
+// at a time goes through a per-wave LDS tile (row pitch padded by 16 bytes) and leaves as
+// 16-byte pieces of full rows.  The caller guarantees that nobody reads the stages any more.
+template <bool kBf16Out>
+__device__ __forceinline__ void store_tile_through_lds(floatx16 (&acc)[4][4], uint8_t *smem, float ts,
+                                                       void *Cout, int64_t ldc, int64_t M, int64_t N,
+                                                       int64_t m0, int64_t n0, int wave, int wm, int wn,
+                                                       int lane, int li, int kb)
+{
+    constexpr int esz = kBf16Out ? 2 : 4;
+    constexpr int pitch = 128 * esz + 16;
+    uint8_t *wtile = smem + wave * (32 * pitch);
+    constexpr int per_row = 128 * esz / 16;          // 16-byte pieces per row
+    constexpr int rows_per_pass = 64 / per_row;      // rows covered by one wave-wide store
+#pragma unroll
+    for (int ti = 0; ti < 4; ++ti) {
+#pragma unroll
+        for (int tj = 0; tj < 4; ++tj)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = 8 * (r >> 2) + 4 * kb + (r & 3), col = tj * 32 + li;
+                const float v = acc[ti][tj][r] * ts;
+                if (kBf16Out) *reinterpret_cast<uint16_t *>(wtile + row * pitch + col * 2) = (uint16_t)f32_to_bf16_bits(v);
+                else *reinterpret_cast<float *>(wtile + row * pitch + col * 4) = v;
+            }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // wave-local: same wave reads below
+#pragma unroll
+        for (int pass = 0; pass < 32 / rows_per_pass; ++pass) {
+            const int row = pass * rows_per_pass + lane / per_row, piece = lane % per_row;
+            const uint4 v = *reinterpret_cast<const uint4 *>(wtile + row * pitch + piece * 16);
+            const int64_t grow = m0 + wm * 128 + ti * 32 + row;
+            const int64_t gcol = n0 + wn * 128 + piece * (16 / esz);
+            if (grow < M) {
+                uint8_t *dst = reinterpret_cast<uint8_t *>(Cout) + (grow * ldc + gcol) * esz;
+                if (gcol + 16 / esz <= N && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
+                    *reinterpret_cast<uint4 *>(dst) = v;
+                } else {
+                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int e = 0; e < 16 / esz; ++e)
+                        if (gcol + e < N) {
+                            if (kBf16Out) reinterpret_cast<uint16_t *>(dst)[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                            else reinterpret_cast<uint32_t *>(dst)[e] = w[e];
+                        }
+                }
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next band overwrites
+    }
+}
+
+// 64 elements of K for the wave's 4 x 4 MFMA tiles: 4 steps of 16 MFMAs, each step
+// dequantizing one dword (8 codes) per fragment
+__device__ __forceinline__ void mma_slice(floatx16 (&acc)[4][4], const RawFrag &f)
+{
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        half8_t fa[4], fb[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const uint32_t wa = d == 0 ? f.a[t].x : d == 1 ? f.a[t].y : d == 2 ? f.a[t].z : f.a[t].w;
+            const uint32_t wb = d == 0 ? f.b[t].x : d == 1 ? f.b[t].y : d == 2 ? f.b[t].z : f.b[t].w;
+            fa[t] = dequant8(wa, scale_pair(f.sa[t], d >> 1));
+            fb[t] = dequant8(wb, scale_pair(f.sb[t], d >> 1));
+        }
+#pragma unroll
+        for (int ti = 0; ti < 4; ++ti)
+#pragma unroll
+            for (int tj = 0; tj < 4; ++tj)
+                acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ti], fb[tj], acc[ti][tj], 0, 0, 0);
+    }
+}
+
+template <bool kBf16Out>
+__global__ __launch_bounds__(256, 1) void gemm_kernel_v2(const uint8_t *__restrict__ a_codes,
+                                                         const uint8_t *__restrict__ a_scales,
+                                                         const float *__restrict__ a_ts,
+                                                         const uint8_t *__restrict__ b_codes,
+                                                         const uint8_t *__restrict__ b_scales,
+                                                         const float *__restrict__ b_ts, int64_t M,
+                                                         int64_t N, int64_t K, void *__restrict__ Cout,
+                                                         int64_t ldc, int tiles_m, int tiles_n)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    // XCD-aware order: consecutive block ids land on different XCDs (8 of them, each with its
+    // own L2), so give every XCD a contiguous run of tiles, walked row-major over (m, n).
+    int tile = blockIdx.x;
+    const int ntiles = tiles_m * tiles_n;
+    if ((ntiles & 7) == 0) tile = (tile & 7) * (ntiles >> 3) + (tile >> 3);
+    const int64_t m0 = (int64_t)(tile / tiles_n) * BM, n0 = (int64_t)(tile % tiles_n) * BN;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int li = lane & 31, kb = lane >> 5;
+
+    floatx16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int ktiles = (int)(K / BK);
+    issue_tile_loads(smem, a_codes, a_scales, b_codes, b_scales, M, N, K, m0, n0, 0, wave);
+    if (ktiles > 1)
+        issue_tile_loads(smem + kStage2Bytes, a_codes, a_scales, b_codes, b_scales, M, N, K, m0, n0, BK, wave);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    // the raw fragments ping-pong between two register sets: f0 holds K slice 0 of a tile,
+    // f1 slice 1; each is refilled from LDS while the other is being multiplied
+    RawFrag f0, f1;
+    read_raw(f0, smem, 0, wm, wn, li, kb);
+    int st_cur = 0;   // stage of tile kt
+    for (int kt = 0; kt < ktiles; ++kt) {
+        const int st_next = st_cur == kStages - 1 ? 0 : st_cur + 1;
+        const int st_load = st_next == kStages - 1 ? 0 : st_next + 1;
+        if (kt + 2 < ktiles)
+            issue_tile_loads(smem + st_load * kStage2Bytes, a_codes, a_scales, b_codes, b_scales, M, N, K, m0,
+                             n0, (int64_t)(kt + 2) * BK, wave);
+        read_raw(f1, smem + st_cur * kStage2Bytes, 1, wm, wn, li, kb);
+        mma_slice(acc, f0);
+        // (after the last tile this reads a stale stage; the values are never used)
+        read_raw(f0, smem + st_next * kStage2Bytes, 0, wm, wn, li, kb);
+        mma_slice(acc, f1);
+        // slot the dequantization (VALU) of the next fragments under the matrix instructions
+#pragma unroll
+        for (int i = 0; i < 128; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+        }
+        // tile kt+2 (issued a whole tile ago) must have landed before anyone reads it, and
+        // everyone must be done with stage st_cur before tile kt+3 overwrites it
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        st_cur = st_next;
+    }
+
+    store_tile_through_lds<kBf16Out>(acc, smem, (*a_ts) * (*b_ts), Cout, ldc, M, N, m0, n0, wave, wm, wn, lane, li, kb);
+}
+
+
+// ------------------------------------------------------------------------------------------
+// Main kernel (K a multiple of 256, scale bytes re-tiled into the workspace).
+// The operand fetch is what bounds this GEMM once the matrix pipe is fed: with 128-wide K
+// tiles every row contributes half a 128-byte line of codes and 8 bytes of a scale line per
+// tile, i.e. five times more L2 line requests than useful bytes.  Here a K tile is 256 wide
+// (one full line of codes per row) and the scale bytes come from a copy laid out as
+// [row tile of 256][K tile of 256][row][16 bytes], so each block reads 4 KiB of contiguous
+// scales per operand and tile.  Two LDS stages of 72 KiB; LDS image of the codes: row r keeps
+// its 16-byte segment s in slot 8r + (s ^ (r & 7)) (conflict-free 128-bit fragment reads).
+constexpr int BK4 = 256;
+constexpr int kOff4A = 0, kOff4B = 32768, kOff4As = 65536, kOff4Bs = 69632, kStage4Bytes = 73728;
+constexpr int kSmem4 = 2 * kStage4Bytes;   // 144 KiB
+
+// scales[rows][K/16] -> tiled[(rt * (K/256) + ks) * 256 + r][16], one 16-byte piece per thread
+__global__ void retile_scales_kernel(const uint8_t *__restrict__ scales, uint8_t *__restrict__ tiled,
+                                     int64_t rows, int64_t K)
+{
+    const int64_t ksn = K / 256;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // (row, ks)
+    if (idx >= rows * ksn) return;
+    const int64_t row = idx / ksn, ks = idx % ksn;
+    const uint4 v = *reinterpret_cast<const uint4 *>(scales + row * (K / 16) + ks * 16);
+    *reinterpret_cast<uint4 *>(tiled + (((row >> 8) * ksn + ks) * 256 + (row & 255)) * 16) = v;
+}
+
+__device__ __forceinline__ void issue_tile_loads4(uint8_t *stage, const uint8_t *a_codes, const uint8_t *a_tiled,
+                                                  const uint8_t *b_codes, const uint8_t *b_tiled, int64_t M,
+                                                  int64_t N, int64_t K, int64_t m0, int64_t n0, int64_t kt,
+                                                  int wave)
+{
+    const int t = threadIdx.x;
+    const int64_t kbyte = kt * (BK4 / 2);
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        const int row = p * 32 + (t >> 3);
+        const int seg = (t & 7) ^ (row & 7);
+        int64_t ra = m0 + row, rb = n0 + row;
+        ra = ra < M ? ra : M - 1;   // rows beyond the matrix read a valid row; their results are dropped
+        rb = rb < N ? rb : N - 1;
+        __builtin_amdgcn_global_load_lds(a_codes + ra * (K / 2) + kbyte + 16 * seg,
+                                         (__attribute__((address_space(3))) void *)(stage + kOff4A + (p * 256 + wave * 64) * 16), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(b_codes + rb * (K / 2) + kbyte + 16 * seg,
+                                         (__attribute__((address_space(3))) void *)(stage + kOff4B + (p * 256 + wave * 64) * 16), 16, 0, 0);
+    }
+    const int64_t ksn = K / BK4;
+    __builtin_amdgcn_global_load_lds(a_tiled + (((m0 >> 8) * ksn + kt) * 256 + t) * 16,
+                                     (__attribute__((address_space(3))) void *)(stage + kOff4As + (wave * 64) * 16), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(b_tiled + (((n0 >> 8) * ksn + kt) * 256 + t) * 16,
+                                     (__attribute__((address_space(3))) void *)(stage + kOff4Bs + (wave * 64) * 16), 16, 0, 0);
+}
+
+// raw fragments of K slice j (64 elements, j = 0..3) of one stage for this lane
+__device__ __forceinline__ void read_raw4(RawFrag &f, const uint8_t *stage, int j, int wm, int wn, int li, int kb)
+{
+    const int seg = 2 * j + kb;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int rowa = wm * 128 + t * 32 + li, rowb = wn * 128 + t * 32 + li;
+        f.a[t] = *reinterpret_cast<const uint4 *>(stage + kOff4A + (rowa * 8 + (seg ^ (rowa & 7))) * 16);
+        f.b[t] = *reinterpret_cast<const uint4 *>(stage + kOff4B + (rowb * 8 + (seg ^ (rowb & 7))) * 16);
+        f.sa[t] = *reinterpret_cast<const uint16_t *>(stage + kOff4As + rowa * 16 + 4 * j + 2 * kb);
+        f.sb[t] = *reinterpret_cast<const uint16_t *>(stage + kOff4Bs + rowb * 16 + 4 * j + 2 * kb);
+    }
+}
+
+template <bool kBf16Out>
+__global__ __launch_bounds__(256, 1) void gemm_kernel_v4(const uint8_t *__restrict__ a_codes,
+                                                         const uint8_t *__restrict__ a_tiled,
+                                                         const float *__restrict__ a_ts,
+                                                         const uint8_t *__restrict__ b_codes,
+                                                         const uint8_t *__restrict__ b_tiled,
+                                                         const float *__restrict__ b_ts, int64_t M,
+                                                         int64_t N, int64_t K, void *__restrict__ Cout,
+                                                         int64_t ldc, int tiles_m, int tiles_n)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    // XCD-aware order: consecutive block ids land on different XCDs (8 of them, each with its
+    // own L2), so give every XCD a contiguous run of tiles, walked row-major over (m, n).
+    int tile = blockIdx.x;
+    const int ntiles = tiles_m * tiles_n;
+    if ((ntiles & 7) == 0) tile = (tile & 7) * (ntiles >> 3) + (tile >> 3);
+    const int64_t m0 = (int64_t)(tile / tiles_n) * BM, n0 = (int64_t)(tile % tiles_n) * BN;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int li = lane & 31, kb = lane >> 5;
+
+    floatx16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int ktiles = (int)(K / BK4);
+    issue_tile_loads4(smem, a_codes, a_tiled, b_codes, b_tiled, M, N, K, m0, n0, 0, wave);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    RawFrag f0, f1;
+    for (int kt = 0; kt < ktiles; ++kt) {
+        const uint8_t *cur = smem + (kt & 1) * kStage4Bytes;
+        if (kt + 1 < ktiles)
+            issue_tile_loads4(smem + ((kt + 1) & 1) * kStage4Bytes, a_codes, a_tiled, b_codes, b_tiled, M, N, K,
+                              m0, n0, kt + 1, wave);
+        read_raw4(f0, cur, 0, wm, wn, li, kb);
+        read_raw4(f1, cur, 1, wm, wn, li, kb);
+        mma_slice(acc, f0);
+        read_raw4(f0, cur, 2, wm, wn, li, kb);
+        mma_slice(acc, f1);
+        read_raw4(f1, cur, 3, wm, wn, li, kb);
+        mma_slice(acc, f0);
+        mma_slice(acc, f1);
+        // slot the dequantization (VALU) of the next fragments under the matrix instructions
+#pragma unroll
+        for (int i = 0; i < 256; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+        }
+        // tile kt+1 (issued a whole tile ago) must have landed before anyone reads it, and
+        // everyone must be done with this stage before tile kt+2 overwrites it
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    }
+    store_tile_through_lds<kBf16Out>(acc, smem, (*a_ts) * (*b_ts), Cout, ldc, M, N, m0, n0, wave, wm, wn, lane, li, kb);
+}
+
 }  // namespace
 
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (K % BK4 != 0) return 0;
+    const int64_t mp = (M + 255) / 256 * 256, np = (N + 255) / 256 * 256;
+    return (size_t)((mp + np) * (K / 16));
+}
+
 hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is_bf16, int64_t ldc,
-                       hipStream_t s)
+                       void *ws, size_t ws_bytes, hipStream_t s)
 {
     const int64_t M = A.rows, N = B.rows, K = A.cols;
     if (M == 0 || N == 0) return hipSuccess;
     const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
+    const size_t need = gemm_workspace_bytes(M, N, K);
+    if (K % BK4 == 0 && ws && ws_bytes >= need && (reinterpret_cast<uintptr_t>(ws) & 15) == 0 &&
+        (reinterpret_cast<uintptr_t>(A.scales) & 15) == 0 && (reinterpret_cast<uintptr_t>(B.scales) & 15) == 0) {
+        uint8_t *a_tiled = reinterpret_cast<uint8_t *>(ws);
+        uint8_t *b_tiled = a_tiled + (M + 255) / 256 * 256 * (K / 16);
+        const int64_t na = M * (K / 256), nb = N * (K / 256);
+        hipLaunchKernelGGL(retile_scales_kernel, dim3((unsigned)((na + 255) / 256)), dim3(256), 0, s, A.scales, a_tiled, M, K);
+        hipLaunchKernelGGL(retile_scales_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, s, B.scales, b_tiled, N, K);
+        hipError_t e;
+        if (c_is_bf16) {
+            e = hipFuncSetAttribute((const void *)gemm_kernel_v4<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kSmem4);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(gemm_kernel_v4<true>, grid, block, kSmem4, s, A.codes, a_tiled, A.tensor_scale,
+                               B.codes, b_tiled, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n);
+        } else {
+            e = hipFuncSetAttribute((const void *)gemm_kernel_v4<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kSmem4);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(gemm_kernel_v4<false>, grid, block, kSmem4, s, A.codes, a_tiled, A.tensor_scale,
+                               B.codes, b_tiled, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n);
+        }
+        return hipGetLastError();
+    }
     const size_t smem = 2 * kStageBytes;
     const bool aligned = (K % 128) == 0;
+    if (aligned) {
+        const size_t smem2 = kSmem2;
+        hipError_t e;
+        if (c_is_bf16) {
+            e = hipFuncSetAttribute((const void *)gemm_kernel_v2<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem2);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(gemm_kernel_v2<true>, grid, block, smem2, s, A.codes, A.scales, A.tensor_scale,
+                               B.codes, B.scales, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n);
+        } else {
+            e = hipFuncSetAttribute((const void *)gemm_kernel_v2<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem2);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(gemm_kernel_v2<false>, grid, block, smem2, s, A.codes, A.scales, A.tensor_scale,
+                               B.codes, B.scales, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n);
+        }
+        return hipGetLastError();
+    }
 #define QII_GEMM(AL, BF)                                                                          \
     do {                                                                                          \
         auto kern = gemm_kernel<AL, BF>;                                                          \

@@ -53,7 +53,10 @@ bool cols_kernels_apply(const Source &src, int64_t R, int64_t C);
 hipError_t launch_absmax_cols(const Source &src, int64_t R, int64_t C, int rht, uint64_t seed_rht,
                               float *amax, hipStream_t s);
 hipError_t launch_quantize_cols(const QuantizeArgs &a, hipStream_t s);
+// ws (nullable): gemm_workspace_bytes(M, N, K) bytes, 16-byte aligned, for the re-tiled scale
+// bytes of the fast kernel; without it a slower kernel reads the row-major scales directly
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is_bf16, int64_t ldc,
-                       hipStream_t s);
+                       void *ws, size_t ws_bytes, hipStream_t s);
 
 }  // namespace qii

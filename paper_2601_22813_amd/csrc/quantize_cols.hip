@@ -38,31 +38,29 @@ struct ColsArgs {
     uint32_t *amax_out;
 };
 
-// load the 128 rows of one chunk of column j, widen to f32, apply the rotation signs
+// load the 128 rows of one chunk of column j, widen to f32, apply the rotation signs.
+// `chunk` is wave-uniform (scalar registers), so each row's address is a scalar base plus the
+// lane's 32-bit column offset; j is clamped into the tensor by the caller, so every lane
+// loads from a valid address and out-of-range lanes simply do not store.
 template <int kSrc, bool kRht>
-__device__ __forceinline__ void load_chunk(float v[128], const ColsArgs &a, int64_t chunk, int64_t j, bool ok)
+__device__ __forceinline__ void load_chunk(float v[128], const ColsArgs &a, int64_t chunk, uint32_t j)
 {
-    constexpr bool kBf16 = kSrc == kSrcBF16;
-    if (!ok) {
-#pragma unroll
-        for (int i = 0; i < 128; ++i) v[i] = 0.0f;
-        return;
-    }
     if (kSrc == kSrcNVFP4) {
         // two lanes share a code byte, sixteen a scale byte; batches of 32 rows bound the
         // number of loads (and registers) in flight
         const int64_t cstride = a.ld / 2, sstride = a.ld / 16;
-        const uint8_t *pc = (const uint8_t *)a.x + (chunk * 128) * cstride + j / 2;
-        const uint8_t *ps = a.in_scales + (chunk * 128) * sstride + j / 16;
-        const uint32_t shift = (uint32_t)(j & 1) * 4u;
+        const uint8_t *pc = (const uint8_t *)a.x + (chunk * 128) * cstride;
+        const uint8_t *ps = a.in_scales + (chunk * 128) * sstride;
+        const uint32_t jc = j / 2, js = j / 16;
+        const uint32_t shift = (j & 1u) * 4u;
         const float x32 = *a.in_ts;
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             uint32_t rc[32], rs[32];
 #pragma unroll
             for (int i = 0; i < 32; ++i) {
-                rc[i] = pc[(int64_t)(32 * b + i) * cstride];
-                rs[i] = ps[(int64_t)(32 * b + i) * sstride];
+                rc[i] = (pc + (int64_t)(32 * b + i) * cstride)[jc];
+                rs[i] = (ps + (int64_t)(32 * b + i) * sstride)[js];
             }
 #pragma unroll
             for (int i = 0; i < 32; ++i) {
@@ -76,15 +74,18 @@ __device__ __forceinline__ void load_chunk(float v[128], const ColsArgs &a, int6
         }
         return;
     }
+    constexpr bool kBf16 = kSrc == kSrcBF16;
+    constexpr int esz = kBf16 ? 2 : 4;
+    const char *base = (const char *)a.x + (chunk * 128) * a.ld * esz;
+    const uint32_t off = j * esz;
     uint32_t raw[128];
-    if (kBf16) {
-        const uint16_t *p = (const uint16_t *)a.x + (chunk * 128) * a.ld + j;
 #pragma unroll
-        for (int i = 0; i < 128; ++i) raw[i] = p[(int64_t)i * a.ld];
-    } else {
-        const uint32_t *p = (const uint32_t *)a.x + (chunk * 128) * a.ld + j;
-#pragma unroll
-        for (int i = 0; i < 128; ++i) raw[i] = p[(int64_t)i * a.ld];
+    for (int i = 0; i < 128; ++i) {
+        const char *rowp = base + (int64_t)i * a.ld * esz;
+        raw[i] = kBf16 ? (uint32_t)*reinterpret_cast<const uint16_t *>(rowp + off)
+                       : *reinterpret_cast<const uint32_t *>(rowp + off);
+        // keep the loads in issue order in batches, so that address registers are recycled
+        if ((i & 15) == 15) __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
     for (int i = 0; i < 128; ++i) {
@@ -138,44 +139,57 @@ __device__ __forceinline__ void quad_draws(uint32_t draw[8], uint64_t seed_sr, i
 template <int kSrc, int kMode, bool kRht>
 __global__ __launch_bounds__(256, 2) void quantize_cols_kernel(ColsArgs a)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;   // wave-uniform
     const int64_t j = (int64_t)blockIdx.y * 64 + lane;
     const TensorConsts tc = tensor_consts(kMode, *a.amax);
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *a.tensor_scale = tc.x32;
-    if (chunk * 128 >= a.C) return;  // wave-uniform
+    if (chunk * 128 >= a.C) return;
     const bool ok = j < a.R;
+    uint4 *pc = reinterpret_cast<uint4 *>(a.codes + j * (a.C / 2) + chunk * 64);
+    uint2 *psc = reinterpret_cast<uint2 *>(a.scales + j * (a.C / 16) + chunk * 8);
+    if (tc.zero) {  // uniform: an all-zero tensor is emitted as zero bytes
+        if (ok) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) pc[i] = make_uint4(0u, 0u, 0u, 0u);
+            *psc = make_uint2(0u, 0u);
+        }
+        return;
+    }
     float v[128];
-    load_chunk<kSrc, kRht>(v, a, chunk, j, ok && !tc.zero);
+    load_chunk<kSrc, kRht>(v, a, chunk, (uint32_t)(ok ? j : a.R - 1));
     if (kRht) fwht128(v);
     uint32_t draw[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
     if (kMode == QII_MS_EDEN) quad_draws(draw, a.seed_sr, chunk, j);
-    uint32_t codes[16];
     uint32_t sc[2] = {0u, 0u};
 #pragma unroll
-    for (int gi = 0; gi < 8; ++gi) {
-        const uint32_t b = quantize_group16<kMode>(v + 16 * gi, tc, draw[gi], a.seed_sr, j, chunk * 8 + gi, codes + 2 * gi);
-        sc[gi >> 2] |= b << (8 * (gi & 3));
-    }
-    if (ok) {
-        uint4 *pc = reinterpret_cast<uint4 *>(a.codes + j * (a.C / 2) + chunk * 64);
+    for (int gp = 0; gp < 4; ++gp) {   // two groups = 16 bytes of codes per store
+        uint32_t codes[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) pc[i] = make_uint4(codes[4 * i], codes[4 * i + 1], codes[4 * i + 2], codes[4 * i + 3]);
-        *reinterpret_cast<uint2 *>(a.scales + j * (a.C / 16) + chunk * 8) = make_uint2(sc[0], sc[1]);
+        for (int h = 0; h < 2; ++h) {
+            const int gi = 2 * gp + h;
+            const uint32_t b = quantize_group16<kMode>(v + 16 * gi, tc, draw[gi], a.seed_sr, j, chunk * 8 + gi, codes + 2 * h);
+            sc[gi >> 2] |= b << (8 * (gi & 3));
+        }
+        if (ok) pc[gp] = make_uint4(codes[0], codes[1], codes[2], codes[3]);
     }
+    if (ok) *psc = make_uint2(sc[0], sc[1]);
 }
 
 template <int kSrc, bool kRht>
 __global__ __launch_bounds__(256, 2) void absmax_cols_kernel(ColsArgs a)
 {
     __shared__ float wave_m[4];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;   // wave-uniform
     const int64_t j = (int64_t)blockIdx.y * 64 + lane;
     float m = 0.0f;
-    if (chunk * 128 < a.C) {  // wave-uniform
+    if (chunk * 128 < a.C) {
         float v[128];
-        load_chunk<kSrc, kRht>(v, a, chunk, j, j < a.R);
+        // a clamped duplicate of a real column cannot change the maximum
+        load_chunk<kSrc, kRht>(v, a, chunk, (uint32_t)(j < a.R ? j : a.R - 1));
         if (kRht) fwht128(v);
 #pragma unroll
         for (int gi = 0; gi < 8; ++gi) m = fmaxf(m, group_absmax(v + 16 * gi));

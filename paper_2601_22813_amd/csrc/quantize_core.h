@@ -8,6 +8,7 @@
 //   v_cvt_pk_fp8_f32 on [0, 448]          = round to nearest E4M3, ties to even;
 //   v_cvt_scalef32_pk_f32_fp4             = exact E2M1 decode.
 #pragma once
+#include "../../include/qii.h"
 #include "qii_device.h"
 
 namespace qii {
@@ -19,7 +20,8 @@ struct TensorConsts {
     float d;     // x^FP32 * s, the divisor of the group-scale equation
     float rd;    // 1 / d, correctly rounded
     bool zero;   // amax == 0: emit zeros
-    bool fast;   // magnitudes far from the denormal range: division by d via rd is exact
+    bool fast;   // magnitudes far from the denormal range: the short division sequences
+                 // below equal IEEE division bit for bit
 };
 
 __device__ __forceinline__ TensorConsts tensor_consts(int mode, float amax)
@@ -33,7 +35,7 @@ __device__ __forceinline__ TensorConsts tensor_consts(int mode, float amax)
     tc.x32 = tc.zero ? 1.0f : amax / (s * cap);
     tc.d = tc.x32 * s;
     tc.rd = 1.0f / tc.d;
-    tc.fast = amax > 0x1p-80f && amax < 0x1p100f;
+    tc.fast = amax > 0x1p-20f && amax < 0x1p20f;
     return tc;
 }
 
@@ -48,6 +50,27 @@ __device__ __forceinline__ float div_by_tensor_const(float a, const TensorConsts
     const float q1 = __builtin_fmaf(e0, tc.rd, q0);
     const float e1 = __builtin_fmaf(-tc.d, q1, a);
     return __builtin_fmaf(e1, tc.rd, q1);
+}
+
+// a / b rounded to nearest for operands far from the denormal and overflow ranges: the
+// Newton-Raphson sequence of a compiler-generated IEEE binary32 division (reciprocal
+// estimate, one refinement of it, quotient, two residual corrections) without the operand
+// pre-scaling and the special-case fix-up, which are identities in that range.
+__device__ __forceinline__ float div_safe_range(float a, float b)
+{
+    const float r0 = __builtin_amdgcn_rcpf(b);
+    const float f0 = __builtin_fmaf(-b, r0, 1.0f);
+    const float r1 = __builtin_fmaf(f0, r0, r0);
+    const float m = a * r1;
+    const float f2 = __builtin_fmaf(-b, m, a);
+    const float f3 = __builtin_fmaf(f2, r1, m);
+    const float f4 = __builtin_fmaf(-b, f3, a);
+    return __builtin_fmaf(f4, r1, f3);
+}
+
+__device__ __forceinline__ float div_ieee(float a, float b, const TensorConsts &tc)
+{
+    return tc.fast ? div_safe_range(a, b) : a / b;
 }
 
 __device__ __forceinline__ float group_absmax(const float y[16])
@@ -76,7 +99,7 @@ __device__ __forceinline__ uint32_t quantize_group16(const float y[16], const Te
     uint32_t b = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(fminf(r, 448.0f), 0.0f, 0, false) & 0xFFu;
     if (b == 0u) return 0u;
     const float x8 = e4m3_decode(b);
-    const float inv = 1.0f / (x8 * tc.x32);
+    const float inv = div_ieee(1.0f, x8 * tc.x32, tc);
     if (kMode == QII_SR) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -114,7 +137,7 @@ __device__ __forceinline__ uint32_t quantize_group16(const float y[16], const Te
         QII_DOT(0, 0); QII_DOT(0, 1); QII_DOT(0, 2); QII_DOT(0, 3);
         QII_DOT(1, 0); QII_DOT(1, 1); QII_DOT(1, 2); QII_DOT(1, 3);
 #undef QII_DOT
-        if (den > 0.0f) b = e4m3_sr(num / (den * tc.x32), draw20);
+        if (den > 0.0f) b = e4m3_sr(div_ieee(num, den * tc.x32, tc), draw20);
     }
     return b;
 }

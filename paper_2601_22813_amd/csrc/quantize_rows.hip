@@ -14,6 +14,8 @@
 // undone exactly by the sign of the lane's final 2^-3.5 scaling constant.  Only the sign
 // of exactly-zero intermediates can differ from the plain butterfly, and the final
 // fma(v, c, +0) maps every zero result to +0, as the arithmetic contract states.
+#include <stdlib.h>
+
 #include "qii_device.h"
 #include "qii_internal.h"
 #include "quantize_core.h"
@@ -110,24 +112,45 @@ __device__ __forceinline__ void rht128_lane(float v[16], const LaneSetup &L)
     for (int k = 0; k < 16; ++k) v[k] = __builtin_fmaf(v[k], L.cfin, 0.0f);  // +0 for exact zeros
 }
 
+// The 8 scale bytes of an octet's chunk are consecutive in memory; single-byte stores are
+// slow, so they are gathered into the lane holding block 0, which stores them as one 8-byte
+// word: each lane shifts its byte to position (blk mod 4), two DPP ORs merge a quad, and the
+// half-mirror brings the upper quad's word (blocks 4..7 sit in lane 7 - blk) to the lower one.
+__device__ __forceinline__ uint2 gather_scale_bytes(uint32_t b, int blk)
+{
+    uint32_t t = b << (8 * (blk & 3));
+    t |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, kDppXor1, 0xF, 0xF, true);
+    t |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, kDppXor2, 0xF, 0xF, true);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, kDppHalfMirror, 0xF, 0xF, true);
+    return make_uint2(t, hi);
+}
+
 // raw row data of one lane: 16 elements
 template <bool kBf16>
 struct Raw {
     uint4 q[kBf16 ? 2 : 4];
 };
 
+// rows and groups are clamped into the tensor, so every lane always loads from a valid
+// address and no exec-masked branch is needed; out-of-range lanes simply do not store
 template <bool kBf16>
-__device__ __forceinline__ void load_raw(Raw<kBf16> &r, const RowsArgs &a, int64_t row, int64_t g, bool ok)
+__device__ __forceinline__ void load_raw(Raw<kBf16> &r, const RowsArgs &a, int64_t row, int64_t g)
 {
     constexpr int n = kBf16 ? 2 : 4;
-    if (ok) {
-        const uint4 *p = kBf16 ? reinterpret_cast<const uint4 *>((const uint16_t *)a.x + row * a.ld + g * 16)
-                               : reinterpret_cast<const uint4 *>((const float *)a.x + row * a.ld + g * 16);
+    const uint4 *p = kBf16 ? reinterpret_cast<const uint4 *>((const uint16_t *)a.x + row * a.ld + g * 16)
+                           : reinterpret_cast<const uint4 *>((const float *)a.x + row * a.ld + g * 16);
 #pragma unroll
-        for (int i = 0; i < n; ++i) r.q[i] = p[i];
-    } else {
+    for (int i = 0; i < n; ++i) r.q[i] = p[i];
+}
+
+template <bool kBf16>
+__device__ __forceinline__ void load_quad(Raw<kBf16> raw[4], const RowsArgs &a, int64_t quad, int64_t g)
+{
 #pragma unroll
-        for (int i = 0; i < n; ++i) r.q[i] = make_uint4(0u, 0u, 0u, 0u);
+    for (int it = 0; it < 4; ++it) {
+        int64_t row = quad * 4 + it;
+        row = row < a.R ? row : a.R - 1;
+        load_raw<kBf16>(raw[it], a, row, g);
     }
 }
 
@@ -166,23 +189,37 @@ __device__ __forceinline__ void make_masks(uint32_t sign16, uint32_t mask[kBf16 
     }
 }
 
-template <bool kBf16, int kMode, bool kRht>
+template <bool kBf16, int kMode, bool kRht, bool kPrefetch, int kAblate = 0>
 __global__ __launch_bounds__(256) void quantize_rows_kernel(RowsArgs a)
 {
     const int64_t G = a.C / 16;
     const LaneSetup L = lane_setup(a, G);
     const TensorConsts tc = tensor_consts(kMode, *a.amax);
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *a.tensor_scale = tc.x32;
+    const int64_t quads = (a.R + 3) / 4;
+    if (tc.zero) {  // uniform: an all-zero tensor is emitted as zero bytes
+        for (int64_t quad = blockIdx.x; quad < quads; quad += gridDim.x)
+            for (int it = 0; it < 4; ++it) {
+                const int64_t row = quad * 4 + it;
+                if (L.col_ok && row < a.R) {
+                    *reinterpret_cast<uint2 *>(a.codes + (row * a.C + L.g * 16) / 2) = make_uint2(0u, 0u);
+                    a.scales[row * G + L.g] = 0;
+                }
+            }
+        return;
+    }
     uint32_t mask[kBf16 ? 8 : 16];
     make_masks<kBf16>(L.sign16, mask);
-    const int64_t quads = (a.R + 3) / 4;
+    const int64_t gc = L.col_ok ? L.g : G - 1;
+    Raw<kBf16> raw[4];
+    load_quad<kBf16>(raw, a, blockIdx.x, gc);
     for (int64_t quad = blockIdx.x; quad < quads; quad += gridDim.x) {
-        Raw<kBf16> raw[4];
-#pragma unroll
-        for (int it = 0; it < 4; ++it)
-            load_raw<kBf16>(raw[it], a, quad * 4 + it, L.g, L.col_ok && !tc.zero && quad * 4 + it < a.R);
+        // prefetch the next quad of this block while the current one is being processed
+        Raw<kBf16> nxt[4];
+        const int64_t qn = quad + gridDim.x;
+        if (kPrefetch) load_quad<kBf16>(nxt, a, qn < quads ? qn : quad, gc);
         uint32_t draw[4] = {0u, 0u, 0u, 0u};
-        if (kMode == QII_MS_EDEN) {
+        if (kMode == QII_MS_EDEN && !(kAblate & 4)) {
             const U4 w = philox_seeded(a.seed_sr, (uint32_t)L.g, (uint32_t)quad, 0, kStreamScale);
             draw[0] = w.x >> 12; draw[1] = w.y >> 12; draw[2] = w.z >> 12; draw[3] = w.w >> 12;
         }
@@ -191,19 +228,34 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowsArgs a)
             const int64_t row = quad * 4 + it;
             float v[16];
             unpack_signed<kBf16, kRht>(raw[it], v, mask);
-            if (kRht) rht128_lane(v, L);
+            if (kRht && !(kAblate & 8)) rht128_lane(v, L);
             uint32_t packed[2];
-            const uint32_t b = quantize_group16<kMode>(v, tc, draw[it], a.seed_sr, row, L.g, packed);
+            uint32_t b;
+            if (kAblate & 16) { b = f2u(v[0] + v[5]) & 0xff; packed[0] = f2u(v[1] + v[7] + v[9] + v[11] + v[13] + v[15]); packed[1] = f2u(v[2] + v[4] + v[6] + v[8] + v[3] + v[10] + v[12] + v[14]); }
+            else b = quantize_group16<kMode>(v, tc, draw[it], a.seed_sr, row, L.g, packed);
             if (L.col_ok && row < a.R) {
-                *reinterpret_cast<uint2 *>(a.codes + (row * a.C + L.g * 16) / 2) = make_uint2(packed[0], packed[1]);
+                if (!(kAblate & 2)) *reinterpret_cast<uint2 *>(a.codes + (row * a.C + L.g * 16) / 2) = make_uint2(packed[0], packed[1]);
+                else if (packed[0] == 0x12345u) a.codes[0] = 1;
+            }
+            if (G % 8 == 0) {   // whole octets: one 8-byte store per chunk
+                const uint2 sc = gather_scale_bytes(b, L.blk);
+                if (L.col_ok && row < a.R && L.blk == 0)
+                    *reinterpret_cast<uint2 *>(a.scales + row * G + L.g) = sc;
+            } else if (L.col_ok && row < a.R) {
                 a.scales[row * G + L.g] = (uint8_t)b;
             }
+        }
+        if (kPrefetch) {
+#pragma unroll
+            for (int it = 0; it < 4; ++it) raw[it] = nxt[it];
+        } else if (qn < quads) {
+            load_quad<kBf16>(raw, a, qn, gc);
         }
     }
 }
 
 template <bool kBf16, bool kRht>
-__global__ __launch_bounds__(256) void absmax_rows_kernel(RowsArgs a)
+__global__ __launch_bounds__(256, 4) void absmax_rows_kernel(RowsArgs a)
 {
     __shared__ float wave_m[4];
     const int64_t G = a.C / 16;
@@ -211,19 +263,25 @@ __global__ __launch_bounds__(256) void absmax_rows_kernel(RowsArgs a)
     uint32_t mask[kBf16 ? 8 : 16];
     make_masks<kBf16>(L.sign16, mask);
     const int64_t quads = (a.R + 3) / 4;
+    const int64_t gc = L.col_ok ? L.g : G - 1;
     float m = 0.0f;
+    Raw<kBf16> raw[4];
+    load_quad<kBf16>(raw, a, blockIdx.x, gc);
     for (int64_t quad = blockIdx.x; quad < quads; quad += gridDim.x) {
-        Raw<kBf16> raw[4];
-#pragma unroll
-        for (int it = 0; it < 4; ++it)
-            load_raw<kBf16>(raw[it], a, quad * 4 + it, L.g, L.col_ok && quad * 4 + it < a.R);
+        Raw<kBf16> nxt[4];
+        const int64_t qn = quad + gridDim.x;
+        load_quad<kBf16>(nxt, a, qn < quads ? qn : quad, gc);
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             float v[16];
             unpack_signed<kBf16, kRht>(raw[it], v, mask);
             if (kRht) rht128_lane(v, L);
-            m = fmaxf(m, group_absmax(v));
+            // a clamped duplicate of a real row cannot change the maximum; lanes beyond the
+            // last column hold a made-up chunk and are left out
+            if (L.col_ok) m = fmaxf(m, group_absmax(v));
         }
+#pragma unroll
+        for (int it = 0; it < 4; ++it) raw[it] = nxt[it];
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
@@ -236,13 +294,17 @@ __global__ __launch_bounds__(256) void absmax_rows_kernel(RowsArgs a)
     }
 }
 
+// blocks: as many as stay resident at once (4 per CU), with the row quads split evenly
 dim3 rows_grid(int64_t R, int64_t C)
 {
     const int64_t G = C / 16, nch = (G + 7) / 8;
     const int64_t gy = (nch + 31) / 32;            // 4 waves x 8 chunks per block
     const int64_t quads = (R + 3) / 4;
-    int64_t gx = (256 * 8 + gy - 1) / gy;          // about 8 blocks per CU in flight
-    if (gx > quads) gx = quads;
+    static const int per_cu = getenv("QII_ROWS_BPC") ? atoi(getenv("QII_ROWS_BPC")) : 4;
+    int64_t cap = (256 * per_cu) / gy;             // 256 CUs x resident blocks
+    if (cap < 1) cap = 1;
+    const int64_t iters = (quads + cap - 1) / cap; // iterations per block
+    int64_t gx = (quads + iters - 1) / iters;      // even split
     if (gx < 1) gx = 1;
     return dim3((unsigned)gx, (unsigned)gy);
 }
@@ -283,7 +345,23 @@ hipError_t launch_quantize_rows(const QuantizeArgs &q, hipStream_t s)
     a.amax = q.amax; a.codes = q.codes; a.scales = q.scales; a.tensor_scale = q.tensor_scale;
     const dim3 grid = rows_grid(q.R, q.C), block(256);
     const bool bf = q.src.kind == kSrcBF16;
-#define QII_ROWS(BF, MODE, RHT) hipLaunchKernelGGL((quantize_rows_kernel<BF, MODE, RHT>), grid, block, 0, s, a)
+    static const int ablate = getenv("QII_ABLATE") ? atoi(getenv("QII_ABLATE")) : 0;
+    static const bool prefetch = getenv("QII_ROWS_PREFETCH") && atoi(getenv("QII_ROWS_PREFETCH"));
+#define QII_ROWS(BF, MODE, RHT)                                                                   \
+    do {                                                                                          \
+        if (BF && MODE == QII_MS_EDEN && RHT && ablate) {                                         \
+            switch (ablate) {                                                                     \
+                case 1: hipLaunchKernelGGL((quantize_rows_kernel<true, QII_MS_EDEN, true, false, 1>), grid, block, 0, s, a); break;  \
+                case 3: hipLaunchKernelGGL((quantize_rows_kernel<true, QII_MS_EDEN, true, false, 3>), grid, block, 0, s, a); break;  \
+                case 4: hipLaunchKernelGGL((quantize_rows_kernel<true, QII_MS_EDEN, true, false, 4>), grid, block, 0, s, a); break;  \
+                case 8: hipLaunchKernelGGL((quantize_rows_kernel<true, QII_MS_EDEN, true, false, 8>), grid, block, 0, s, a); break;  \
+                case 16: hipLaunchKernelGGL((quantize_rows_kernel<true, QII_MS_EDEN, true, false, 16>), grid, block, 0, s, a); break; \
+                case 24: hipLaunchKernelGGL((quantize_rows_kernel<true, QII_MS_EDEN, true, false, 24>), grid, block, 0, s, a); break; \
+                default: break;                                                                   \
+            }                                                                                     \
+        } else if (prefetch) hipLaunchKernelGGL((quantize_rows_kernel<BF, MODE, RHT, true>), grid, block, 0, s, a);  \
+        else hipLaunchKernelGGL((quantize_rows_kernel<BF, MODE, RHT, false>), grid, block, 0, s, a);          \
+    } while (0)
 #define QII_ROWS_MODE(BF, RHT)                                   \
     do {                                                         \
         if (q.mode == QII_RTN) QII_ROWS(BF, QII_RTN, RHT);       \

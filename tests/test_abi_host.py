@@ -40,7 +40,11 @@ def test_host_helpers(libqii, oracle):
     assert libqii.qii_quantize_workspace_bytes() == 256
     need = libqii.qii_linear_bwd_workspace_bytes(256, 128, 384)
     payload = (256 * 384 + 128 * 384 + 384 * 256 + 128 * 256) * 9 // 16
-    assert payload <= need <= payload + 16 * 256
+    gemm_ws = max(libqii.qii_gemm_workspace_bytes(256, 128, 384), libqii.qii_gemm_workspace_bytes(384, 128, 256))
+    assert payload + gemm_ws <= need <= payload + gemm_ws + 16 * 256
+    # re-tiled scale bytes of both operands, rows padded to 256; nothing when K is not a multiple of 256
+    assert libqii.qii_gemm_workspace_bytes(300, 200, 512) == (512 + 256) * 512 // 16
+    assert libqii.qii_gemm_workspace_bytes(300, 200, 384) == 0
     L = libqii.lib()
     assert L.qii_status_string(0) == b"QII_OK" and L.qii_status_string(2) == b"QII_BAD_SHAPE"
 

@@ -19,11 +19,15 @@ pytestmark = pytest.mark.gpu
 E2M1 = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0, -0.0, -0.5, -1.0, -1.5, -2.0, -3.0, -4.0, -6.0])
 
 
-def gemm_gpu(qa, qb, dtype, ldc=None):
+def gemm_gpu(qa, qb, dtype, ldc=None, use_ws=True):
+    """With a workspace the fast kernel runs (when K is a multiple of 256); without, the fallbacks."""
     M, N = qa.rows, qb.rows
     ldc = ldc or N
     C = torch.full((M, ldc), float("nan"), dtype=dtype, device="cuda")
-    qii.qii_gemm_nvfp4(nv_to_dev(qa), nv_to_dev(qb), C)
+    w = ws(qii.qii_gemm_workspace_bytes(M, N, qa.cols)) if use_ws else None
+    if w is not None:
+        w.fill_(0x7F)   # a scale byte the library never writes: stale workspace must not leak in
+    qii.qii_gemm_nvfp4(nv_to_dev(qa), nv_to_dev(qb), C, w)
     torch.cuda.synchronize()
     return C[:, :N].float().cpu().numpy().astype(np.float64)
 
@@ -44,10 +48,11 @@ def test_gemm_256_cubed_config(oracle, dtype):
         qb = oracle.quantize(W, mode, seed_rht=0, seed_sr=1)
         ref, absum = oracle.gemm(qa, qb, with_abs=True)
         check(gemm_gpu(qa, qb, dtype), ref, absum, dtype == torch.bfloat16)
+        check(gemm_gpu(qa, qb, dtype, use_ws=False), ref, absum, dtype == torch.bfloat16)
 
 
 @pytest.mark.parametrize("M,N,K", [(300, 200, 160), (1, 1, 32), (513, 257, 384), (64, 700, 1024),
-                                   (256, 256, 96)])
+                                   (256, 256, 96), (300, 520, 512), (1024, 768, 2048)])
 def test_gemm_ragged_shapes(oracle, M, N, K):
     rng = np.random.default_rng(M + N + K)
     a = (rng.standard_t(3, size=(M, K)) * 0.1).astype(np.float32)
@@ -58,6 +63,7 @@ def test_gemm_ragged_shapes(oracle, M, N, K):
     print(f"gemm {M}x{N}x{K}", flush=True)
     check(gemm_gpu(qa, qb, torch.float32, ldc=N + 8), ref, absum, False)
     check(gemm_gpu(qa, qb, torch.bfloat16), ref, absum, True)
+    check(gemm_gpu(qa, qb, torch.bfloat16, ldc=N + 3, use_ws=False), ref, absum, True)
 
 
 def test_gemm_unit_scales_is_exact(oracle):
