@@ -4,16 +4,18 @@
 // re-quantization of a saved NVFP4 tensor with transposition (Q(W^T), Q(X^T)), where the
 // source element is dequantized on load: (e2m1 * e4m3) * tensor_scale.
 //
-// Layout of the work: a lane owns one column j of x, i.e. one output row, and one whole
-// 128-chunk of it: 128 registers.  A wave reads, for each of the 128 rows of the chunk, 64
-// adjacent elements (one 128-byte line of bf16), so global loads stay coalesced without a
-// transpose through LDS; all seven butterfly stages of the rotation, the eight group maxima
-// and dot products are in-lane and the rotation signs are wave-uniform scalars.  A lane
-// writes 64 contiguous bytes of codes and 8 scale bytes per chunk; the 4 waves of a block
-// take 4 consecutive chunks of the same columns, so a block writes 256 contiguous bytes of
-// every output row.  The scale-rounding draws follow the library-wide rule (one Philox call
-// feeds rows 4q..4q+3 of one column group): the 4 lanes of a quad compute two calls each
-// and hand the words round with quad broadcasts.
+// Layout of the work: two neighbouring lanes own one column j of x (= one output row) and one
+// 128-chunk of it, 64 values each (lane parity p holds rows 64p .. 64p+63 of the chunk), so a
+// wave covers 32 columns and, for each of its 64 load instructions, two 64-byte row pieces:
+// global loads stay coalesced without a transpose through LDS.  Butterfly stages over index
+// bits 0..5 are in-lane, the last stage pairs the two lanes with one v_fmac_f32_dpp (the odd
+// lane carries -(a - b), undone by the sign of its scaling constant, as in the row kernels).
+// A lane owns four whole scale groups, so group maxima and dot products never leave it; it
+// writes 32 contiguous bytes of codes and 4 scale bytes, a lane pair 64 + 8, and the 4 waves
+// of a block take 4 consecutive chunks of the same columns (256 contiguous bytes per output
+// row).  The scale-rounding draws follow the library-wide rule (one Philox call feeds rows
+// 4q..4q+3 of one column group): the 8 lanes that own columns 4q..4q+3 compute one call each
+// (column groups 0..7 of the chunk) and fetch the words they need with ds_bpermute.
 #include "qii_device.h"
 #include "qii_internal.h"
 #include "quantize_core.h"
@@ -22,6 +24,8 @@ namespace qii {
 namespace {
 
 constexpr float kInvSqrt128 = 0x1.6a09e6p-4f;  // binary32 nearest to 2^-3.5
+// a block's 4 waves: kColHalves neighbouring 32-column ranges x kChunksPerBlock chunks
+constexpr int kColHalves = 1, kChunksPerBlock = 4;
 
 struct ColsArgs {
     const void *x;       // f32 / bf16 data, or the FP4 codes of an NVFP4 source
@@ -38,161 +42,182 @@ struct ColsArgs {
     uint32_t *amax_out;
 };
 
-// load the 128 rows of one chunk of column j, widen to f32, apply the rotation signs.
-// `chunk` is wave-uniform (scalar registers), so each row's address is a scalar base plus the
-// lane's 32-bit column offset; j is clamped into the tensor by the caller, so every lane
-// loads from a valid address and out-of-range lanes simply do not store.
+// load this lane's 64 rows (rows 64p .. 64p+63 of the chunk) of column j, widen to f32 and
+// apply the rotation signs.  `chunk` is wave-uniform; j is clamped into the tensor by the
+// caller, so every lane loads from a valid address and out-of-range lanes do not store.
 template <int kSrc, bool kRht>
-__device__ __forceinline__ void load_chunk(float v[128], const ColsArgs &a, int64_t chunk, uint32_t j)
+__device__ __forceinline__ void load_half_chunk(float v[64], const ColsArgs &a, int64_t chunk, uint32_t j, int p)
 {
+    // rotation sign bits of this lane's 64 elements: words 2p and 2p+1
+    const uint32_t s0 = p ? a.sign[2] : a.sign[0], s1 = p ? a.sign[3] : a.sign[1];
     if (kSrc == kSrcNVFP4) {
-        // two lanes share a code byte, sixteen a scale byte; batches of 32 rows bound the
-        // number of loads (and registers) in flight
+        // two columns share a code byte, sixteen a scale byte
         const int64_t cstride = a.ld / 2, sstride = a.ld / 16;
-        const uint8_t *pc = (const uint8_t *)a.x + (chunk * 128) * cstride;
-        const uint8_t *ps = a.in_scales + (chunk * 128) * sstride;
-        const uint32_t jc = j / 2, js = j / 16;
+        const uint8_t *pc = (const uint8_t *)a.x + (chunk * 128 + 64 * p) * cstride + j / 2;
+        const uint8_t *ps = a.in_scales + (chunk * 128 + 64 * p) * sstride + j / 16;
         const uint32_t shift = (j & 1u) * 4u;
         const float x32 = *a.in_ts;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
+        for (int b = 0; b < 2; ++b) {
             uint32_t rc[32], rs[32];
 #pragma unroll
             for (int i = 0; i < 32; ++i) {
-                rc[i] = (pc + (int64_t)(32 * b + i) * cstride)[jc];
-                rs[i] = (ps + (int64_t)(32 * b + i) * sstride)[js];
+                rc[i] = pc[(int64_t)(32 * b + i) * cstride];
+                rs[i] = ps[(int64_t)(32 * b + i) * sstride];
             }
 #pragma unroll
             for (int i = 0; i < 32; ++i) {
                 const int k = 32 * b + i;
                 const float2_t c = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(rc[i] >> shift, 1.0f, 0);
                 const float m = c[0] * e4m3_decode(rs[i]);   // exact
-                const uint32_t flip = kRht ? (((a.sign[k >> 5] >> (k & 31)) & 1u) << 31) : 0u;
-                v[k] = m * u2f(f2u(x32) ^ flip);
+                const uint32_t flip = kRht ? ((((k < 32 ? s0 : s1) >> (k & 31)) & 1u) << 31) : 0u;
+                v[k] = u2f(f2u(m * x32) ^ flip);
             }
-            asm volatile("" ::: "memory");
         }
         return;
     }
     constexpr bool kBf16 = kSrc == kSrcBF16;
     constexpr int esz = kBf16 ? 2 : 4;
-    const char *base = (const char *)a.x + (chunk * 128) * a.ld * esz;
-    const uint32_t off = j * esz;
-    uint32_t raw[128];
+    const char *base = (const char *)a.x + ((chunk * 128 + 64 * p) * a.ld + j) * esz;
+    uint32_t raw[64];
 #pragma unroll
-    for (int i = 0; i < 128; ++i) {
+    for (int i = 0; i < 64; ++i) {
         const char *rowp = base + (int64_t)i * a.ld * esz;
-        raw[i] = kBf16 ? (uint32_t)*reinterpret_cast<const uint16_t *>(rowp + off)
-                       : *reinterpret_cast<const uint32_t *>(rowp + off);
-        // keep the loads in issue order in batches, so that address registers are recycled
-        if ((i & 15) == 15) __builtin_amdgcn_sched_barrier(0);
+        raw[i] = kBf16 ? (uint32_t)*reinterpret_cast<const uint16_t *>(rowp) : *reinterpret_cast<const uint32_t *>(rowp);
     }
 #pragma unroll
-    for (int i = 0; i < 128; ++i) {
+    for (int i = 0; i < 64; ++i) {
         uint32_t u = kBf16 ? (raw[i] << 16) : raw[i];
-        if (kRht) u ^= ((a.sign[i >> 5] >> (i & 31)) & 1u) << 31;
+        if (kRht) u ^= (((i < 32 ? s0 : s1) >> (i & 31)) & 1u) << 31;
         v[i] = u2f(u);
     }
 }
 
-// y = H v / sqrt(128) in registers: stages over index bits 0..6 in order
-__device__ __forceinline__ void fwht128(float v[128])
+// one cross-lane butterfly stage on 16 registers: v[k] += partner(v[k]) * s, partner = lane xor 1
+__device__ __forceinline__ void dpp_pair_stage16(float *v, float s)
+{
+    asm volatile("s_nop 1\n"
+                 "v_fmac_f32_dpp %0, %0, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
+                 "v_fmac_f32_dpp %1, %1, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
+                 "v_fmac_f32_dpp %2, %2, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
+                 "v_fmac_f32_dpp %3, %3, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
+                 "v_fmac_f32_dpp %4, %4, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
+                 "v_fmac_f32_dpp %5, %5, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
+                 "v_fmac_f32_dpp %6, %6, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
+                 "v_fmac_f32_dpp %7, %7, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
+                 "v_fmac_f32_dpp %8, %8, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
+                 "v_fmac_f32_dpp %9, %9, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
+                 "v_fmac_f32_dpp %10, %10, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
+                 "v_fmac_f32_dpp %11, %11, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
+                 "v_fmac_f32_dpp %12, %12, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
+                 "v_fmac_f32_dpp %13, %13, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
+                 "v_fmac_f32_dpp %14, %14, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
+                 "v_fmac_f32_dpp %15, %15, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
+                 : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]),
+                   "+v"(v[6]), "+v"(v[7]), "+v"(v[8]), "+v"(v[9]), "+v"(v[10]), "+v"(v[11]),
+                   "+v"(v[12]), "+v"(v[13]), "+v"(v[14]), "+v"(v[15])
+                 : "v"(s));
+}
+
+// y = H v / sqrt(128) over the 128 values held by a lane pair: stages over index bits 0..5
+// in-lane, bit 6 across the pair, then the scaling (the odd lane's constant is negative)
+__device__ __forceinline__ void fwht128_pair(float v[64], int p)
 {
 #pragma unroll
-    for (int len = 1; len < 128; len <<= 1)
+    for (int len = 1; len < 64; len <<= 1)
 #pragma unroll
-        for (int i = 0; i < 128; ++i)
+        for (int i = 0; i < 64; ++i)
             if ((i & len) == 0) {
                 const float x = v[i], y = v[i + len];
                 v[i] = x + y;
                 v[i + len] = x - y;
             }
+    const float s = p ? -1.0f : 1.0f;
+    dpp_pair_stage16(v, s);
+    dpp_pair_stage16(v + 16, s);
+    dpp_pair_stage16(v + 32, s);
+    dpp_pair_stage16(v + 48, s);
+    const float c = p ? -kInvSqrt128 : kInvSqrt128;
 #pragma unroll
-    for (int i = 0; i < 128; ++i) v[i] = __builtin_fmaf(v[i], kInvSqrt128, 0.0f);  // +0 for exact zeros
+    for (int i = 0; i < 64; ++i) v[i] = __builtin_fmaf(v[i], c, 0.0f);  // +0 for exact zeros
 }
 
-template <int kSrcLane>
-__device__ __forceinline__ uint32_t quad_bcast(uint32_t v)
+// draws of this lane's 4 groups (column groups 8*chunk + 4p .. +3) of output row j.
+// Lane o of an octet (the 8 lanes that own columns 4q..4q+3) computes the call of column
+// group 8*chunk + o; a lane then takes word (j mod 4) of the calls of its own four groups.
+__device__ __forceinline__ void octet_draws(uint32_t draw[4], uint64_t seed_sr, int64_t chunk, int64_t j, int p)
 {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, kSrcLane * 0x55, 0xF, 0xF, true);
-}
-
-// draws of the 8 groups (column groups 8*chunk .. 8*chunk+7) of output row j.
-// Lane m of a quad computes the calls of column groups 2m and 2m+1 of the chunk; every lane
-// then takes word (j mod 4) of each call.
-__device__ __forceinline__ void quad_draws(uint32_t draw[8], uint64_t seed_sr, int64_t chunk, int64_t j)
-{
-    const int m = threadIdx.x & 3;
-    const U4 wa = philox_seeded(seed_sr, (uint32_t)(chunk * 8 + 2 * m), (uint32_t)(j >> 2), 0, kStreamScale);
-    const U4 wb = philox_seeded(seed_sr, (uint32_t)(chunk * 8 + 2 * m + 1), (uint32_t)(j >> 2), 0, kStreamScale);
-#define QII_PICK(GI, SRC, W)                                                                      \
-    do {                                                                                          \
-        const uint32_t x = quad_bcast<SRC>(W.x), y = quad_bcast<SRC>(W.y);                        \
-        const uint32_t z = quad_bcast<SRC>(W.z), w = quad_bcast<SRC>(W.w);                        \
-        draw[GI] = (m == 0 ? x : m == 1 ? y : m == 2 ? z : w) >> 12;                              \
-    } while (0)
-    QII_PICK(0, 0, wa); QII_PICK(1, 0, wb); QII_PICK(2, 1, wa); QII_PICK(3, 1, wb);
-    QII_PICK(4, 2, wa); QII_PICK(5, 2, wb); QII_PICK(6, 3, wa); QII_PICK(7, 3, wb);
-#undef QII_PICK
+    const int lane = threadIdx.x & 63, o = lane & 7, word = (lane >> 1) & 3;
+    const U4 w = philox_seeded(seed_sr, (uint32_t)(chunk * 8 + o), (uint32_t)(j >> 2), 0, kStreamScale);
+#pragma unroll
+    for (int gi = 0; gi < 4; ++gi) {
+        const int src = ((lane & ~7) | (4 * p + gi)) * 4;
+        const uint32_t x = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)w.x);
+        const uint32_t y = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)w.y);
+        const uint32_t z = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)w.z);
+        const uint32_t q = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)w.w);
+        draw[gi] = (word == 0 ? x : word == 1 ? y : word == 2 ? z : q) >> 12;
+    }
 }
 
 template <int kSrc, int kMode, bool kRht>
-__global__ __launch_bounds__(256, 2) void quantize_cols_kernel(ColsArgs a)
+__global__ __launch_bounds__(256) void quantize_cols_kernel(ColsArgs a)
 {
-    const int lane = threadIdx.x & 63;
+    const int lane = threadIdx.x & 63, p = lane & 1;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;   // wave-uniform
-    const int64_t j = (int64_t)blockIdx.y * 64 + lane;
+    const int64_t chunk = (int64_t)blockIdx.x * kChunksPerBlock + (wave / kColHalves);   // wave-uniform
+    const int64_t j = ((int64_t)blockIdx.y * kColHalves + (wave % kColHalves)) * 32 + (lane >> 1);
     const TensorConsts tc = tensor_consts(kMode, *a.amax);
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *a.tensor_scale = tc.x32;
     if (chunk * 128 >= a.C) return;
     const bool ok = j < a.R;
-    uint4 *pc = reinterpret_cast<uint4 *>(a.codes + j * (a.C / 2) + chunk * 64);
-    uint2 *psc = reinterpret_cast<uint2 *>(a.scales + j * (a.C / 16) + chunk * 8);
+    uint4 *pc = reinterpret_cast<uint4 *>(a.codes + j * (a.C / 2) + chunk * 64 + 32 * p);
+    uint32_t *psc = reinterpret_cast<uint32_t *>(a.scales + j * (a.C / 16) + chunk * 8 + 4 * p);
     if (tc.zero) {  // uniform: an all-zero tensor is emitted as zero bytes
         if (ok) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) pc[i] = make_uint4(0u, 0u, 0u, 0u);
-            *psc = make_uint2(0u, 0u);
+            pc[0] = make_uint4(0u, 0u, 0u, 0u);
+            pc[1] = make_uint4(0u, 0u, 0u, 0u);
+            *psc = 0u;
         }
         return;
     }
-    float v[128];
-    load_chunk<kSrc, kRht>(v, a, chunk, (uint32_t)(ok ? j : a.R - 1));
-    if (kRht) fwht128(v);
-    uint32_t draw[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
-    if (kMode == QII_MS_EDEN) quad_draws(draw, a.seed_sr, chunk, j);
-    uint32_t sc[2] = {0u, 0u};
+    float v[64];
+    load_half_chunk<kSrc, kRht>(v, a, chunk, (uint32_t)(ok ? j : a.R - 1), p);
+    if (kRht) fwht128_pair(v, p);
+    uint32_t draw[4] = {0u, 0u, 0u, 0u};
+    if (kMode == QII_MS_EDEN) octet_draws(draw, a.seed_sr, chunk, j, p);
+    uint32_t sc = 0u;
 #pragma unroll
-    for (int gp = 0; gp < 4; ++gp) {   // two groups = 16 bytes of codes per store
+    for (int gp = 0; gp < 2; ++gp) {   // two groups = 16 bytes of codes per store
         uint32_t codes[4];
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int gi = 2 * gp + h;
-            const uint32_t b = quantize_group16<kMode>(v + 16 * gi, tc, draw[gi], a.seed_sr, j, chunk * 8 + gi, codes + 2 * h);
-            sc[gi >> 2] |= b << (8 * (gi & 3));
+            const uint32_t b = quantize_group16<kMode>(v + 16 * gi, tc, draw[gi], a.seed_sr, j,
+                                                       chunk * 8 + 4 * p + gi, codes + 2 * h);
+            sc |= b << (8 * gi);
         }
         if (ok) pc[gp] = make_uint4(codes[0], codes[1], codes[2], codes[3]);
     }
-    if (ok) *psc = make_uint2(sc[0], sc[1]);
+    if (ok) *psc = sc;
 }
 
 template <int kSrc, bool kRht>
-__global__ __launch_bounds__(256, 2) void absmax_cols_kernel(ColsArgs a)
+__global__ __launch_bounds__(256) void absmax_cols_kernel(ColsArgs a)
 {
     __shared__ float wave_m[4];
-    const int lane = threadIdx.x & 63;
+    const int lane = threadIdx.x & 63, p = lane & 1;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;   // wave-uniform
-    const int64_t j = (int64_t)blockIdx.y * 64 + lane;
+    const int64_t chunk = (int64_t)blockIdx.x * kChunksPerBlock + (wave / kColHalves);   // wave-uniform
+    const int64_t j = ((int64_t)blockIdx.y * kColHalves + (wave % kColHalves)) * 32 + (lane >> 1);
     float m = 0.0f;
     if (chunk * 128 < a.C) {
-        float v[128];
+        float v[64];
         // a clamped duplicate of a real column cannot change the maximum
-        load_chunk<kSrc, kRht>(v, a, chunk, (uint32_t)(j < a.R ? j : a.R - 1));
-        if (kRht) fwht128(v);
+        load_half_chunk<kSrc, kRht>(v, a, chunk, (uint32_t)(j < a.R ? j : a.R - 1), p);
+        if (kRht) fwht128_pair(v, p);
 #pragma unroll
-        for (int gi = 0; gi < 8; ++gi) m = fmaxf(m, group_absmax(v + 16 * gi));
+        for (int gi = 0; gi < 4; ++gi) m = fmaxf(m, group_absmax(v + 16 * gi));
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
@@ -218,7 +243,8 @@ ColsArgs make_args(const Source &src, int64_t R, int64_t C, uint64_t seed_rht, u
 
 dim3 cols_grid(int64_t R, int64_t C)
 {
-    return dim3((unsigned)((C / 128 + 3) / 4), (unsigned)((R + 63) / 64));
+    return dim3((unsigned)((C / 128 + kChunksPerBlock - 1) / kChunksPerBlock),
+                (unsigned)((R + 32 * kColHalves - 1) / (32 * kColHalves)));
 }
 
 }  // namespace

@@ -14,8 +14,6 @@
 // undone exactly by the sign of the lane's final 2^-3.5 scaling constant.  Only the sign
 // of exactly-zero intermediates can differ from the plain butterfly, and the final
 // fma(v, c, +0) maps every zero result to +0, as the arithmetic contract states.
-#include <stdlib.h>
-
 #include "qii_device.h"
 #include "qii_internal.h"
 #include "quantize_core.h"
@@ -189,7 +187,7 @@ __device__ __forceinline__ void make_masks(uint32_t sign16, uint32_t mask[kBf16 
     }
 }
 
-template <bool kBf16, int kMode, bool kRht, bool kPrefetch, int kAblate = 0>
+template <bool kBf16, int kMode, bool kRht>
 __global__ __launch_bounds__(256) void quantize_rows_kernel(RowsArgs a)
 {
     const int64_t G = a.C / 16;
@@ -214,12 +212,9 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowsArgs a)
     Raw<kBf16> raw[4];
     load_quad<kBf16>(raw, a, blockIdx.x, gc);
     for (int64_t quad = blockIdx.x; quad < quads; quad += gridDim.x) {
-        // prefetch the next quad of this block while the current one is being processed
-        Raw<kBf16> nxt[4];
         const int64_t qn = quad + gridDim.x;
-        if (kPrefetch) load_quad<kBf16>(nxt, a, qn < quads ? qn : quad, gc);
         uint32_t draw[4] = {0u, 0u, 0u, 0u};
-        if (kMode == QII_MS_EDEN && !(kAblate & 4)) {
+        if (kMode == QII_MS_EDEN) {
             const U4 w = philox_seeded(a.seed_sr, (uint32_t)L.g, (uint32_t)quad, 0, kStreamScale);
             draw[0] = w.x >> 12; draw[1] = w.y >> 12; draw[2] = w.z >> 12; draw[3] = w.w >> 12;
         }
@@ -228,15 +223,11 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowsArgs a)
             const int64_t row = quad * 4 + it;
             float v[16];
             unpack_signed<kBf16, kRht>(raw[it], v, mask);
-            if (kRht && !(kAblate & 8)) rht128_lane(v, L);
+            if (kRht) rht128_lane(v, L);
             uint32_t packed[2];
-            uint32_t b;
-            if (kAblate & 16) { b = f2u(v[0] + v[5]) & 0xff; packed[0] = f2u(v[1] + v[7] + v[9] + v[11] + v[13] + v[15]); packed[1] = f2u(v[2] + v[4] + v[6] + v[8] + v[3] + v[10] + v[12] + v[14]); }
-            else b = quantize_group16<kMode>(v, tc, draw[it], a.seed_sr, row, L.g, packed);
-            if (L.col_ok && row < a.R) {
-                if (!(kAblate & 2)) *reinterpret_cast<uint2 *>(a.codes + (row * a.C + L.g * 16) / 2) = make_uint2(packed[0], packed[1]);
-                else if (packed[0] == 0x12345u) a.codes[0] = 1;
-            }
+            const uint32_t b = quantize_group16<kMode>(v, tc, draw[it], a.seed_sr, row, L.g, packed);
+            if (L.col_ok && row < a.R)
+                *reinterpret_cast<uint2 *>(a.codes + (row * a.C + L.g * 16) / 2) = make_uint2(packed[0], packed[1]);
             if (G % 8 == 0) {   // whole octets: one 8-byte store per chunk
                 const uint2 sc = gather_scale_bytes(b, L.blk);
                 if (L.col_ok && row < a.R && L.blk == 0)
@@ -245,12 +236,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowsArgs a)
                 a.scales[row * G + L.g] = (uint8_t)b;
             }
         }
-        if (kPrefetch) {
-#pragma unroll
-            for (int it = 0; it < 4; ++it) raw[it] = nxt[it];
-        } else if (qn < quads) {
-            load_quad<kBf16>(raw, a, qn, gc);
-        }
+        if (qn < quads) load_quad<kBf16>(raw, a, qn, gc);
     }
 }
 
@@ -300,8 +286,7 @@ dim3 rows_grid(int64_t R, int64_t C)
     const int64_t G = C / 16, nch = (G + 7) / 8;
     const int64_t gy = (nch + 31) / 32;            // 4 waves x 8 chunks per block
     const int64_t quads = (R + 3) / 4;
-    static const int per_cu = getenv("QII_ROWS_BPC") ? atoi(getenv("QII_ROWS_BPC")) : 4;
-    int64_t cap = (256 * per_cu) / gy;             // 256 CUs x resident blocks
+    int64_t cap = (256 * 4) / gy;                  // 256 CUs x 4 resident blocks
     if (cap < 1) cap = 1;
     const int64_t iters = (quads + cap - 1) / cap; // iterations per block
     int64_t gx = (quads + iters - 1) / iters;      // even split
@@ -345,23 +330,7 @@ hipError_t launch_quantize_rows(const QuantizeArgs &q, hipStream_t s)
     a.amax = q.amax; a.codes = q.codes; a.scales = q.scales; a.tensor_scale = q.tensor_scale;
     const dim3 grid = rows_grid(q.R, q.C), block(256);
     const bool bf = q.src.kind == kSrcBF16;
-    static const int ablate = getenv("QII_ABLATE") ? atoi(getenv("QII_ABLATE")) : 0;
-    static const bool prefetch = getenv("QII_ROWS_PREFETCH") && atoi(getenv("QII_ROWS_PREFETCH"));
-#define QII_ROWS(BF, MODE, RHT)                                                                   \
-    do {                                                                                          \
-        if (BF && MODE == QII_MS_EDEN && RHT && ablate) {                                         \
-            switch (ablate) {                                                                     \
-                case 1: hipLaunchKernelGGL((quantize_rows_kernel<true, QII_MS_EDEN, true, false, 1>), grid, block, 0, s, a); break;  \
-                case 3: hipLaunchKernelGGL((quantize_rows_kernel<true, QII_MS_EDEN, true, false, 3>), grid, block, 0, s, a); break;  \
-                case 4: hipLaunchKernelGGL((quantize_rows_kernel<true, QII_MS_EDEN, true, false, 4>), grid, block, 0, s, a); break;  \
-                case 8: hipLaunchKernelGGL((quantize_rows_kernel<true, QII_MS_EDEN, true, false, 8>), grid, block, 0, s, a); break;  \
-                case 16: hipLaunchKernelGGL((quantize_rows_kernel<true, QII_MS_EDEN, true, false, 16>), grid, block, 0, s, a); break; \
-                case 24: hipLaunchKernelGGL((quantize_rows_kernel<true, QII_MS_EDEN, true, false, 24>), grid, block, 0, s, a); break; \
-                default: break;                                                                   \
-            }                                                                                     \
-        } else if (prefetch) hipLaunchKernelGGL((quantize_rows_kernel<BF, MODE, RHT, true>), grid, block, 0, s, a);  \
-        else hipLaunchKernelGGL((quantize_rows_kernel<BF, MODE, RHT, false>), grid, block, 0, s, a);          \
-    } while (0)
+#define QII_ROWS(BF, MODE, RHT) hipLaunchKernelGGL((quantize_rows_kernel<BF, MODE, RHT>), grid, block, 0, s, a)
 #define QII_ROWS_MODE(BF, RHT)                                   \
     do {                                                         \
         if (q.mode == QII_RTN) QII_ROWS(BF, QII_RTN, RHT);       \

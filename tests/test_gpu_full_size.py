@@ -1,0 +1,68 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times: one
+linear layer forward + backward with tokens 16384, d_in 2048, d_out 8192 (bf16 inputs with
+outlier channels).  Saved forward tensors are compared byte for byte; the three GEMM outputs are
+compared on sampled entries (plus one full row and one full column of Y) that the oracle
+computes one by one from its own quantized operands."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_22813_amd import binding as qii
+from paper_2601_22813_amd import synth
+
+from gpu_util import assert_nv_equal, to_dev, ws
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_pairs(M, N, count, rng):
+    return rng.integers(0, M, count), rng.integers(0, N, count)
+
+
+def check_samples(C, a, b, ms, ns, oracle, bf16, what):
+    ref, absum = oracle.gemm_sampled(a, b, ms, ns)
+    got = C[torch.from_numpy(ms).cuda(), torch.from_numpy(ns).cuda()].float().cpu().numpy().astype(np.float64)
+    tol = 1e-5 * absum + (2.0 ** -8 * np.abs(ref) if bf16 else 0.0) + 1e-30
+    bad = np.abs(got - ref) > tol
+    assert not bad.any(), f"{what}: {bad.sum()} of {len(ms)} samples off, e.g. ({ms[bad][0]},{ns[bad][0]}) gpu {got[bad][0]} ref {ref[bad][0]}"
+
+
+def test_linear_layer_at_benchmark_size(oracle):
+    T, d_in, d_out = 16384, 2048, 8192
+    rng = np.random.default_rng(0)
+    Xb, Wb, Eb = synth.linear_layer_bf16(T, d_in, d_out, seed=2)
+    X, W, E = to_dev(Xb), to_dev(Wb), to_dev(Eb)
+    Xq, Wq = qii.NVFP4Tensor.empty(T, d_in), qii.NVFP4Tensor.empty(d_out, d_in)
+    Y = torch.empty((T, d_out), dtype=torch.bfloat16, device="cuda")
+    print("forward", flush=True)
+    qii.qii_linear_fwd(X, W, Y, Xq, Wq, ws(qii.qii_linear_fwd_workspace_bytes(T, d_in, d_out)))
+    oXq, oWq = oracle.linear_fwd(Xb, Wb)
+    assert_nv_equal(Xq, oXq, "saved X")
+    assert_nv_equal(Wq, oWq, "saved W")
+    ms, ns = sample_pairs(T, d_out, 4096, rng)
+    ms = np.concatenate([ms, np.full(d_out, 12345), np.arange(T)])          # one full row
+    ns = np.concatenate([ns, np.arange(d_out), np.full(T, 4321)])           # one full column
+    check_samples(Y, oXq, oWq, ms, ns, oracle, True, "Y")
+    print("backward", flush=True)
+    dX = torch.empty((T, d_in), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((d_out, d_in), dtype=torch.bfloat16, device="cuda")
+    seed = 2024
+    qii.qii_linear_bwd(E, Xq, Wq, seed, dX, dW, ws(qii.qii_linear_bwd_workspace_bytes(T, d_in, d_out)))
+    torch.cuda.synchronize()
+    print("oracle operands", flush=True)
+    Eq, WTq, ETq, XTq = oracle.linear_bwd_operands(Eb, oXq, oWq, seed)
+    ms, ns = sample_pairs(T, d_in, 4096, rng)
+    check_samples(dX, Eq, WTq, ms, ns, oracle, True, "dX")
+    ms, ns = sample_pairs(d_out, d_in, 4096, rng)
+    check_samples(dW, ETq, XTq, ms, ns, oracle, True, "dW")
+    # the quantized backward operands themselves, through the public quantizer with the derived seeds
+    s = [qii.qii_derive_seed(seed, i) for i in range(6)]
+    out = qii.NVFP4Tensor.empty(d_out, T)
+    qii.qii_quantize_nvfp4(E, True, qii.MS_EDEN, 128, s[1], s[4], None, out, ws(256))
+    assert_nv_equal(out, ETq, "Q(E^T)")
+    out = qii.NVFP4Tensor.empty(d_in, T)
+    qii.qii_requantize_nvfp4(Xq, True, qii.MS_EDEN, 128, s[1], s[5], None, out, ws(256))
+    assert_nv_equal(out, XTq, "Q(X^T)")
+    out = qii.NVFP4Tensor.empty(T, d_out)
+    qii.qii_quantize_nvfp4(E, False, qii.MS_EDEN, 128, s[0], s[2], None, out, ws(256))
+    assert_nv_equal(out, Eq, "Q(E)")
