@@ -4,18 +4,21 @@
 // re-quantization of a saved NVFP4 tensor with transposition (Q(W^T), Q(X^T)), where the
 // source element is dequantized on load: (e2m1 * e4m3) * tensor_scale.
 //
-// Layout of the work: two neighbouring lanes own one column j of x (= one output row) and one
-// 128-chunk of it, 64 values each (lane parity p holds rows 64p .. 64p+63 of the chunk), so a
-// wave covers 32 columns and, for each of its 64 load instructions, two 64-byte row pieces:
-// global loads stay coalesced without a transpose through LDS.  Butterfly stages over index
-// bits 0..5 are in-lane, the last stage pairs the two lanes with one v_fmac_f32_dpp (the odd
-// lane carries -(a - b), undone by the sign of its scaling constant, as in the row kernels).
-// A lane owns four whole scale groups, so group maxima and dot products never leave it; it
-// writes 32 contiguous bytes of codes and 4 scale bytes, a lane pair 64 + 8, and the 4 waves
-// of a block take 4 consecutive chunks of the same columns (256 contiguous bytes per output
-// row).  The scale-rounding draws follow the library-wide rule (one Philox call feeds rows
-// 4q..4q+3 of one column group): the 8 lanes that own columns 4q..4q+3 compute one call each
-// (column groups 0..7 of the chunk) and fetch the words they need with ds_bpermute.
+// Layout of the work: the 4 lanes of a quad own two adjacent columns of x (= two output rows)
+// and one 128-chunk of them, 32 rows each (lane q holds rows 32q .. 32q+31 of the chunk, for
+// both columns): one 4-byte load fetches a row's two bf16 columns, so a wave covers 32 columns
+// with 32 load instructions of four 64-byte row pieces each, coalesced without a transpose
+// through LDS.  Butterfly stages over index bits 0..4 are in-lane, bits 5 and 6 pair lanes
+// xor 1 and xor 2 with one v_fmac_f32_dpp each (lanes with the stage bit set carry -(a - b),
+// undone by the sign of their scaling constant, as in the row kernels).  A lane owns two whole
+// scale groups per column, so group maxima and dot products never leave it; it writes 16
+// contiguous bytes of codes per column, a quad 64, and the 4 waves of a block take 4
+// consecutive chunks of the same columns (256 contiguous bytes per output row); the 8 scale
+// bytes of a (column, chunk) are gathered with DPP into one store.  The scale-rounding draws
+// follow the library-wide rule (one Philox call feeds rows 4j..4j+3 of one column group): the
+// 8 lanes that own columns 4j..4j+3 compute one call each (column groups 0..7 of the chunk)
+// and fetch the words they need with ds_bpermute.  An NVFP4 source (re-quantization with
+// transposition) is dequantized on load; there one byte holds a row's two columns.
 #include "qii_device.h"
 #include "qii_internal.h"
 #include "quantize_core.h"
@@ -24,8 +27,6 @@ namespace qii {
 namespace {
 
 constexpr float kInvSqrt128 = 0x1.6a09e6p-4f;  // binary32 nearest to 2^-3.5
-// a block's 4 waves: kColHalves neighbouring 32-column ranges x kChunksPerBlock chunks
-constexpr int kColHalves = 1, kChunksPerBlock = 4;
 
 struct ColsArgs {
     const void *x;       // f32 / bf16 data, or the FP4 codes of an NVFP4 source
@@ -42,182 +43,210 @@ struct ColsArgs {
     uint32_t *amax_out;
 };
 
-// load this lane's 64 rows (rows 64p .. 64p+63 of the chunk) of column j, widen to f32 and
-// apply the rotation signs.  `chunk` is wave-uniform; j is clamped into the tensor by the
-// caller, so every lane loads from a valid address and out-of-range lanes do not store.
+// load this lane's 32 rows (rows 32q .. 32q+31 of the chunk) of columns j0 and j0+1 (j0 even),
+// widen to f32 and apply the rotation signs.  `chunk` is wave-uniform; j0 is clamped into the
+// tensor by the caller, so every lane loads from a valid address.
 template <int kSrc, bool kRht>
-__device__ __forceinline__ void load_half_chunk(float v[64], const ColsArgs &a, int64_t chunk, uint32_t j, int p)
+__device__ __forceinline__ void load_quarter_chunk(float v[2][32], const ColsArgs &a, int64_t chunk, uint32_t j0, int q)
 {
-    // rotation sign bits of this lane's 64 elements: words 2p and 2p+1
-    const uint32_t s0 = p ? a.sign[2] : a.sign[0], s1 = p ? a.sign[3] : a.sign[1];
+    const uint32_t sw = q == 0 ? a.sign[0] : q == 1 ? a.sign[1] : q == 2 ? a.sign[2] : a.sign[3];
     if (kSrc == kSrcNVFP4) {
-        // two columns share a code byte, sixteen a scale byte
         const int64_t cstride = a.ld / 2, sstride = a.ld / 16;
-        const uint8_t *pc = (const uint8_t *)a.x + (chunk * 128 + 64 * p) * cstride + j / 2;
-        const uint8_t *ps = a.in_scales + (chunk * 128 + 64 * p) * sstride + j / 16;
-        const uint32_t shift = (j & 1u) * 4u;
+        const uint8_t *pc = (const uint8_t *)a.x + (chunk * 128 + 32 * q) * cstride + j0 / 2;
+        const uint8_t *ps = a.in_scales + (chunk * 128 + 32 * q) * sstride + j0 / 16;
         const float x32 = *a.in_ts;
+        uint32_t rc[32], rs[32];
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            uint32_t rc[32], rs[32];
+        for (int i = 0; i < 32; ++i) {
+            rc[i] = pc[(int64_t)i * cstride];
+            rs[i] = ps[(int64_t)i * sstride];
+        }
 #pragma unroll
-            for (int i = 0; i < 32; ++i) {
-                rc[i] = pc[(int64_t)(32 * b + i) * cstride];
-                rs[i] = ps[(int64_t)(32 * b + i) * sstride];
-            }
-#pragma unroll
-            for (int i = 0; i < 32; ++i) {
-                const int k = 32 * b + i;
-                const float2_t c = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(rc[i] >> shift, 1.0f, 0);
-                const float m = c[0] * e4m3_decode(rs[i]);   // exact
-                const uint32_t flip = kRht ? ((((k < 32 ? s0 : s1) >> (k & 31)) & 1u) << 31) : 0u;
-                v[k] = u2f(f2u(m * x32) ^ flip);
-            }
+        for (int i = 0; i < 32; ++i) {
+            const float2_t c = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(rc[i], 1.0f, 0);
+            const float x8 = e4m3_decode(rs[i]);
+            const uint32_t flip = kRht ? (((sw >> i) & 1u) << 31) : 0u;
+            v[0][i] = u2f(f2u((c[0] * x8) * x32) ^ flip);   // first product exact
+            v[1][i] = u2f(f2u((c[1] * x8) * x32) ^ flip);
         }
         return;
     }
-    constexpr bool kBf16 = kSrc == kSrcBF16;
-    constexpr int esz = kBf16 ? 2 : 4;
-    const char *base = (const char *)a.x + ((chunk * 128 + 64 * p) * a.ld + j) * esz;
-    uint32_t raw[64];
+    if (kSrc == kSrcBF16) {
+        const char *base = (const char *)a.x + ((chunk * 128 + 32 * q) * a.ld + j0) * 2;
+        uint32_t raw[32];
 #pragma unroll
-    for (int i = 0; i < 64; ++i) {
-        const char *rowp = base + (int64_t)i * a.ld * esz;
-        raw[i] = kBf16 ? (uint32_t)*reinterpret_cast<const uint16_t *>(rowp) : *reinterpret_cast<const uint32_t *>(rowp);
-    }
+        for (int i = 0; i < 32; ++i) raw[i] = *reinterpret_cast<const uint32_t *>(base + (int64_t)i * a.ld * 2);
 #pragma unroll
-    for (int i = 0; i < 64; ++i) {
-        uint32_t u = kBf16 ? (raw[i] << 16) : raw[i];
-        if (kRht) u ^= (((i < 32 ? s0 : s1) >> (i & 31)) & 1u) << 31;
-        v[i] = u2f(u);
+        for (int i = 0; i < 32; ++i) {
+            const uint32_t flip = kRht ? (((sw >> i) & 1u) << 31) : 0u;
+            v[0][i] = u2f((raw[i] << 16) ^ flip);
+            v[1][i] = u2f((raw[i] & 0xFFFF0000u) ^ flip);
+        }
+    } else {
+        const char *base = (const char *)a.x + ((chunk * 128 + 32 * q) * a.ld + j0) * 4;
+        uint2 raw[32];
+#pragma unroll
+        for (int i = 0; i < 32; ++i) raw[i] = *reinterpret_cast<const uint2 *>(base + (int64_t)i * a.ld * 4);
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+            const uint32_t flip = kRht ? (((sw >> i) & 1u) << 31) : 0u;
+            v[0][i] = u2f(raw[i].x ^ flip);
+            v[1][i] = u2f(raw[i].y ^ flip);
+        }
     }
 }
 
-// one cross-lane butterfly stage on 16 registers: v[k] += partner(v[k]) * s, partner = lane xor 1
-__device__ __forceinline__ void dpp_pair_stage16(float *v, float s)
-{
-    asm volatile("s_nop 1\n"
-                 "v_fmac_f32_dpp %0, %0, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
-                 "v_fmac_f32_dpp %1, %1, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
-                 "v_fmac_f32_dpp %2, %2, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
-                 "v_fmac_f32_dpp %3, %3, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
-                 "v_fmac_f32_dpp %4, %4, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
-                 "v_fmac_f32_dpp %5, %5, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
-                 "v_fmac_f32_dpp %6, %6, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
-                 "v_fmac_f32_dpp %7, %7, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
-                 "v_fmac_f32_dpp %8, %8, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
-                 "v_fmac_f32_dpp %9, %9, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
-                 "v_fmac_f32_dpp %10, %10, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
-                 "v_fmac_f32_dpp %11, %11, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
-                 "v_fmac_f32_dpp %12, %12, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
-                 "v_fmac_f32_dpp %13, %13, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
-                 "v_fmac_f32_dpp %14, %14, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
-                 "v_fmac_f32_dpp %15, %15, %16 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
-                 : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]),
-                   "+v"(v[6]), "+v"(v[7]), "+v"(v[8]), "+v"(v[9]), "+v"(v[10]), "+v"(v[11]),
-                   "+v"(v[12]), "+v"(v[13]), "+v"(v[14]), "+v"(v[15])
-                 : "v"(s));
-}
+// one cross-lane butterfly stage on 16 registers: v[k] += partner(v[k]) * s
+#define QII_PAIR_STAGE(NAME, CTRL)                                                                \
+    __device__ __forceinline__ void NAME(float *v, float s)                                       \
+    {                                                                                             \
+        asm volatile("s_nop 1\n"                                                                  \
+                     "v_fmac_f32_dpp %0, %0, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
+                     "v_fmac_f32_dpp %1, %1, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
+                     "v_fmac_f32_dpp %2, %2, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
+                     "v_fmac_f32_dpp %3, %3, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
+                     "v_fmac_f32_dpp %4, %4, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
+                     "v_fmac_f32_dpp %5, %5, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
+                     "v_fmac_f32_dpp %6, %6, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
+                     "v_fmac_f32_dpp %7, %7, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
+                     "v_fmac_f32_dpp %8, %8, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
+                     "v_fmac_f32_dpp %9, %9, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
+                     "v_fmac_f32_dpp %10, %10, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"         \
+                     "v_fmac_f32_dpp %11, %11, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"         \
+                     "v_fmac_f32_dpp %12, %12, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"         \
+                     "v_fmac_f32_dpp %13, %13, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"         \
+                     "v_fmac_f32_dpp %14, %14, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"         \
+                     "v_fmac_f32_dpp %15, %15, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"         \
+                     : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]),    \
+                       "+v"(v[6]), "+v"(v[7]), "+v"(v[8]), "+v"(v[9]), "+v"(v[10]), "+v"(v[11]),  \
+                       "+v"(v[12]), "+v"(v[13]), "+v"(v[14]), "+v"(v[15])                         \
+                     : "v"(s));                                                                   \
+    }
+QII_PAIR_STAGE(dpp_xor1_stage16, "quad_perm:[1,0,3,2]")
+QII_PAIR_STAGE(dpp_xor2_stage16, "quad_perm:[2,3,0,1]")
+#undef QII_PAIR_STAGE
 
-// y = H v / sqrt(128) over the 128 values held by a lane pair: stages over index bits 0..5
-// in-lane, bit 6 across the pair, then the scaling (the odd lane's constant is negative)
-__device__ __forceinline__ void fwht128_pair(float v[64], int p)
+// y = H v / sqrt(128) over the 128 values of one column held by a lane quad: stages over
+// index bits 0..4 in-lane, bits 5 and 6 across the quad, then the scaling
+__device__ __forceinline__ void fwht128_quad(float v[32], int q)
 {
 #pragma unroll
-    for (int len = 1; len < 64; len <<= 1)
+    for (int len = 1; len < 32; len <<= 1)
 #pragma unroll
-        for (int i = 0; i < 64; ++i)
+        for (int i = 0; i < 32; ++i)
             if ((i & len) == 0) {
                 const float x = v[i], y = v[i + len];
                 v[i] = x + y;
                 v[i + len] = x - y;
             }
-    const float s = p ? -1.0f : 1.0f;
-    dpp_pair_stage16(v, s);
-    dpp_pair_stage16(v + 16, s);
-    dpp_pair_stage16(v + 32, s);
-    dpp_pair_stage16(v + 48, s);
-    const float c = p ? -kInvSqrt128 : kInvSqrt128;
+    const float s5 = (q & 1) ? -1.0f : 1.0f, s6 = (q & 2) ? -1.0f : 1.0f;
+    dpp_xor1_stage16(v, s5);
+    dpp_xor1_stage16(v + 16, s5);
+    dpp_xor2_stage16(v, s6);
+    dpp_xor2_stage16(v + 16, s6);
+    const float c = (q == 1 || q == 2) ? -kInvSqrt128 : kInvSqrt128;
 #pragma unroll
-    for (int i = 0; i < 64; ++i) v[i] = __builtin_fmaf(v[i], c, 0.0f);  // +0 for exact zeros
+    for (int i = 0; i < 32; ++i) v[i] = __builtin_fmaf(v[i], c, 0.0f);  // +0 for exact zeros
 }
 
-// draws of this lane's 4 groups (column groups 8*chunk + 4p .. +3) of output row j.
-// Lane o of an octet (the 8 lanes that own columns 4q..4q+3) computes the call of column
-// group 8*chunk + o; a lane then takes word (j mod 4) of the calls of its own four groups.
-__device__ __forceinline__ void octet_draws(uint32_t draw[4], uint64_t seed_sr, int64_t chunk, int64_t j, int p)
+// draws of this lane's groups: draw[e][h] for column j0+e, column group 8*chunk + 2q + h.
+// Lane o of an octet (the 8 lanes that own columns 4j..4j+3) computes the call of column
+// group 8*chunk + o; a lane then takes the words of its two columns from its two calls.
+__device__ __forceinline__ void octet_draws(uint32_t draw[2][2], uint64_t seed_sr, int64_t chunk, int64_t j0, int q)
 {
-    const int lane = threadIdx.x & 63, o = lane & 7, word = (lane >> 1) & 3;
-    const U4 w = philox_seeded(seed_sr, (uint32_t)(chunk * 8 + o), (uint32_t)(j >> 2), 0, kStreamScale);
+    const int lane = threadIdx.x & 63, o = lane & 7, upper = (lane >> 2) & 1;   // upper: columns 2,3 of the four
+    const U4 w = philox_seeded(seed_sr, (uint32_t)(chunk * 8 + o), (uint32_t)(j0 >> 2), 0, kStreamScale);
 #pragma unroll
-    for (int gi = 0; gi < 4; ++gi) {
-        const int src = ((lane & ~7) | (4 * p + gi)) * 4;
+    for (int h = 0; h < 2; ++h) {
+        const int src = ((lane & ~7) | (2 * q + h)) * 4;
         const uint32_t x = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)w.x);
         const uint32_t y = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)w.y);
         const uint32_t z = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)w.z);
-        const uint32_t q = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)w.w);
-        draw[gi] = (word == 0 ? x : word == 1 ? y : word == 2 ? z : q) >> 12;
+        const uint32_t t = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)w.w);
+        draw[0][h] = (upper ? z : x) >> 12;
+        draw[1][h] = (upper ? t : y) >> 12;
     }
+}
+
+// the 8 scale bytes of a (column, chunk): lane q contributes bytes 2q, 2q+1; lane 0 of the quad
+// ends up with all of them
+__device__ __forceinline__ uint2 gather_quad_scales(uint32_t two_bytes, int q)
+{
+    uint32_t t = two_bytes << (16 * (q & 1));
+    t |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, kDppXor1, 0xF, 0xF, true);
+    const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, kDppXor2, 0xF, 0xF, true);
+    return make_uint2(t, other);
 }
 
 template <int kSrc, int kMode, bool kRht>
 __global__ __launch_bounds__(256) void quantize_cols_kernel(ColsArgs a)
 {
-    const int lane = threadIdx.x & 63, p = lane & 1;
+    const int lane = threadIdx.x & 63, q = lane & 3;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t chunk = (int64_t)blockIdx.x * kChunksPerBlock + (wave / kColHalves);   // wave-uniform
-    const int64_t j = ((int64_t)blockIdx.y * kColHalves + (wave % kColHalves)) * 32 + (lane >> 1);
+    const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;   // wave-uniform
+    const int64_t j0 = (int64_t)blockIdx.y * 32 + 2 * (lane >> 2);
     const TensorConsts tc = tensor_consts(kMode, *a.amax);
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *a.tensor_scale = tc.x32;
     if (chunk * 128 >= a.C) return;
-    const bool ok = j < a.R;
-    uint4 *pc = reinterpret_cast<uint4 *>(a.codes + j * (a.C / 2) + chunk * 64 + 32 * p);
-    uint32_t *psc = reinterpret_cast<uint32_t *>(a.scales + j * (a.C / 16) + chunk * 8 + 4 * p);
     if (tc.zero) {  // uniform: an all-zero tensor is emitted as zero bytes
-        if (ok) {
-            pc[0] = make_uint4(0u, 0u, 0u, 0u);
-            pc[1] = make_uint4(0u, 0u, 0u, 0u);
-            *psc = 0u;
-        }
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+            if (j0 + e < a.R) {
+                *reinterpret_cast<uint4 *>(a.codes + (j0 + e) * (a.C / 2) + chunk * 64 + 16 * q) = make_uint4(0u, 0u, 0u, 0u);
+                if (q == 0) *reinterpret_cast<uint2 *>(a.scales + (j0 + e) * (a.C / 16) + chunk * 8) = make_uint2(0u, 0u);
+            }
         return;
     }
-    float v[64];
-    load_half_chunk<kSrc, kRht>(v, a, chunk, (uint32_t)(ok ? j : a.R - 1), p);
-    if (kRht) fwht128_pair(v, p);
-    uint32_t draw[4] = {0u, 0u, 0u, 0u};
-    if (kMode == QII_MS_EDEN) octet_draws(draw, a.seed_sr, chunk, j, p);
-    uint32_t sc = 0u;
+    float v[2][32];
+    // R is even whenever this kernel is chosen, so a pair of columns is in range or not as a whole
+    const int64_t jc = j0 < a.R ? j0 : a.R - 2;
+    load_quarter_chunk<kSrc, kRht>(v, a, chunk, (uint32_t)jc, q);
+    if (kRht) {
+        fwht128_quad(v[0], q);
+        fwht128_quad(v[1], q);
+    }
+    uint32_t draw[2][2] = {{0u, 0u}, {0u, 0u}};
+    if (kMode == QII_MS_EDEN) octet_draws(draw, a.seed_sr, chunk, j0, q);
 #pragma unroll
-    for (int gp = 0; gp < 2; ++gp) {   // two groups = 16 bytes of codes per store
+    for (int e = 0; e < 2; ++e) {
         uint32_t codes[4];
+        uint32_t sc = 0u;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const int gi = 2 * gp + h;
-            const uint32_t b = quantize_group16<kMode>(v + 16 * gi, tc, draw[gi], a.seed_sr, j,
-                                                       chunk * 8 + 4 * p + gi, codes + 2 * h);
-            sc |= b << (8 * gi);
+            const uint32_t b = quantize_group16<kMode>(v[e] + 16 * h, tc, draw[e][h], a.seed_sr, j0 + e,
+                                                       chunk * 8 + 2 * q + h, codes + 2 * h);
+            sc |= b << (8 * h);
         }
-        if (ok) pc[gp] = make_uint4(codes[0], codes[1], codes[2], codes[3]);
+        const uint2 s8 = gather_quad_scales(sc, q);
+        if (j0 + e < a.R) {
+            *reinterpret_cast<uint4 *>(a.codes + (j0 + e) * (a.C / 2) + chunk * 64 + 16 * q) =
+                make_uint4(codes[0], codes[1], codes[2], codes[3]);
+            if (q == 0) *reinterpret_cast<uint2 *>(a.scales + (j0 + e) * (a.C / 16) + chunk * 8) = s8;
+        }
     }
-    if (ok) *psc = sc;
 }
 
 template <int kSrc, bool kRht>
 __global__ __launch_bounds__(256) void absmax_cols_kernel(ColsArgs a)
 {
     __shared__ float wave_m[4];
-    const int lane = threadIdx.x & 63, p = lane & 1;
+    const int lane = threadIdx.x & 63, q = lane & 3;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t chunk = (int64_t)blockIdx.x * kChunksPerBlock + (wave / kColHalves);   // wave-uniform
-    const int64_t j = ((int64_t)blockIdx.y * kColHalves + (wave % kColHalves)) * 32 + (lane >> 1);
+    const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;   // wave-uniform
+    const int64_t j0 = (int64_t)blockIdx.y * 32 + 2 * (lane >> 2);
     float m = 0.0f;
     if (chunk * 128 < a.C) {
-        float v[64];
-        // a clamped duplicate of a real column cannot change the maximum
-        load_half_chunk<kSrc, kRht>(v, a, chunk, (uint32_t)(j < a.R ? j : a.R - 1), p);
-        if (kRht) fwht128_pair(v, p);
+        float v[2][32];
+        // a clamped duplicate of a real column pair cannot change the maximum
+        load_quarter_chunk<kSrc, kRht>(v, a, chunk, (uint32_t)(j0 < a.R ? j0 : a.R - 2), q);
+        if (kRht) {
+            fwht128_quad(v[0], q);
+            fwht128_quad(v[1], q);
+        }
 #pragma unroll
-        for (int gi = 0; gi < 4; ++gi) m = fmaxf(m, group_absmax(v + 16 * gi));
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) m = fmaxf(m, group_absmax(v[e] + 16 * h));
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
@@ -243,15 +272,20 @@ ColsArgs make_args(const Source &src, int64_t R, int64_t C, uint64_t seed_rht, u
 
 dim3 cols_grid(int64_t R, int64_t C)
 {
-    return dim3((unsigned)((C / 128 + kChunksPerBlock - 1) / kChunksPerBlock),
-                (unsigned)((R + 32 * kColHalves - 1) / (32 * kColHalves)));
+    return dim3((unsigned)((C / 128 + 3) / 4), (unsigned)((R + 31) / 32));
 }
 
 }  // namespace
 
+// transposed sources whose quantized dimension is a multiple of 128 and whose rows allow the
+// two-column loads: an even number of columns and 4-byte (bf16) / 8-byte (f32) aligned pairs
 bool cols_kernels_apply(const Source &src, int64_t R, int64_t C)
 {
-    return src.transpose && C % 128 == 0 && (R + 63) / 64 <= 65535;
+    if (!src.transpose || C % 128 != 0 || R % 2 != 0 || (R + 31) / 32 > 65535) return false;
+    const uintptr_t p = reinterpret_cast<uintptr_t>(src.x);
+    if (src.kind == kSrcBF16) return src.ld % 2 == 0 && p % 4 == 0;
+    if (src.kind == kSrcF32) return src.ld % 2 == 0 && p % 8 == 0;
+    return true;   // NVFP4: stored columns are a multiple of 16
 }
 
 hipError_t launch_absmax_cols(const Source &src, int64_t R, int64_t C, int rht, uint64_t seed_rht,
