@@ -28,6 +28,7 @@ HBM_PEAK_GBPS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2500.0
 BYTES_PER_ELEM_QUANT = 2 + 0.5 + 0.0625      # bf16 in, packed FP4 + E4M3 scale out
 BYTES_PER_ELEM_ABSMAX = 2.0                  # bf16 in
+TRAFFIC_QUANT_ROWS_BYTES = 172_278_000       # measured, see the roofline entry below
 
 
 def main() -> int:
@@ -145,6 +146,19 @@ def main() -> int:
     avg = {k: float(np.mean(v)) for k, v in kernel_ms.items()}
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
+    # after the timed steps: the forward GEMM alone (the layer's dominant kernel), for its roofline line
+    gemm_ws = torch.empty(max(256, qii.qii_gemm_workspace_bytes(T, d_out, d_in)), dtype=torch.uint8, device=dev)
+    gemm_ms = []
+    for i in range(6):
+        e0, e1 = ev(), ev()
+        e0.record()
+        qii.qii_gemm_nvfp4(Xq, Wq, Y, gemm_ws)
+        e1.record()
+        torch.cuda.synchronize()
+        if i:
+            gemm_ms.append(e0.elapsed_time(e1))
+    gemm_tflops = 2.0 * T * d_in * d_out / (float(np.mean(gemm_ms)) * 1e-3) / 1e12
+
     n = R * C
     bytes_a1 = 2 * n * BYTES_PER_ELEM_QUANT
     value = bytes_a1 / ((avg["single_rows"] + avg["single_cols"]) * 1e-3) / 1e9
@@ -191,7 +205,15 @@ def main() -> int:
             "bound": "hbm",
             "achieved": round(quant_kernel_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(quant_kernel_gbps / HBM_PEAK_GBPS, 4),
-            "traffic": None,
+            # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by what the same
+            # counters read for a 512 MiB device copy (x2.0 and x1.0): profiles/bench_hbm_traffic.txt
+            "traffic": {"bytes": TRAFFIC_QUANT_ROWS_BYTES, "algorithmic_bytes": int(n * BYTES_PER_ELEM_QUANT),
+                        "valid_for": "8192x8192 bf16"} if (R, C) == (8192, 8192) else None,
+        },
+        "roofline_gemm": {
+            "kernel": f"gemm_kernel_v4<bf16 out> M={T} N={d_out} K={d_in} (incl. the two scale re-tiling launches)",
+            "bound": "mfma", "achieved": round(gemm_tflops, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(gemm_tflops / MFMA_F16_PEAK_TFLOPS, 4),
         },
     }
 
