@@ -180,13 +180,6 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const uint8_t *__restrict_
                         acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ti], fb[tj], acc[ti][tj], 0, 0, 0);
             }
         }
-        // ask the scheduler to slot the dequantization (VALU) of the next fragments under the
-        // matrix instructions: one MFMA, then five VALU ops, over the whole K tile
-#pragma unroll
-        for (int i = 0; i < 128; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
-        }
         if (kt + 1 < ktiles) {
             store_tile(st, stage_ptr(smem, (int)((kt + 1) & 1)));
             __syncthreads();
@@ -407,12 +400,6 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel_v2(const uint8_t *__restri
         // (after the last tile this reads a stale stage; the values are never used)
         read_raw(f0, smem + st_next * kStage2Bytes, 0, wm, wn, li, kb);
         mma_slice(acc, f1);
-        // slot the dequantization (VALU) of the next fragments under the matrix instructions
-#pragma unroll
-        for (int i = 0; i < 128; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
-        }
         // tile kt+2 (issued a whole tile ago) must have landed before anyone reads it, and
         // everyone must be done with stage st_cur before tile kt+3 overwrites it
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -475,18 +462,85 @@ __device__ __forceinline__ void issue_tile_loads4(uint8_t *stage, const uint8_t 
                                      (__attribute__((address_space(3))) void *)(stage + kOff4Bs + (wave * 64) * 16), 16, 0, 0);
 }
 
-// raw fragments of K slice j (64 elements, j = 0..3) of one stage for this lane
-__device__ __forceinline__ void read_raw4(RawFrag &f, const uint8_t *stage, int j, int wm, int wn, int li, int kb)
+// ---- fragment pipeline of the main kernel -------------------------------------------------
+// The compiler makes every LDS read that follows a global_load_lds wait for that load
+// (it cannot tell the two LDS regions apart), which would serialise the fetch of the next
+// K tile with the multiplication of the current one.  The fragment reads are therefore
+// written as inline assembly, with their own wait: a read block only names its
+// destination registers, and the matching wait "produces" them for the code that follows.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+struct RawFrag4 {
+    u32x4 a[4], b[4];       // 32 codes (16 bytes) of K for 4 row blocks of A and of B
+    uint32_t sa[4], sb[4];  // their two scale bytes
+};
+
+struct FragAddr {
+    uint32_t a, b, sa, sb;  // LDS byte addresses of this lane's row 0 pieces in stage 0
+    uint32_t xo[4];         // swizzled 16-byte slot of K slice j, times 16
+};
+
+template <int J>
+__device__ __forceinline__ void frag_read_issue(RawFrag4 &f, const FragAddr &fa, uint32_t stage_off)
 {
-    const int seg = 2 * j + kb;
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int rowa = wm * 128 + t * 32 + li, rowb = wn * 128 + t * 32 + li;
-        f.a[t] = *reinterpret_cast<const uint4 *>(stage + kOff4A + (rowa * 8 + (seg ^ (rowa & 7))) * 16);
-        f.b[t] = *reinterpret_cast<const uint4 *>(stage + kOff4B + (rowb * 8 + (seg ^ (rowb & 7))) * 16);
-        f.sa[t] = *reinterpret_cast<const uint16_t *>(stage + kOff4As + rowa * 16 + 4 * j + 2 * kb);
-        f.sb[t] = *reinterpret_cast<const uint16_t *>(stage + kOff4Bs + rowb * 16 + 4 * j + 2 * kb);
-    }
+    const uint32_t va = fa.a + fa.xo[J] + stage_off, vb = fa.b + fa.xo[J] + stage_off;
+    const uint32_t vsa = fa.sa + stage_off, vsb = fa.sb + stage_off;
+    // rows 32 t: codes 32 * 128 bytes apart, re-tiled scales 32 * 16 bytes apart
+#define QII_RD(T)                                                                                       \
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f.a[T]) : "v"(va), "n"(T * 4096));              \
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f.b[T]) : "v"(vb), "n"(T * 4096));              \
+    asm volatile("ds_read_u16 %0, %1 offset:%2" : "=v"(f.sa[T]) : "v"(vsa), "n"(T * 512 + 4 * J));      \
+    asm volatile("ds_read_u16 %0, %1 offset:%2" : "=v"(f.sb[T]) : "v"(vsb), "n"(T * 512 + 4 * J))
+    QII_RD(0); QII_RD(1); QII_RD(2); QII_RD(3);
+#undef QII_RD
+}
+
+// all outstanding LDS reads have landed; ties the registers of f to the wait
+__device__ __forceinline__ void frag_read_wait(RawFrag4 &f)
+{
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.b[0]), "+v"(f.b[1]),
+                   "+v"(f.b[2]), "+v"(f.b[3]), "+v"(f.sa[0]), "+v"(f.sa[1]), "+v"(f.sa[2]), "+v"(f.sa[3]),
+                   "+v"(f.sb[0]), "+v"(f.sb[1]), "+v"(f.sb[2]), "+v"(f.sb[3]));
+}
+
+// half of one fragment (4 of its 8 values): two conversions and two packed multiplies
+template <int H>
+__device__ __forceinline__ void dequant_half(half8_t &dst, uint32_t codes, uint32_t scale16x2)
+{
+    const half2_t s2 = __builtin_bit_cast(half2_t, scale16x2);
+    const half2_t h0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, 256.0f, 2 * H) * s2;
+    const half2_t h1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, 256.0f, 2 * H + 1) * s2;
+    dst[4 * H] = h0[0]; dst[4 * H + 1] = h0[1]; dst[4 * H + 2] = h1[0]; dst[4 * H + 3] = h1[1];
+}
+
+struct Frags {
+    half8_t a[4], b[4];
+};
+
+// chunk I (0..15) of the dequantization of dword D of raw fragments f into nx:
+// fragment I/2 (0..3 = A, 4..7 = B), half I%2
+template <int I, int D>
+__device__ __forceinline__ void dequant_chunk(Frags &nx, const RawFrag4 &f)
+{
+    constexpr int t = (I >> 1) & 3, h = I & 1;
+    if (I < 8) dequant_half<h>(nx.a[t], f.a[t][D], scale_pair(f.sa[t], D >> 1));
+    else dequant_half<h>(nx.b[t], f.b[t][D], scale_pair(f.sb[t], D >> 1));
+}
+
+// One step = 16 matrix instructions on the fragments in cu, with the fragments of the next
+// step (dword D of f) dequantized into nx in between, one chunk per matrix instruction; the
+// scheduling barriers keep that order, so the conversions run in the shadow of the matrix pipe.
+template <int D>
+__device__ __forceinline__ void mma_step(floatx16 (&acc)[4][4], const Frags &cu, Frags &nx, const RawFrag4 &f)
+{
+#define QII_MMA(I)                                                                                          \
+    acc[(I) >> 2][(I) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(cu.a[(I) >> 2], cu.b[(I) & 3],          \
+                                                                    acc[(I) >> 2][(I) & 3], 0, 0, 0);       \
+    dequant_chunk<I, D>(nx, f);                                                                             \
+    __builtin_amdgcn_sched_barrier(0)
+    QII_MMA(0); QII_MMA(1); QII_MMA(2); QII_MMA(3); QII_MMA(4); QII_MMA(5); QII_MMA(6); QII_MMA(7);
+    QII_MMA(8); QII_MMA(9); QII_MMA(10); QII_MMA(11); QII_MMA(12); QII_MMA(13); QII_MMA(14); QII_MMA(15);
+#undef QII_MMA
 }
 
 template <bool kBf16Out>
@@ -524,36 +578,83 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel_v4(const uint8_t *__restri
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
+    FragAddr fa;
+    {
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
+        fa.a = lds0 + kOff4A + (wm * 128 + li) * 128;
+        fa.b = lds0 + kOff4B + (wn * 128 + li) * 128;
+        fa.sa = lds0 + kOff4As + (wm * 128 + li) * 16 + 2 * kb;
+        fa.sb = lds0 + kOff4Bs + (wn * 128 + li) * 16 + 2 * kb;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) fa.xo[j] = (uint32_t)(((2 * j + kb) ^ (li & 7)) * 16);
+    }
+
     const int ktiles = (int)(K / BK4);
     issue_tile_loads4(smem, a_codes, a_tiled, b_codes, b_tiled, M, N, K, m0, n0, 0, wave);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    if (ktiles > 1)
+        issue_tile_loads4(smem + kStage4Bytes, a_codes, a_tiled, b_codes, b_tiled, M, N, K, m0, n0, 1, wave);
 
-    RawFrag f0, f1;
-    for (int kt = 0; kt < ktiles; ++kt) {
-        const uint8_t *cur = smem + (kt & 1) * kStage4Bytes;
-        if (kt + 1 < ktiles)
-            issue_tile_loads4(smem + ((kt + 1) & 1) * kStage4Bytes, a_codes, a_tiled, b_codes, b_tiled, M, N, K,
-                              m0, n0, kt + 1, wave);
-        read_raw4(f0, cur, 0, wm, wn, li, kb);
-        read_raw4(f1, cur, 1, wm, wn, li, kb);
-        mma_slice(acc, f0);
-        read_raw4(f0, cur, 2, wm, wn, li, kb);
-        mma_slice(acc, f1);
-        read_raw4(f1, cur, 3, wm, wn, li, kb);
-        mma_slice(acc, f0);
-        mma_slice(acc, f1);
-        // slot the dequantization (VALU) of the next fragments under the matrix instructions
+    // Pipeline over K, in steps of 16 columns of K per lane half (4 steps = one 64-wide slice,
+    // 4 slices = one tile).  While step n multiplies, the fragments of step n+1 are dequantized;
+    // the raw fragments of slice g live in fe (g even) or fo (g odd) and are re-filled with
+    // slice g+2 at the start of step (g, 3), once the last conversion of slice g is done, a
+    // full slice ahead of their first use.  The hand-over between the two LDS stages sits at
+    // step (2, 3) of a tile: this wave's last read of the current stage (slice 3) has landed,
+    // so after the barrier tile kt+1, issued a whole tile earlier, is complete in the other
+    // stage and the current stage can take tile kt+2.
+    RawFrag4 fe, fo;
+    Frags x, y;
+    frag_read_issue<0>(fe, fa, 0);
+    frag_read_issue<1>(fo, fa, 0);
+    frag_read_wait(fe);   // (waits for both)
 #pragma unroll
-        for (int i = 0; i < 256; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
-        }
-        // tile kt+1 (issued a whole tile ago) must have landed before anyone reads it, and
-        // everyone must be done with this stage before tile kt+2 overwrites it
+    for (int t = 0; t < 4; ++t) {
+        dequant_half<0>(x.a[t], fe.a[t][0], scale_pair(fe.sa[t], 0));
+        dequant_half<1>(x.a[t], fe.a[t][0], scale_pair(fe.sa[t], 0));
+        dequant_half<0>(x.b[t], fe.b[t][0], scale_pair(fe.sb[t], 0));
+        dequant_half<1>(x.b[t], fe.b[t][0], scale_pair(fe.sb[t], 0));
+    }
+    for (int kt = 0; kt < ktiles; ++kt) {
+        const uint32_t cur_off = (kt & 1) * kStage4Bytes, nxt_off = ((kt + 1) & 1) * kStage4Bytes;
+        // slice 0 (raw: fe)
+        mma_step<1>(acc, x, y, fe);
+        mma_step<2>(acc, y, x, fe);
+        mma_step<3>(acc, x, y, fe);
+        frag_read_wait(fo);
+        frag_read_issue<2>(fe, fa, cur_off);
+        mma_step<0>(acc, y, x, fo);
+        // slice 1 (raw: fo)
+        mma_step<1>(acc, x, y, fo);
+        mma_step<2>(acc, y, x, fo);
+        mma_step<3>(acc, x, y, fo);
+        frag_read_wait(fe);
+        frag_read_issue<3>(fo, fa, cur_off);
+        mma_step<0>(acc, y, x, fe);
+        // slice 2 (raw: fe)
+        mma_step<1>(acc, x, y, fe);
+        mma_step<2>(acc, y, x, fe);
+        mma_step<3>(acc, x, y, fe);
+        frag_read_wait(fo);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
+        if (kt + 2 < ktiles)
+            issue_tile_loads4(smem + cur_off, a_codes, a_tiled, b_codes, b_tiled, M, N, K, m0, n0, kt + 2, wave);
+        // (after the last tile the two reads below fetch a stale stage; the values are never used)
+        frag_read_issue<0>(fe, fa, nxt_off);
+        mma_step<0>(acc, y, x, fo);
+        // slice 3 (raw: fo)
+        mma_step<1>(acc, x, y, fo);
+        mma_step<2>(acc, y, x, fo);
+        mma_step<3>(acc, x, y, fo);
+        frag_read_wait(fe);
+        frag_read_issue<1>(fo, fa, nxt_off);
+        mma_step<0>(acc, y, x, fe);
     }
+    // the last read block is still in flight: its registers and the stages are reused below
+    frag_read_wait(fo);
+    __syncthreads();
     store_tile_through_lds<kBf16Out>(acc, smem, (*a_ts) * (*b_ts), Cout, ldc, M, N, m0, n0, wave, wm, wn, lane, li, kb);
 }
 

@@ -187,6 +187,43 @@ __device__ __forceinline__ void make_masks(uint32_t sign16, uint32_t mask[kBf16 
     }
 }
 
+// One quad of rows for one lane.  Once a row's raw words are unpacked its slot is free, so with
+// kPrefetch the same row of the block's next quad (qn) is fetched right away, four rows of
+// arithmetic ahead of its use; the block's last quad runs the copy without the loads.
+template <bool kBf16, int kMode, bool kRht, bool kPrefetch>
+__device__ __forceinline__ void quantize_quad(const RowsArgs &a, const LaneSetup &L, const TensorConsts &tc,
+                                              const uint32_t *mask, Raw<kBf16> raw[4], int64_t quad,
+                                              int64_t qn, int64_t G, int64_t gc)
+{
+    uint32_t draw[4] = {0u, 0u, 0u, 0u};
+    if (kMode == QII_MS_EDEN) {
+        const U4 w = philox_seeded(a.seed_sr, (uint32_t)L.g, (uint32_t)quad, 0, kStreamScale);
+        draw[0] = w.x >> 12; draw[1] = w.y >> 12; draw[2] = w.z >> 12; draw[3] = w.w >> 12;
+    }
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int64_t row = quad * 4 + it;
+        float v[16];
+        unpack_signed<kBf16, kRht>(raw[it], v, mask);
+        if (kPrefetch) {
+            const int64_t rn = qn * 4 + it;
+            load_raw<kBf16>(raw[it], a, rn < a.R ? rn : a.R - 1, gc);
+        }
+        if (kRht) rht128_lane(v, L);
+        uint32_t packed[2];
+        const uint32_t b = quantize_group16<kMode>(v, tc, draw[it], a.seed_sr, row, L.g, packed);
+        if (L.col_ok && row < a.R)
+            *reinterpret_cast<uint2 *>(a.codes + (row * a.C + L.g * 16) / 2) = make_uint2(packed[0], packed[1]);
+        if (G % 8 == 0) {   // whole octets: one 8-byte store per chunk
+            const uint2 sc = gather_scale_bytes(b, L.blk);
+            if (L.col_ok && row < a.R && L.blk == 0)
+                *reinterpret_cast<uint2 *>(a.scales + row * G + L.g) = sc;
+        } else if (L.col_ok && row < a.R) {
+            a.scales[row * G + L.g] = (uint8_t)b;
+        }
+    }
+}
+
 template <bool kBf16, int kMode, bool kRht>
 __global__ __launch_bounds__(256) void quantize_rows_kernel(RowsArgs a)
 {
@@ -210,34 +247,11 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowsArgs a)
     make_masks<kBf16>(L.sign16, mask);
     const int64_t gc = L.col_ok ? L.g : G - 1;
     Raw<kBf16> raw[4];
-    load_quad<kBf16>(raw, a, blockIdx.x, gc);
-    for (int64_t quad = blockIdx.x; quad < quads; quad += gridDim.x) {
-        const int64_t qn = quad + gridDim.x;
-        uint32_t draw[4] = {0u, 0u, 0u, 0u};
-        if (kMode == QII_MS_EDEN) {
-            const U4 w = philox_seeded(a.seed_sr, (uint32_t)L.g, (uint32_t)quad, 0, kStreamScale);
-            draw[0] = w.x >> 12; draw[1] = w.y >> 12; draw[2] = w.z >> 12; draw[3] = w.w >> 12;
-        }
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int64_t row = quad * 4 + it;
-            float v[16];
-            unpack_signed<kBf16, kRht>(raw[it], v, mask);
-            if (kRht) rht128_lane(v, L);
-            uint32_t packed[2];
-            const uint32_t b = quantize_group16<kMode>(v, tc, draw[it], a.seed_sr, row, L.g, packed);
-            if (L.col_ok && row < a.R)
-                *reinterpret_cast<uint2 *>(a.codes + (row * a.C + L.g * 16) / 2) = make_uint2(packed[0], packed[1]);
-            if (G % 8 == 0) {   // whole octets: one 8-byte store per chunk
-                const uint2 sc = gather_scale_bytes(b, L.blk);
-                if (L.col_ok && row < a.R && L.blk == 0)
-                    *reinterpret_cast<uint2 *>(a.scales + row * G + L.g) = sc;
-            } else if (L.col_ok && row < a.R) {
-                a.scales[row * G + L.g] = (uint8_t)b;
-            }
-        }
-        if (qn < quads) load_quad<kBf16>(raw, a, qn, gc);
-    }
+    int64_t quad = blockIdx.x;             // the grid never has more blocks than quads
+    load_quad<kBf16>(raw, a, quad, gc);
+    for (; quad + gridDim.x < quads; quad += gridDim.x)
+        quantize_quad<kBf16, kMode, kRht, true>(a, L, tc, mask, raw, quad, quad + gridDim.x, G, gc);
+    quantize_quad<kBf16, kMode, kRht, false>(a, L, tc, mask, raw, quad, quad, G, gc);
 }
 
 template <bool kBf16, bool kRht>
