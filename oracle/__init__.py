@@ -20,7 +20,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "qii_oracle.c")
 _LIB = os.path.join(_HERE, "libqii_oracle.so")
 
-RTN, SR, MS_EDEN = 0, 1, 2
+RTN, SR, MS_EDEN, RTN_46 = 0, 1, 2, 3
 F32, BF16 = 0, 1
 
 
@@ -273,12 +273,13 @@ def gemm_sampled(a: NVFP4, b: NVFP4, ms: np.ndarray, ns: np.ndarray):
 SEED_RHT_DGRAD, SEED_RHT_WGRAD, SEED_SR_E, SEED_SR_WT, SEED_SR_ET, SEED_SR_XT = range(6)
 
 
-def linear_fwd(X: np.ndarray, W: np.ndarray):
+def linear_fwd(X: np.ndarray, W: np.ndarray, mode: int = RTN):
     """Sec. 5, forward pass: RTN-quantize X (T x d_in) and W (d_out x d_in) along d_in with the
-    native 1x16 scales and no rotation, multiply, keep the quantized tensors.
+    native 1x16 scales and no rotation, multiply, keep the quantized tensors; mode RTN_46 adds
+    the per-block 4/6 choice of Sec. 4.1.
     Returns (Xq, Wq); Y = gemm(Xq, Wq) is left to the caller (it is O(T d_in d_out))."""
-    Xq = quantize(X, RTN, rht_group=0)
-    Wq = quantize(W, RTN, rht_group=0)
+    Xq = quantize(X, mode, rht_group=0)
+    Wq = quantize(W, mode, rht_group=0)
     return Xq, Wq
 
 

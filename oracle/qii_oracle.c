@@ -20,6 +20,10 @@
  *             the three equations of the clipping quantizer Q_RTN(x, s) with
  *             cap 256 and s = 6*(16/17)/0.93.
  *   Table 1   row "RTN 1x16": plain round-to-nearest NVFP4 (s = 6, cap 448).
+ *   Sec. 4.1  "Forward Pass Using 4/6" and Table 1 row "+4/6": per block, the
+ *             round-to-nearest quantization is done twice, with the block
+ *             maximum mapped to 6 and to 4, and the one with the lower squared
+ *             error is kept (mode RTN_46).
  *   Sec. 5    forward pass (RTN on X and W, save the quantized tensors) and
  *             backward pass (dequantize, transpose, re-quantize with MS-EDEN,
  *             MS-EDEN of E and E^T, two GEMMs; rotations cancel on the inner
@@ -37,6 +41,7 @@
 #define QO_RTN 0
 #define QO_SR 1
 #define QO_MS_EDEN 2
+#define QO_RTN_46 3
 
 #define QO_F32 0
 #define QO_BF16 1
@@ -302,13 +307,46 @@ int qo_rht(const void *x, int dtype, int64_t rows, int64_t cols, int64_t ld, int
 /*   RTN     (Table 1, "RTN 1x16")        s = 6,             cap 448        */
 /*   SR      (Sec. 3.1, Q_SR)             s = 6*16/17,       cap 448        */
 /*   MS-EDEN (Sec. 3.3, Q_RTN(x, s))      s = 6*16/17/0.93,  cap 256        */
+/*   RTN+4/6 (Sec. 4.1)                   s = 6 (and 4),     cap 256: the   */
+/*           scale of a block mapped to 4 is 1.5 times that of the same     */
+/*           block mapped to 6, and 1.5 * 256 = 384 still is an E4M3 value  */
 /* s_override > 0 replaces s (Algorithm 1 takes s as an input).             */
 static void mode_constants(int mode, float s_override, float *s, float *cap)
 {
     if (mode == QO_RTN) { *s = 6.0f; *cap = 448.0f; }
+    else if (mode == QO_RTN_46) { *s = 6.0f; *cap = 256.0f; }
     else if (mode == QO_SR) { *s = (float)(96.0 / 17.0); *cap = 448.0f; }
     else { *s = (float)(96.0 / 17.0 / 0.93); *cap = 256.0f; }
     if (s_override > 0.0f) *s = s_override;
+}
+
+/* One candidate of the 4/6 choice (Sec. 4.1): round the 16 values of a      */
+/* group to nearest with the group maximum mapped to `level` (6 or 4).      */
+/* Returns the scale byte, the codes (8 bytes) and the squared error of the */
+/* de-quantized group: d_i = x_i - c_i * (x^FP8 * x^FP32) as one fused      */
+/* multiply-add, summed as a fused multiply-add chain in index order.       */
+static uint8_t rtn_candidate(const float *yg, float gmax, float x32, float level, uint8_t *cg,
+                             float *err_out)
+{
+    uint8_t b = qo_e4m3_rtn(gmax / (x32 * level));
+    float err = 0.0f;
+    memset(cg, 0, 8);
+    if (b == 0) { /* scale under-flowed: all codes zero, error = <x, x> */
+        for (int k = 0; k < 16; ++k) err = fmaf(yg[k], yg[k], err);
+        *err_out = err;
+        return 0;
+    }
+    const float p = qo_e4m3_decode(b) * x32;
+    const float inv = 1.0f / p;
+    for (int k = 0; k < 16; ++k) {
+        uint8_t code = qo_e2m1_rtn(yg[k] * inv);
+        float d = fmaf(-qo_e2m1_decode(code), p, yg[k]);
+        err = fmaf(d, d, err);
+        if (k & 1) cg[k >> 1] |= (uint8_t)(code << 4);
+        else cg[k >> 1] = code;
+    }
+    *err_out = err;
+    return b;
 }
 
 /* Quantize an already rotated R x C f32 matrix y, groups of 16 along rows. */
@@ -338,6 +376,18 @@ static void quantize_rotated(const float *y, int64_t R, int64_t C, int mode, flo
             for (int k = 0; k < 16; ++k) {
                 float a = fabsf(yg[k]);
                 if (a > gmax) gmax = a;
+            }
+            if (mode == QO_RTN_46) {
+                /* Sec. 4.1: keep the candidate with the lower squared error; */
+                /* the usual mapping to 6 wins ties                          */
+                uint8_t c6[8], c4[8];
+                float e6, e4;
+                uint8_t b6 = rtn_candidate(yg, gmax, x32, 6.0f, c6, &e6);
+                uint8_t b4 = rtn_candidate(yg, gmax, x32, 4.0f, c4, &e4);
+                int use4 = e4 < e6;
+                memcpy(cg, use4 ? c4 : c6, 8);
+                scales[r * G + g] = use4 ? b4 : b6;
+                continue;
             }
             uint8_t b = qo_e4m3_rtn(gmax / (x32 * s));
             if (b == 0) { /* scale under-flowed to 0: the group is all zeros */
@@ -388,7 +438,7 @@ int qo_quantize(const void *x, int dtype, int64_t rows, int64_t cols, int64_t ld
                 const float *amax_in, float s_override, uint8_t *codes, uint8_t *scales,
                 float *tensor_scale)
 {
-    if (mode != QO_RTN && mode != QO_SR && mode != QO_MS_EDEN) return QO_BAD;
+    if (mode != QO_RTN && mode != QO_SR && mode != QO_MS_EDEN && mode != QO_RTN_46) return QO_BAD;
     int64_t R = transpose ? cols : rows, C = transpose ? rows : cols;
     float *y = (float *)malloc(sizeof(float) * (size_t)(R * C > 0 ? R * C : 1));
     if (!y) return QO_BAD;

@@ -167,13 +167,58 @@ def test_table1_mse_on_standard_normal(oracle):
     rng = np.random.default_rng(5)
     x = rng.standard_normal((512, 2048)).astype(np.float32)
     got = {}
-    for name, mode in [("RTN", 0), ("SR", 1), ("MS_EDEN", 2)]:
+    for name, mode in [("RTN", 0), ("SR", 1), ("MS_EDEN", 2), ("RTN_46", 3)]:
         q = oracle.quantize(x, mode, seed_rht=1, seed_sr=2)
         y, _ = oracle.rht(x, seed_rht=1)
         got[name] = np.mean((dequant_f64(q) - y) ** 2) * 1e3
         assert got[name] == pytest.approx(rows[name], rel=0.03)
     # the abstract: more than 2x lower quantization error than SR
     assert got["SR"] / got["MS_EDEN"] > 2.0
+
+
+def test_four_over_six_keeps_the_better_of_two_rtn_candidates(oracle):
+    """Sec. 4.1: every group of the 4/6 quantizer is the round-to-nearest quantization with the
+    group maximum mapped to 6 or to 4 (scale byte = library cast of gmax / (x32 * level), codes =
+    brute-force nearest), and the kept candidate is the one with the smaller squared error
+    (recomputed here in double; near-ties within 1e-5 relative may go either way)."""
+    rng = np.random.default_rng(14)
+    x = (rng.standard_t(3, size=(64, 256)) * 0.1).astype(np.float32)
+    x[5, 32:48] = 0.0                       # an all-zero group
+    x[6, 0:16] *= 1e-6                      # a group whose scale under-flows
+    q = oracle.quantize(x, 3, rht_group=0)
+    amax = np.abs(x).max()
+    x32 = np.float32(amax) / (np.float32(6.0) * np.float32(256.0))
+    assert q.tensor_scale[0] == x32
+    gmax = np.abs(x).reshape(64, 16, 16).max(-1)
+    xg = x.reshape(64, 16, 16).astype(np.float64)
+    cand = {}
+    for level in (6.0, 4.0):
+        r = (gmax / (x32 * np.float32(level))).astype(np.float32)
+        b = torch.from_numpy(r).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+        p = e4m3_values(b).astype(np.float64) * np.float64(x32)
+        with np.errstate(divide="ignore", invalid="ignore"):
+            qn = np.where(p[..., None] > 0, xg / p[..., None], 0.0)
+        idx = np.abs(np.abs(qn)[..., None] - E2M1[:8]).argmin(-1)
+        deq = np.sign(qn) * E2M1[idx] * p[..., None]
+        cand[level] = (b, idx, ((xg - deq) ** 2).sum(-1))
+    got_b = q.scales
+    got_mag = (unpack(q.codes) & 7).reshape(64, 16, 16)
+    e6, e4 = cand[6.0][2], cand[4.0][2]
+    want4 = e4 < e6
+    close = np.abs(e4 - e6) <= 1e-5 * np.maximum(e4, e6)
+    is4 = (got_b == cand[4.0][0]) & (E2M1[got_mag] == E2M1[cand[4.0][1]]).all(-1)
+    is6 = (got_b == cand[6.0][0]) & (E2M1[got_mag] == E2M1[cand[6.0][1]]).all(-1)
+    # exact ties of the nearest-code search aside, every group is one of the two candidates
+    assert (is4 | is6).mean() > 0.999
+    ok = np.where(want4, is4, is6) | (close & (is4 | is6))
+    assert ok.mean() > 0.999
+    assert 0.2 < want4.mean() < 0.8         # both branches are really in use
+    live = np.repeat(got_b != 0, 16, axis=1)     # groups with a zero scale byte carry zero codes
+    assert np.array_equal(((unpack(q.codes) >> 3) == 1)[live], np.signbit(x)[live])
+    # zero group: zero scale and codes; the choice never makes the error worse than plain RTN
+    assert got_b[5, 2] == 0 and not q.codes[5, 16:24].any()
+    err46 = ((dequant_f64(q) - x) ** 2).reshape(64, 16, 16).sum(-1)
+    assert np.all(err46 <= np.minimum(e4, e6) * (1 + 1e-5) + 1e-30)
 
 
 def test_eden_grid_max_minimises_mse(oracle):
