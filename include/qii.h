@@ -56,8 +56,14 @@ typedef enum {
  *               rounding to FP4; never clips; unbiased.
  *   QII_MS_EDEN Algorithm 1 (Sec. 3.3): Q_RTN(x, s) with s = 6*16/17/0.93 and cap 256,
  *               then the per-16 EDEN factor merged into the E4M3 scale by stochastic
- *               rounding; unbiased after the inverse rotation. */
-typedef enum { QII_RTN = 0, QII_SR = 1, QII_MS_EDEN = 2 } qii_mode;
+ *               rounding; unbiased after the inverse rotation.
+ *   QII_RTN_46  round to nearest with the per-block "4/6" choice of Sec. 4.1 (Table 1,
+ *               row "+4/6"; the forward pass of Sec. 5): each group of 16 is quantized
+ *               twice, with its maximum mapped to 6 and to 4, and the candidate with the
+ *               smaller squared error is kept (ties: 6).  Scale cap 256, so that the 1.5
+ *               times larger scale of a block mapped to 4 (at most 384) is an E4M3 value.
+ *               Deterministic; biased, hence forward pass only. */
+typedef enum { QII_RTN = 0, QII_SR = 1, QII_MS_EDEN = 2, QII_RTN_46 = 3 } qii_mode;
 
 typedef enum { QII_F32 = 0, QII_BF16 = 1 } qii_dtype;
 
@@ -138,6 +144,14 @@ qii_status qii_gemm_nvfp4(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_d
 qii_status qii_linear_fwd(const void *X, const void *W, qii_dtype dt, int64_t T, int64_t d_in,
                           int64_t d_out, void *Y, qii_dtype y_dt, const qii_nvfp4 *Xq_saved,
                           const qii_nvfp4 *Wq_saved, void *ws, size_t ws_bytes, void *stream);
+
+/* The same forward pass with the rounding scheme of X and W chosen by the caller:
+ * QII_RTN (as qii_linear_fwd) or QII_RTN_46, the forward pass of Sec. 5 with the 4/6
+ * choice of Sec. 4.1.  Other modes are rejected (the forward pass is deterministic).   */
+qii_status qii_linear_fwd_mode(const void *X, const void *W, qii_dtype dt, int64_t T, int64_t d_in,
+                               int64_t d_out, qii_mode mode, void *Y, qii_dtype y_dt,
+                               const qii_nvfp4 *Xq_saved, const qii_nvfp4 *Wq_saved, void *ws,
+                               size_t ws_bytes, void *stream);
 
 /* Backward pass of one linear layer (Sec. 5): with six sub-seeds derived from `seed`
  * (0: rotation of the dX GEMM, 1: rotation of the dW GEMM, 2..5: rounding seeds of

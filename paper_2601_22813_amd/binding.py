@@ -16,12 +16,13 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libqii.so")
 
-RTN, SR, MS_EDEN = 0, 1, 2
+RTN, SR, MS_EDEN, RTN_46 = 0, 1, 2, 3
 F32, BF16 = 0, 1
 
 EXPORTS = [
     "qii_rht", "qii_absmax", "qii_quantize_nvfp4", "qii_requantize_nvfp4", "qii_dequantize_nvfp4",
-    "qii_gemm_nvfp4", "qii_linear_fwd", "qii_linear_bwd", "qii_quantize_workspace_bytes",
+    "qii_gemm_nvfp4", "qii_linear_fwd", "qii_linear_fwd_mode", "qii_linear_bwd",
+    "qii_quantize_workspace_bytes",
     "qii_gemm_workspace_bytes", "qii_linear_fwd_workspace_bytes", "qii_linear_bwd_workspace_bytes",
     "qii_derive_seed", "qii_status_string", "qii_last_error", "qii_version",
 ]
@@ -57,9 +58,11 @@ def lib() -> ctypes.CDLL:
         L.qii_dequantize_nvfp4.argtypes = [nv, vp, vp]
         L.qii_gemm_nvfp4.argtypes = [nv, nv, vp, c.c_int, i64, vp, sz, vp]
         L.qii_linear_fwd.argtypes = [vp, vp, c.c_int, i64, i64, i64, vp, c.c_int, nv, nv, vp, sz, vp]
+        L.qii_linear_fwd_mode.argtypes = [vp, vp, c.c_int, i64, i64, i64, c.c_int, vp, c.c_int, nv, nv, vp, sz, vp]
         L.qii_linear_bwd.argtypes = [vp, c.c_int, nv, nv, u64, vp, vp, c.c_int, vp, sz, vp]
         for name in ("qii_rht", "qii_absmax", "qii_quantize_nvfp4", "qii_requantize_nvfp4",
-                     "qii_dequantize_nvfp4", "qii_gemm_nvfp4", "qii_linear_fwd", "qii_linear_bwd"):
+                     "qii_dequantize_nvfp4", "qii_gemm_nvfp4", "qii_linear_fwd", "qii_linear_fwd_mode",
+                     "qii_linear_bwd"):
             getattr(L, name).restype = c.c_int
         L.qii_quantize_workspace_bytes.argtypes = []
         L.qii_quantize_workspace_bytes.restype = sz
@@ -196,6 +199,16 @@ def qii_linear_fwd(X: torch.Tensor, W: torch.Tensor, Y: torch.Tensor, Xq: NVFP4T
     _check(lib().qii_linear_fwd(X.data_ptr(), W.data_ptr(), _dt(X), T, d_in, d_out, Y.data_ptr(), _dt(Y),
                                 ctypes.byref(sx), ctypes.byref(sw), ws.data_ptr(),
                                 ws.numel() * ws.element_size(), _stream()))
+
+
+def qii_linear_fwd_mode(X: torch.Tensor, W: torch.Tensor, mode: int, Y: torch.Tensor, Xq: NVFP4Tensor,
+                        Wq: NVFP4Tensor, ws: torch.Tensor):
+    T, d_in = X.shape
+    d_out = W.shape[0]
+    sx, sw = Xq.c_struct(), Wq.c_struct()
+    _check(lib().qii_linear_fwd_mode(X.data_ptr(), W.data_ptr(), _dt(X), T, d_in, d_out, mode, Y.data_ptr(),
+                                     _dt(Y), ctypes.byref(sx), ctypes.byref(sw), ws.data_ptr(),
+                                     ws.numel() * ws.element_size(), _stream()))
 
 
 def qii_linear_bwd(dY: torch.Tensor, Xq: NVFP4Tensor, Wq: NVFP4Tensor, seed: int, dX: torch.Tensor,

@@ -96,7 +96,7 @@ qii_status quantize_source(const qii::Source &src, int64_t R, int64_t C, qii_mod
                            uint64_t seed_rht, uint64_t seed_sr, const float *amax_in,
                            const qii_nvfp4 *out, float *amax_slot, hipStream_t s)
 {
-    if (mode != QII_RTN && mode != QII_SR && mode != QII_MS_EDEN) return fail(QII_INVALID_ARG, "bad mode %d", (int)mode);
+    if (mode != QII_RTN && mode != QII_SR && mode != QII_MS_EDEN && mode != QII_RTN_46) return fail(QII_INVALID_ARG, "bad mode %d", (int)mode);
     qii_status st = check_nvfp4(out, "out");
     if (st != QII_OK) return st;
     if (out->rows != R || out->cols != C)
@@ -282,20 +282,29 @@ qii_status qii_gemm_nvfp4(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_d
     return QII_OK;
 }
 
-qii_status qii_linear_fwd(const void *X, const void *W, qii_dtype dt, int64_t T, int64_t d_in,
-                          int64_t d_out, void *Y, qii_dtype y_dt, const qii_nvfp4 *Xq,
-                          const qii_nvfp4 *Wq, void *ws, size_t ws_bytes, void *stream)
+qii_status qii_linear_fwd_mode(const void *X, const void *W, qii_dtype dt, int64_t T, int64_t d_in,
+                               int64_t d_out, qii_mode mode, void *Y, qii_dtype y_dt, const qii_nvfp4 *Xq,
+                               const qii_nvfp4 *Wq, void *ws, size_t ws_bytes, void *stream)
 {
+    if (mode != QII_RTN && mode != QII_RTN_46)
+        return fail(QII_INVALID_ARG, "the forward pass takes QII_RTN or QII_RTN_46, not mode %d", (int)mode);
     if (d_in % 32 != 0) return fail(QII_BAD_SHAPE, "d_in must be a multiple of 32");
     if (!ws || ws_bytes < qii_linear_fwd_workspace_bytes(T, d_in, d_out) || !aligned(ws, kSlot))
         return fail(QII_WORKSPACE_TOO_SMALL, "linear_fwd needs %zu bytes of 256-byte aligned workspace",
                     qii_linear_fwd_workspace_bytes(T, d_in, d_out));
     uint8_t *p = reinterpret_cast<uint8_t *>(ws);
-    qii_status st = qii_quantize_nvfp4(X, dt, T, d_in, d_in, 0, QII_RTN, 0, 0, 0, nullptr, Xq, p, kSlot, stream);
+    qii_status st = qii_quantize_nvfp4(X, dt, T, d_in, d_in, 0, mode, 0, 0, 0, nullptr, Xq, p, kSlot, stream);
     if (st != QII_OK) return st;
-    st = qii_quantize_nvfp4(W, dt, d_out, d_in, d_in, 0, QII_RTN, 0, 0, 0, nullptr, Wq, p + kSlot, kSlot, stream);
+    st = qii_quantize_nvfp4(W, dt, d_out, d_in, d_in, 0, mode, 0, 0, 0, nullptr, Wq, p + kSlot, kSlot, stream);
     if (st != QII_OK) return st;
     return qii_gemm_nvfp4(Xq, Wq, Y, y_dt, d_out, p + 2 * kSlot, ws_bytes - 2 * kSlot, stream);
+}
+
+qii_status qii_linear_fwd(const void *X, const void *W, qii_dtype dt, int64_t T, int64_t d_in,
+                          int64_t d_out, void *Y, qii_dtype y_dt, const qii_nvfp4 *Xq,
+                          const qii_nvfp4 *Wq, void *ws, size_t ws_bytes, void *stream)
+{
+    return qii_linear_fwd_mode(X, W, dt, T, d_in, d_out, QII_RTN, Y, y_dt, Xq, Wq, ws, ws_bytes, stream);
 }
 
 qii_status qii_linear_bwd(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq, const qii_nvfp4 *Wq,

@@ -13,6 +13,7 @@
 //   Philox4x32 call feed the four scale roundings of a lane.
 #include "qii_device.h"
 #include "qii_internal.h"
+#include "quantize_core.h"
 
 namespace qii {
 namespace {
@@ -234,14 +235,6 @@ __global__ __launch_bounds__(256) void rht_kernel(Loader load, int64_t R, int64_
     if (amax_bits) block_max_to_global(m, amax_bits);
 }
 
-// s and cap of the three schemes (Table 1 RTN; Sec. 3.1 Q_SR; Sec. 3.3 Q_RTN(x, s))
-__device__ __forceinline__ void mode_constants(int mode, float &s, float &cap)
-{
-    if (mode == QII_RTN) { s = 6.0f; cap = 448.0f; }
-    else if (mode == QII_SR) { s = (float)(96.0 / 17.0); cap = 448.0f; }
-    else { s = (float)(96.0 / 17.0 / 0.93); cap = 256.0f; }
-}
-
 template <class Loader, int kMode, bool kRht>
 __global__ __launch_bounds__(256) void quantize_kernel(Loader load, int64_t R, int64_t C,
                                                        uint64_t seed_rht, uint64_t seed_sr,
@@ -250,14 +243,8 @@ __global__ __launch_bounds__(256) void quantize_kernel(Loader load, int64_t R, i
 {
     const int64_t G = C / 16;
     const Lane L = lane_geometry(R, G);
-    const float amax = *amax_ptr;
-    float s, cap;
-    mode_constants(kMode, s, cap);
-    const bool zero_tensor = !(amax > 0.0f);
-    // x^FP32 = max|x| / (s * cap)
-    const float x32 = zero_tensor ? 1.0f : amax / (s * cap);
-    if (blockIdx.x == 0 && threadIdx.x == 0) *tensor_scale = x32;
-    const float x32s = x32 * s;
+    const TensorConsts tc = tensor_consts(kMode, *amax_ptr);
+    if (blockIdx.x == 0 && threadIdx.x == 0) *tensor_scale = tc.x32;
     const uint32_t sign16 = kRht ? lane_sign16(seed_rht, L.blk) : 0u;
     uint32_t draw[4] = {0, 0, 0, 0};
     if (kMode == QII_MS_EDEN) {
@@ -269,58 +256,16 @@ __global__ __launch_bounds__(256) void quantize_kernel(Loader load, int64_t R, i
         const int64_t row = L.quad * 4 + it;
         const bool ok = L.in_range && row < R;
         float v[16];
-        if (ok && !zero_tensor) load(row, L.g * 16, v);
+        if (ok && !tc.zero) load(row, L.g * 16, v);
         else {
 #pragma unroll
             for (int k = 0; k < 16; ++k) v[k] = 0.0f;
         }
         if (kRht) rht128(v, sign16, L.blk);
-        // x^FP8_g = RTN_FP8( max_g |x| / (x^FP32 * s) )
-        float gmax = 0.0f;
-#pragma unroll
-        for (int k = 0; k < 16; ++k) gmax = fmaxf(gmax, fabsf(v[k]));
-        uint32_t b = e4m3_rtn(gmax / x32s);
-        uint32_t packed[2] = {0u, 0u};
-        if (b != 0u) {
-            const float x8 = e4m3_decode(b);
-            const float inv = 1.0f / (x8 * x32);
-            float num = 0.0f, den = 0.0f;
-            uint32_t r16[16];
-            if (kMode == QII_SR) {
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const U4 w = philox_seeded(seed_sr, (uint32_t)(L.g * 2 + h), (uint32_t)row, 0, kStreamElem);
-                    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        r16[h * 8 + j] = (j & 1) ? (ww[j >> 1] >> 16) : (ww[j >> 1] & 0xFFFFu);
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                const float q = v[k] * inv;
-                const float a = fabsf(q);
-                uint32_t mcode;
-                if (kMode == QII_SR) {
-                    mcode = e2m1_sr_code(a, r16[k]);
-                } else {
-                    const float c = e2m1_round_mag(a);
-                    mcode = e2m1_mag_code(c);
-                    if (kMode == QII_MS_EDEN) {
-                        const float cs = u2f(f2u(c) | (f2u(q) & 0x80000000u));
-                        num = __builtin_fmaf(v[k], v[k], num);
-                        den = __builtin_fmaf(v[k], cs, den);
-                    }
-                }
-                const uint32_t code = mcode | ((f2u(q) >> 28) & 8u);
-                packed[k >> 3] |= code << (4 * (k & 7));
-            }
-            if (kMode == QII_MS_EDEN && den > 0.0f) {
-                // S_g * x^FP8_g = <x,x> / (<x, x^FP4> * x^FP32), rounded stochastically to E4M3
-                const float t = num / (den * x32);
-                b = e4m3_sr(t, it == 0 ? draw[0] : it == 1 ? draw[1] : it == 2 ? draw[2] : draw[3]);
-            }
-        }
+        // the per-group arithmetic of all schemes (an all-zero group gives scale byte 0, zero codes)
+        uint32_t packed[2];
+        const uint32_t b = quantize_group16<kMode>(v, tc, it == 0 ? draw[0] : it == 1 ? draw[1] : it == 2 ? draw[2] : draw[3],
+                                                   seed_sr, row, L.g, packed);
         if (ok) {
             *reinterpret_cast<uint2 *>(codes + (row * C + L.g * 16) / 2) = make_uint2(packed[0], packed[1]);
             scales[row * G + L.g] = (uint8_t)b;
@@ -413,6 +358,7 @@ hipError_t launch_quantize(const QuantizeArgs &a, hipStream_t s)
     hipLaunchKernelGGL((quantize_kernel<L, MODE, RHT>), grid, block, 0, s, load, a.R, a.C,        \
                        a.seed_rht, a.seed_sr, a.amax, a.codes, a.scales, a.tensor_scale)
         if (a.mode == QII_RTN) { if (a.rht) QII_LAUNCH(QII_RTN, true); else QII_LAUNCH(QII_RTN, false); }
+        else if (a.mode == QII_RTN_46) { if (a.rht) QII_LAUNCH(QII_RTN_46, true); else QII_LAUNCH(QII_RTN_46, false); }
         else if (a.mode == QII_SR) { if (a.rht) QII_LAUNCH(QII_SR, true); else QII_LAUNCH(QII_SR, false); }
         else { if (a.rht) QII_LAUNCH(QII_MS_EDEN, true); else QII_LAUNCH(QII_MS_EDEN, false); }
 #undef QII_LAUNCH

@@ -316,6 +316,7 @@ hipError_t launch_quantize_cols(const QuantizeArgs &q, hipStream_t s)
     do {                                                          \
         if (q.mode == QII_RTN) QII_COLS(SRC, QII_RTN, RHT);       \
         else if (q.mode == QII_SR) QII_COLS(SRC, QII_SR, RHT);    \
+        else if (q.mode == QII_RTN_46) QII_COLS(SRC, QII_RTN_46, RHT); \
         else QII_COLS(SRC, QII_MS_EDEN, RHT);                     \
     } while (0)
 #define QII_COLS_SRC(SRC)                                         \

@@ -19,6 +19,8 @@ struct TensorConsts {
     float x32;   // x^FP32 = amax / (s * cap)
     float d;     // x^FP32 * s, the divisor of the group-scale equation
     float rd;    // 1 / d, correctly rounded
+    float d4;    // x^FP32 * 4 and its reciprocal: the second candidate of the 4/6 choice
+    float rd4;
     bool zero;   // amax == 0: emit zeros
     bool fast;   // magnitudes far from the denormal range: the short division sequences
                  // below equal IEEE division bit for bit
@@ -28,6 +30,7 @@ __device__ __forceinline__ TensorConsts tensor_consts(int mode, float amax)
 {
     float s, cap;
     if (mode == QII_RTN) { s = 6.0f; cap = 448.0f; }
+    else if (mode == QII_RTN_46) { s = 6.0f; cap = 256.0f; }
     else if (mode == QII_SR) { s = (float)(96.0 / 17.0); cap = 448.0f; }
     else { s = (float)(96.0 / 17.0 / 0.93); cap = 256.0f; }
     TensorConsts tc;
@@ -35,6 +38,8 @@ __device__ __forceinline__ TensorConsts tensor_consts(int mode, float amax)
     tc.x32 = tc.zero ? 1.0f : amax / (s * cap);
     tc.d = tc.x32 * s;
     tc.rd = 1.0f / tc.d;
+    tc.d4 = tc.x32 * 4.0f;
+    tc.rd4 = 1.0f / tc.d4;
     tc.fast = amax > 0x1p-20f && amax < 0x1p20f;
     return tc;
 }
@@ -42,14 +47,19 @@ __device__ __forceinline__ TensorConsts tensor_consts(int mode, float amax)
 // a / d rounded to nearest: with rd = RN(1/d), two residual corrections of a * rd give the
 // correctly rounded quotient when nothing under- or overflows (the same refinement a
 // compiler-generated IEEE division ends with); otherwise fall back to the division.
+__device__ __forceinline__ float div_by_const(float a, float d, float rd, bool fast)
+{
+    if (!fast) return a / d;
+    const float q0 = a * rd;
+    const float e0 = __builtin_fmaf(-d, q0, a);
+    const float q1 = __builtin_fmaf(e0, rd, q0);
+    const float e1 = __builtin_fmaf(-d, q1, a);
+    return __builtin_fmaf(e1, rd, q1);
+}
+
 __device__ __forceinline__ float div_by_tensor_const(float a, const TensorConsts &tc)
 {
-    if (!tc.fast) return a / tc.d;
-    const float q0 = a * tc.rd;
-    const float e0 = __builtin_fmaf(-tc.d, q0, a);
-    const float q1 = __builtin_fmaf(e0, tc.rd, q0);
-    const float e1 = __builtin_fmaf(-tc.d, q1, a);
-    return __builtin_fmaf(e1, tc.rd, q1);
+    return div_by_const(a, tc.d, tc.rd, tc.fast);
 }
 
 // a / b rounded to nearest for operands far from the denormal and overflow ranges: the
@@ -84,6 +94,42 @@ __device__ __forceinline__ float group_absmax(const float y[16])
     return fmaxf(m0, m1);
 }
 
+// One candidate of the 4/6 choice (Sec. 4.1): round the group to nearest with the scale byte
+// RTN_FP8(r), r = group maximum / (x^FP32 * level).  Fills packed[2]; err = sum of
+// (x_i - c_i * (x^FP8 * x^FP32))^2, each difference one fused multiply-add, summed as a fused
+// multiply-add chain in index order.  A scale byte of 0 gives zero codes and err = <x, x>.
+__device__ __forceinline__ uint32_t rtn_candidate(const float y[16], float r, const TensorConsts &tc,
+                                                  uint32_t packed[2], float &err)
+{
+    const uint32_t b = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(fminf(r, 448.0f), 0.0f, 0, false) & 0xFFu;
+    // with b == 0 the arithmetic below runs on a stand-in scale and its results are dropped
+    const float p = b == 0u ? 1.0f : e4m3_decode(b) * tc.x32;
+    const float inv = div_ieee(1.0f, p, tc);
+    packed[0] = 0u;
+    packed[1] = 0u;
+#define QII_ENC(H, I)                                                                             \
+    packed[H] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed[H], y[8 * H + 2 * I] * inv,       \
+                                                         y[8 * H + 2 * I + 1] * inv, 1.0f, I)
+    QII_ENC(0, 0); QII_ENC(0, 1); QII_ENC(0, 2); QII_ENC(0, 3);
+    QII_ENC(1, 0); QII_ENC(1, 1); QII_ENC(1, 2); QII_ENC(1, 3);
+#undef QII_ENC
+    if (b == 0u) { packed[0] = 0u; packed[1] = 0u; }
+    float e = 0.0f;
+#define QII_ERR(H, I)                                                                             \
+    do {                                                                                          \
+        const float2_t c = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(packed[H], 1.0f, I);          \
+        const float d0 = __builtin_fmaf(-c[0], p, y[8 * H + 2 * I]);                              \
+        e = __builtin_fmaf(d0, d0, e);                                                            \
+        const float d1 = __builtin_fmaf(-c[1], p, y[8 * H + 2 * I + 1]);                          \
+        e = __builtin_fmaf(d1, d1, e);                                                            \
+    } while (0)
+    QII_ERR(0, 0); QII_ERR(0, 1); QII_ERR(0, 2); QII_ERR(0, 3);
+    QII_ERR(1, 0); QII_ERR(1, 1); QII_ERR(1, 2); QII_ERR(1, 3);
+#undef QII_ERR
+    err = e;
+    return b;
+}
+
 // Quantize one group.  y: rotated values; draw20: the 20 scale-rounding bits of this group
 // (MS-EDEN); (seed_sr, row, g): identify the element draws (SR).  Returns the scale byte and
 // fills packed[2] with the 16 codes (element 2j in the low nibble of byte j).
@@ -94,6 +140,18 @@ __device__ __forceinline__ uint32_t quantize_group16(const float y[16], const Te
 {
     packed[0] = 0u;
     packed[1] = 0u;
+    if (kMode == QII_RTN_46) {
+        // both candidates, then the one with the lower error; the mapping to 6 wins ties
+        const float gmax = group_absmax(y);
+        uint32_t p6[2], p4[2];
+        float e6, e4;
+        const uint32_t b6 = rtn_candidate(y, div_by_const(gmax, tc.d, tc.rd, tc.fast), tc, p6, e6);
+        const uint32_t b4 = rtn_candidate(y, div_by_const(gmax, tc.d4, tc.rd4, tc.fast), tc, p4, e4);
+        const bool use4 = e4 < e6;
+        packed[0] = use4 ? p4[0] : p6[0];
+        packed[1] = use4 ? p4[1] : p6[1];
+        return use4 ? b4 : b6;
+    }
     // x^FP8_g = RTN_FP8( max_g |x| / (x^FP32 * s) ), saturating at 448
     const float r = div_by_tensor_const(group_absmax(y), tc);
     uint32_t b = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(fminf(r, 448.0f), 0.0f, 0, false) & 0xFFu;

@@ -349,6 +349,7 @@ hipError_t launch_quantize_rows(const QuantizeArgs &q, hipStream_t s)
     do {                                                         \
         if (q.mode == QII_RTN) QII_ROWS(BF, QII_RTN, RHT);       \
         else if (q.mode == QII_SR) QII_ROWS(BF, QII_SR, RHT);    \
+        else if (q.mode == QII_RTN_46) QII_ROWS(BF, QII_RTN_46, RHT); \
         else QII_ROWS(BF, QII_MS_EDEN, RHT);                     \
     } while (0)
     if (bf) { if (q.rht) QII_ROWS_MODE(true, true); else QII_ROWS_MODE(true, false); }

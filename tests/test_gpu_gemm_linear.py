@@ -119,3 +119,22 @@ def test_linear_forward_and_backward(oracle):
         check(dX.cpu().numpy().astype(np.float64), ref, absum, False)
         ref, absum = oracle.gemm(ETq, XTq, with_abs=True)
         check(dW.cpu().numpy().astype(np.float64), ref, absum, False)
+
+
+def test_linear_forward_with_four_over_six(oracle):
+    """Forward pass of Sec. 5 with the 4/6 choice of Sec. 4.1 on X and W; other modes are refused."""
+    T, d_in, d_out = 384, 512, 256
+    Xb, Wb, _ = synth.linear_layer_bf16(T, d_in, d_out, seed=5)
+    X, W = to_dev(Xb), to_dev(Wb)
+    Xq, Wq = qii.NVFP4Tensor.empty(T, d_in), qii.NVFP4Tensor.empty(d_out, d_in)
+    Y = torch.empty((T, d_out), dtype=torch.float32, device="cuda")
+    w = ws(qii.qii_linear_fwd_workspace_bytes(T, d_in, d_out))
+    qii.qii_linear_fwd_mode(X, W, qii.RTN_46, Y, Xq, Wq, w)
+    oXq, oWq = oracle.linear_fwd(Xb, Wb, mode=oracle.RTN_46)
+    assert_nv_equal(Xq, oXq, "saved X (4/6)")
+    assert_nv_equal(Wq, oWq, "saved W (4/6)")
+    ref, absum = oracle.gemm(oXq, oWq, with_abs=True)
+    torch.cuda.synchronize()
+    check(Y.cpu().numpy().astype(np.float64), ref, absum, False)
+    with pytest.raises(qii.QiiError):
+        qii.qii_linear_fwd_mode(X, W, qii.MS_EDEN, Y, Xq, Wq, w)

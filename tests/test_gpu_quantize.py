@@ -11,7 +11,7 @@ from gpu_util import assert_nv_equal, nv_to_dev, to_dev, ws
 
 pytestmark = pytest.mark.gpu
 
-MODES = [qii.RTN, qii.SR, qii.MS_EDEN]
+MODES = [qii.RTN, qii.SR, qii.MS_EDEN, qii.RTN_46]
 
 
 def make(kind, shape, seed):
@@ -147,8 +147,9 @@ def test_degenerate_tensors(oracle):
         assert_nv_equal(out, oracle.quantize(z, mode, seed_rht=1, seed_sr=2), "zeros")
     x = np.full((4, 256), 1e-9, dtype=np.float32)
     x[0, 0] = 1e6
-    out = run_quantize(x, qii.RTN, False, 0, 0, 0)
-    assert_nv_equal(out, oracle.quantize(x, qii.RTN, rht_group=0), "underflowing groups")
+    for mode in (qii.RTN, qii.RTN_46):
+        out = run_quantize(x, mode, False, 0, 0, 0)
+        assert_nv_equal(out, oracle.quantize(x, mode, rht_group=0), f"underflowing groups, mode {mode}")
     # empty input: nothing is launched, nothing is written
     out = qii.NVFP4Tensor.empty(0, 128)
     qii.qii_quantize_nvfp4(torch.empty((0, 128), dtype=torch.bfloat16, device="cuda"), False,
