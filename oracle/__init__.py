@@ -20,7 +20,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "qii_oracle.c")
 _LIB = os.path.join(_HERE, "libqii_oracle.so")
 
-RTN, SR, MS_EDEN, RTN_46 = 0, 1, 2, 3
+RTN, SR, MS_EDEN, RTN_46, MS_EDEN_PH = 0, 1, 2, 3, 4
 F32, BF16 = 0, 1
 
 
@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         _lib.qo_e4m3_decode.restype = c.c_float
         _lib.qo_e4m3_rtn.argtypes = [c.c_float]
         _lib.qo_e4m3_rtn.restype = c.c_uint8
+        _lib.qo_e8m3_rtn.argtypes = [c.c_float]
+        _lib.qo_e8m3_rtn.restype = c.c_float
         _lib.qo_e4m3_sr.argtypes = [c.c_float, c.c_uint32]
         _lib.qo_e4m3_sr.restype = c.c_uint8
         _lib.qo_rht.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int64, c.c_int64, c.c_int,
@@ -171,6 +173,10 @@ def e4m3_decode(b: int) -> float:
 
 def e4m3_rtn(r: float) -> int:
     return int(lib().qo_e4m3_rtn(ctypes.c_float(r)))
+
+
+def e8m3_rtn(u: float) -> float:
+    return float(lib().qo_e8m3_rtn(ctypes.c_float(u)))
 
 
 def e4m3_sr(t: float, r20: int) -> int:

@@ -28,6 +28,13 @@
  *             backward pass (dequantize, transpose, re-quantize with MS-EDEN,
  *             MS-EDEN of E and E^T, two GEMMs; rotations cancel on the inner
  *             dimension).
+ *   Sec. 7    "Post Hoc Range Alignment": MS-EDEN without knowing the tensor
+ *             maximum in the heavy pass (mode MS_EDEN_PH): group scales are
+ *             rounded to E8M3 (three mantissa bits, binary32 exponent range)
+ *             instead of being aligned to the E4M3 range first, codes and EDEN
+ *             factors follow from those pseudo-scales, and a second pass over
+ *             the scales alone shifts them by the tensor scale and rounds them
+ *             stochastically to E4M3.
  *   App. A    one rotation per tensor, shared by all its 128-chunks.
  *
  * Every function is pinned by tests/test_oracle_*.py against format
@@ -42,6 +49,7 @@
 #define QO_SR 1
 #define QO_MS_EDEN 2
 #define QO_RTN_46 3
+#define QO_MS_EDEN_PH 4
 
 #define QO_F32 0
 #define QO_BF16 1
@@ -315,6 +323,7 @@ static void mode_constants(int mode, float s_override, float *s, float *cap)
 {
     if (mode == QO_RTN) { *s = 6.0f; *cap = 448.0f; }
     else if (mode == QO_RTN_46) { *s = 6.0f; *cap = 256.0f; }
+    else if (mode == QO_MS_EDEN_PH) { *s = (float)(96.0 / 17.0 / 0.93); *cap = 256.0f; }
     else if (mode == QO_SR) { *s = (float)(96.0 / 17.0); *cap = 448.0f; }
     else { *s = (float)(96.0 / 17.0 / 0.93); *cap = 256.0f; }
     if (s_override > 0.0f) *s = s_override;
@@ -349,6 +358,72 @@ static uint8_t rtn_candidate(const float *yg, float gmax, float x32, float level
     return b;
 }
 
+/* E8M3 (Sec. 7): a non-negative binary32 rounded to three mantissa bits,     */
+/* nearest even, exponent range unchanged ("extended-range" stand-in for E4M3).*/
+float qo_e8m3_rtn(float u)
+{
+    uint32_t b;
+    memcpy(&b, &u, 4);
+    b = (b + 0x7FFFFu + ((b >> 20) & 1u)) & 0xFFF00000u;
+    memcpy(&u, &b, 4);
+    return u;
+}
+
+/* MS-EDEN with post hoc range alignment (Sec. 7), in the paper's two passes. */
+/* Pass 1 needs no tensor maximum: pseudo-scale p_g = RTN_E8M3(max_g|x| / s),  */
+/* codes RTN_FP4(x_i / p_g), and the corrected pseudo-scale                   */
+/*   t_g = S_g * p_g = <x,x> / <x, x^FP4>   (p_g cancels; t_g = p_g if the     */
+/*   denominator is not positive), kept in binary32.                          */
+/* Pass 2 reads only t_g and the tensor maximum: x^FP32 = max|x| / (s * 256), */
+/* scale byte = SR_E4M3(t_g / x^FP32) with the same draw as Algorithm 1.      */
+static void quantize_rotated_posthoc(const float *y, int64_t R, int64_t C, float s, float cap,
+                                     float amax, uint64_t seed_sr, uint8_t *codes, uint8_t *scales,
+                                     float *tensor_scale)
+{
+    int64_t G = C / 16;
+    float *t = (float *)malloc(sizeof(float) * (size_t)(R * G > 0 ? R * G : 1));
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < R; ++r)
+        for (int64_t g = 0; g < G; ++g) {
+            const float *yg = y + r * C + g * 16;
+            uint8_t *cg = codes + (r * C + g * 16) / 2;
+            float gmax = 0.0f;
+            for (int k = 0; k < 16; ++k) {
+                float a = fabsf(yg[k]);
+                if (a > gmax) gmax = a;
+            }
+            const float p = qo_e8m3_rtn(gmax / s);
+            memset(cg, 0, 8);
+            if (!(p > 0.0f)) { /* all-zero group (or a maximum that rounds to nothing) */
+                t[r * G + g] = 0.0f;
+                continue;
+            }
+            const float inv = 1.0f / p;
+            float num = 0.0f, den = 0.0f;
+            for (int k = 0; k < 16; ++k) {
+                uint8_t code = qo_e2m1_rtn(yg[k] * inv);
+                if (k & 1) cg[k >> 1] |= (uint8_t)(code << 4);
+                else cg[k >> 1] = code;
+                num = fmaf(yg[k], yg[k], num);
+                den = fmaf(yg[k], qo_e2m1_decode(code), den);
+            }
+            t[r * G + g] = den > 0.0f ? num / den : p;
+        }
+    if (!(amax > 0.0f)) {
+        *tensor_scale = 1.0f;
+        memset(scales, 0, (size_t)(R * G));
+    } else {
+        const float x32 = amax / (s * cap);
+        *tensor_scale = x32;
+#pragma omp parallel for schedule(static)
+        for (int64_t r = 0; r < R; ++r)
+            for (int64_t g = 0; g < G; ++g) {
+                scales[r * G + g] = qo_e4m3_sr(t[r * G + g] / x32, qo_scale_draw(seed_sr, r, g));
+            }
+    }
+    free(t);
+}
+
 /* Quantize an already rotated R x C f32 matrix y, groups of 16 along rows. */
 static void quantize_rotated(const float *y, int64_t R, int64_t C, int mode, float s_override,
                              float amax, uint64_t seed_sr, uint8_t *codes, uint8_t *scales,
@@ -363,6 +438,10 @@ static void quantize_rotated(const float *y, int64_t R, int64_t C, int mode, flo
     }
     float s, cap;
     mode_constants(mode, s_override, &s, &cap);
+    if (mode == QO_MS_EDEN_PH) {
+        quantize_rotated_posthoc(y, R, C, s, cap, amax, seed_sr, codes, scales, tensor_scale);
+        return;
+    }
     /* x^FP32 = max|x| / (s * cap)                                          */
     const float x32 = amax / (s * cap);
     *tensor_scale = x32;
@@ -438,7 +517,7 @@ int qo_quantize(const void *x, int dtype, int64_t rows, int64_t cols, int64_t ld
                 const float *amax_in, float s_override, uint8_t *codes, uint8_t *scales,
                 float *tensor_scale)
 {
-    if (mode != QO_RTN && mode != QO_SR && mode != QO_MS_EDEN && mode != QO_RTN_46) return QO_BAD;
+    if (mode != QO_RTN && mode != QO_SR && mode != QO_MS_EDEN && mode != QO_RTN_46 && mode != QO_MS_EDEN_PH) return QO_BAD;
     int64_t R = transpose ? cols : rows, C = transpose ? rows : cols;
     float *y = (float *)malloc(sizeof(float) * (size_t)(R * C > 0 ? R * C : 1));
     if (!y) return QO_BAD;
