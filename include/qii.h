@@ -62,8 +62,16 @@ typedef enum {
  *               twice, with its maximum mapped to 6 and to 4, and the candidate with the
  *               smaller squared error is kept (ties: 6).  Scale cap 256, so that the 1.5
  *               times larger scale of a block mapped to 4 (at most 384) is an E4M3 value.
- *               Deterministic; biased, hence forward pass only. */
-typedef enum { QII_RTN = 0, QII_SR = 1, QII_MS_EDEN = 2, QII_RTN_46 = 3 } qii_mode;
+ *               Deterministic; biased, hence forward pass only.
+ *   QII_MS_EDEN_PH  MS-EDEN with the post hoc range alignment of Sec. 7: one heavy pass that
+ *               needs no tensor maximum (group scales rounded to E8M3 = three mantissa bits at
+ *               binary32 range, FP4 codes and EDEN factors w.r.t. those pseudo-scales, the
+ *               rotated maximum reduced on the way) and one pass over the scales alone
+ *               (divide by the tensor scale, stochastic rounding to E4M3 with the draws of
+ *               QII_MS_EDEN).  Equal to QII_MS_EDEN bit for bit when the tensor scale is a
+ *               power of two, otherwise a different but equally unbiased estimate.  Needs
+ *               qii_quantize_posthoc_workspace_bytes of workspace. */
+typedef enum { QII_RTN = 0, QII_SR = 1, QII_MS_EDEN = 2, QII_RTN_46 = 3, QII_MS_EDEN_PH = 4 } qii_mode;
 
 typedef enum { QII_F32 = 0, QII_BF16 = 1 } qii_dtype;
 
@@ -164,11 +172,22 @@ qii_status qii_linear_bwd(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq_save
                           const qii_nvfp4 *Wq_saved, uint64_t seed, void *dX, void *dW,
                           qii_dtype g_dt, void *ws, size_t ws_bytes, void *stream);
 
+/* The same backward pass with the scheme of its four quantizers chosen by the caller:
+ * QII_MS_EDEN (as qii_linear_bwd: an abs-max pass and a quantize pass per tensor) or
+ * QII_MS_EDEN_PH (Sec. 7: one heavy pass and a scales-only pass per tensor).  Workspace:
+ * qii_linear_bwd_mode_workspace_bytes.  Other modes are rejected.                       */
+qii_status qii_linear_bwd_mode(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq_saved,
+                               const qii_nvfp4 *Wq_saved, uint64_t seed, qii_mode mode, void *dX,
+                               void *dW, qii_dtype g_dt, void *ws, size_t ws_bytes, void *stream);
+
 /* Workspace sizes in bytes (host computations, no device work).                       */
 size_t qii_quantize_workspace_bytes(void);
+/* for mode QII_MS_EDEN_PH; rows x cols is the shape of the quantized output            */
+size_t qii_quantize_posthoc_workspace_bytes(int64_t rows, int64_t cols);
 size_t qii_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 size_t qii_linear_fwd_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out);
 size_t qii_linear_bwd_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out);
+size_t qii_linear_bwd_mode_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out, qii_mode mode);
 
 /* Host helpers.                                                                        */
 uint64_t qii_derive_seed(uint64_t seed, uint32_t i); /* backward sub-seed i (0..5)      */

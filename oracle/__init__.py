@@ -289,13 +289,14 @@ def linear_fwd(X: np.ndarray, W: np.ndarray, mode: int = RTN):
     return Xq, Wq
 
 
-def linear_bwd_operands(E: np.ndarray, Xq: NVFP4, Wq: NVFP4, seed: int):
-    """Sec. 5, backward pass: the four MS-EDEN operands.
+def linear_bwd_operands(E: np.ndarray, Xq: NVFP4, Wq: NVFP4, seed: int, mode: int = MS_EDEN):
+    """Sec. 5, backward pass: the four MS-EDEN operands (mode MS_EDEN, or MS_EDEN_PH for the
+    post hoc range alignment of Sec. 7).
     dX = gemm(Eq, WTq)  (inner dimension d_out, both rotated with sub-seed 0);
     dW = gemm(ETq, XTq) (inner dimension T,     both rotated with sub-seed 1)."""
     s = [derive_seed(seed, i) for i in range(6)]
-    Eq = quantize(E, MS_EDEN, seed_rht=s[SEED_RHT_DGRAD], seed_sr=s[SEED_SR_E])
-    WTq = requantize(Wq, MS_EDEN, transpose=True, seed_rht=s[SEED_RHT_DGRAD], seed_sr=s[SEED_SR_WT])
-    ETq = quantize(E, MS_EDEN, transpose=True, seed_rht=s[SEED_RHT_WGRAD], seed_sr=s[SEED_SR_ET])
-    XTq = requantize(Xq, MS_EDEN, transpose=True, seed_rht=s[SEED_RHT_WGRAD], seed_sr=s[SEED_SR_XT])
+    Eq = quantize(E, mode, seed_rht=s[SEED_RHT_DGRAD], seed_sr=s[SEED_SR_E])
+    WTq = requantize(Wq, mode, transpose=True, seed_rht=s[SEED_RHT_DGRAD], seed_sr=s[SEED_SR_WT])
+    ETq = quantize(E, mode, transpose=True, seed_rht=s[SEED_RHT_WGRAD], seed_sr=s[SEED_SR_ET])
+    XTq = requantize(Xq, mode, transpose=True, seed_rht=s[SEED_RHT_WGRAD], seed_sr=s[SEED_SR_XT])
     return Eq, WTq, ETq, XTq

@@ -16,13 +16,13 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libqii.so")
 
-RTN, SR, MS_EDEN, RTN_46 = 0, 1, 2, 3
+RTN, SR, MS_EDEN, RTN_46, MS_EDEN_PH = 0, 1, 2, 3, 4
 F32, BF16 = 0, 1
 
 EXPORTS = [
     "qii_rht", "qii_absmax", "qii_quantize_nvfp4", "qii_requantize_nvfp4", "qii_dequantize_nvfp4",
-    "qii_gemm_nvfp4", "qii_linear_fwd", "qii_linear_fwd_mode", "qii_linear_bwd",
-    "qii_quantize_workspace_bytes",
+    "qii_gemm_nvfp4", "qii_linear_fwd", "qii_linear_fwd_mode", "qii_linear_bwd", "qii_linear_bwd_mode",
+    "qii_quantize_workspace_bytes", "qii_quantize_posthoc_workspace_bytes", "qii_linear_bwd_mode_workspace_bytes",
     "qii_gemm_workspace_bytes", "qii_linear_fwd_workspace_bytes", "qii_linear_bwd_workspace_bytes",
     "qii_derive_seed", "qii_status_string", "qii_last_error", "qii_version",
 ]
@@ -60,6 +60,12 @@ def lib() -> ctypes.CDLL:
         L.qii_linear_fwd.argtypes = [vp, vp, c.c_int, i64, i64, i64, vp, c.c_int, nv, nv, vp, sz, vp]
         L.qii_linear_fwd_mode.argtypes = [vp, vp, c.c_int, i64, i64, i64, c.c_int, vp, c.c_int, nv, nv, vp, sz, vp]
         L.qii_linear_bwd.argtypes = [vp, c.c_int, nv, nv, u64, vp, vp, c.c_int, vp, sz, vp]
+        L.qii_linear_bwd_mode.argtypes = [vp, c.c_int, nv, nv, u64, c.c_int, vp, vp, c.c_int, vp, sz, vp]
+        L.qii_linear_bwd_mode.restype = c.c_int
+        L.qii_quantize_posthoc_workspace_bytes.argtypes = [i64, i64]
+        L.qii_quantize_posthoc_workspace_bytes.restype = sz
+        L.qii_linear_bwd_mode_workspace_bytes.argtypes = [i64, i64, i64, c.c_int]
+        L.qii_linear_bwd_mode_workspace_bytes.restype = sz
         for name in ("qii_rht", "qii_absmax", "qii_quantize_nvfp4", "qii_requantize_nvfp4",
                      "qii_dequantize_nvfp4", "qii_gemm_nvfp4", "qii_linear_fwd", "qii_linear_fwd_mode",
                      "qii_linear_bwd"):
@@ -140,6 +146,14 @@ def qii_linear_fwd_workspace_bytes(T: int, d_in: int, d_out: int) -> int:
     return int(lib().qii_linear_fwd_workspace_bytes(T, d_in, d_out))
 
 
+def qii_quantize_posthoc_workspace_bytes(rows: int, cols: int) -> int:
+    return int(lib().qii_quantize_posthoc_workspace_bytes(rows, cols))
+
+
+def qii_linear_bwd_mode_workspace_bytes(T: int, d_in: int, d_out: int, mode: int) -> int:
+    return int(lib().qii_linear_bwd_mode_workspace_bytes(T, d_in, d_out, mode))
+
+
 def qii_linear_bwd_workspace_bytes(T: int, d_in: int, d_out: int) -> int:
     return int(lib().qii_linear_bwd_workspace_bytes(T, d_in, d_out))
 
@@ -217,3 +231,11 @@ def qii_linear_bwd(dY: torch.Tensor, Xq: NVFP4Tensor, Wq: NVFP4Tensor, seed: int
     _check(lib().qii_linear_bwd(dY.data_ptr(), _dt(dY), ctypes.byref(sx), ctypes.byref(sw), seed,
                                 dX.data_ptr(), dW.data_ptr(), _dt(dX), ws.data_ptr(),
                                 ws.numel() * ws.element_size(), _stream()))
+
+
+def qii_linear_bwd_mode(dY: torch.Tensor, Xq: NVFP4Tensor, Wq: NVFP4Tensor, seed: int, mode: int,
+                        dX: torch.Tensor, dW: torch.Tensor, ws: torch.Tensor):
+    sx, sw = Xq.c_struct(), Wq.c_struct()
+    _check(lib().qii_linear_bwd_mode(dY.data_ptr(), _dt(dY), ctypes.byref(sx), ctypes.byref(sw), seed, mode,
+                                     dX.data_ptr(), dW.data_ptr(), _dt(dX), ws.data_ptr(),
+                                     ws.numel() * ws.element_size(), _stream()))

@@ -94,15 +94,35 @@ qii_status nvfp4_source(const qii_nvfp4 *in, int transpose, int rht_group, qii::
 // measure (if needed) and quantize one logical R x C source
 qii_status quantize_source(const qii::Source &src, int64_t R, int64_t C, qii_mode mode, int rht_group,
                            uint64_t seed_rht, uint64_t seed_sr, const float *amax_in,
-                           const qii_nvfp4 *out, float *amax_slot, hipStream_t s)
+                           const qii_nvfp4 *out, float *amax_slot, float *tbuf, hipStream_t s)
 {
-    if (mode != QII_RTN && mode != QII_SR && mode != QII_MS_EDEN && mode != QII_RTN_46) return fail(QII_INVALID_ARG, "bad mode %d", (int)mode);
+    if (mode != QII_RTN && mode != QII_SR && mode != QII_MS_EDEN && mode != QII_RTN_46 && mode != QII_MS_EDEN_PH)
+        return fail(QII_INVALID_ARG, "bad mode %d", (int)mode);
     qii_status st = check_nvfp4(out, "out");
     if (st != QII_OK) return st;
     if (out->rows != R || out->cols != C)
         return fail(QII_BAD_SHAPE, "out is %lld x %lld, expected %lld x %lld", (long long)out->rows,
                     (long long)out->cols, (long long)R, (long long)C);
     if (R * C == 0) return QII_OK;
+    if (mode == QII_MS_EDEN_PH) {
+        // Sec. 7: heavy pass (codes, corrected pseudo-scales, running maximum), then scales only
+        if (!tbuf) return fail(QII_WORKSPACE_TOO_SMALL, "the post hoc scheme needs qii_quantize_posthoc_workspace_bytes of workspace");
+        if (!amax_in) {
+            hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(amax_slot), 0u, s);
+            if (e != hipSuccess) return hip_fail(e, "fill");
+        }
+        qii::QuantizeArgs a;
+        a.src = src; a.R = R; a.C = C; a.mode = (int)mode; a.rht = rht_group == 128;
+        a.seed_rht = seed_rht; a.seed_sr = seed_sr; a.amax = nullptr;
+        a.codes = out->codes; a.scales = out->scales; a.tensor_scale = out->tensor_scale;
+        a.tbuf = tbuf; a.amax_accum = amax_in ? nullptr : reinterpret_cast<uint32_t *>(amax_slot);
+        hipError_t e = qii::launch_quantize(a, s);
+        if (e != hipSuccess) return hip_fail(e, "quantize (heavy pass)");
+        e = qii::launch_posthoc_scales(tbuf, amax_in ? amax_in : amax_slot, R, C, seed_sr, out->scales,
+                                       out->tensor_scale, s);
+        if (e != hipSuccess) return hip_fail(e, "quantize (scales pass)");
+        return QII_OK;
+    }
     const float *amax = amax_in;
     if (!amax) {
         if (!amax_slot) return fail(QII_WORKSPACE_TOO_SMALL, "workspace needed to measure the abs-max");
@@ -116,9 +136,43 @@ qii_status quantize_source(const qii::Source &src, int64_t R, int64_t C, qii_mod
     a.src = src; a.R = R; a.C = C; a.mode = (int)mode; a.rht = rht_group == 128;
     a.seed_rht = seed_rht; a.seed_sr = seed_sr; a.amax = amax;
     a.codes = out->codes; a.scales = out->scales; a.tensor_scale = out->tensor_scale;
+    a.tbuf = nullptr; a.amax_accum = nullptr;
     hipError_t e = qii::launch_quantize(a, s);
     if (e != hipSuccess) return hip_fail(e, "quantize");
     return QII_OK;
+}
+
+// workspace of one quantizer call: [abs-max slot][post hoc scheme only: one f32 per group]
+qii_status carve_quantize_ws(qii_mode mode, const float *amax_in, int64_t R, int64_t C, void *ws,
+                             size_t ws_bytes, float **slot, float **tbuf)
+{
+    *slot = nullptr;
+    *tbuf = nullptr;
+    if (mode == QII_MS_EDEN_PH) {
+        const size_t need = kSlot + align_up((size_t)(R * (C / 16)) * 4);
+        if (!ws || ws_bytes < need || !aligned(ws, kSlot))
+            return fail(QII_WORKSPACE_TOO_SMALL, "the post hoc scheme needs %zu bytes of 256-byte aligned workspace", need);
+        *slot = reinterpret_cast<float *>(ws);
+        *tbuf = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + kSlot);
+        return QII_OK;
+    }
+    if (!amax_in) {
+        if (!ws || ws_bytes < kSlot || !aligned(ws, 4))
+            return fail(QII_WORKSPACE_TOO_SMALL, "need %zu bytes of workspace without amax_in", kSlot);
+        *slot = reinterpret_cast<float *>(ws);
+    }
+    return QII_OK;
+}
+
+// quantizer workspace of a backward pass: the abs-max slot plus, for the post hoc scheme, one f32
+// per group of the largest of its four tensors (T x d_out and d_in x max(d_out, T))
+size_t posthoc_region_bytes(int64_t T, int64_t d_in, int64_t d_out, qii_mode mode)
+{
+    if (mode != QII_MS_EDEN_PH) return kSlot;
+    int64_t groups = T * d_out / 16;
+    if (d_in * d_out / 16 > groups) groups = d_in * d_out / 16;
+    if (d_in * T / 16 > groups) groups = d_in * T / 16;
+    return kSlot + align_up((size_t)groups * 4);
 }
 
 size_t nvfp4_bytes(int64_t rows, int64_t cols)
@@ -165,6 +219,11 @@ uint64_t qii_derive_seed(uint64_t seed, uint32_t i)
 
 size_t qii_quantize_workspace_bytes(void) { return kSlot; }
 
+size_t qii_quantize_posthoc_workspace_bytes(int64_t rows, int64_t cols)
+{
+    return kSlot + align_up((size_t)(rows * (cols / 16)) * 4);
+}
+
 size_t qii_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) { return align_up(qii::gemm_workspace_bytes(M, N, K)); }
 
 size_t qii_linear_fwd_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out)
@@ -172,11 +231,16 @@ size_t qii_linear_fwd_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out)
     return 2 * kSlot + qii_gemm_workspace_bytes(T, d_out, d_in);
 }
 
-size_t qii_linear_bwd_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out)
+size_t qii_linear_bwd_mode_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out, qii_mode mode)
 {
     const size_t g1 = qii_gemm_workspace_bytes(T, d_in, d_out), g2 = qii_gemm_workspace_bytes(d_out, d_in, T);
-    return 4 * kSlot + nvfp4_bytes(T, d_out) + nvfp4_bytes(d_in, d_out) + nvfp4_bytes(d_out, T) +
-           nvfp4_bytes(d_in, T) + (g1 > g2 ? g1 : g2);
+    return posthoc_region_bytes(T, d_in, d_out, mode) + nvfp4_bytes(T, d_out) + nvfp4_bytes(d_in, d_out) +
+           nvfp4_bytes(d_out, T) + nvfp4_bytes(d_in, T) + (g1 > g2 ? g1 : g2);
+}
+
+size_t qii_linear_bwd_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out)
+{
+    return qii_linear_bwd_mode_workspace_bytes(T, d_in, d_out, QII_MS_EDEN);
 }
 
 qii_status qii_rht(const void *x, qii_dtype dt, int64_t rows, int64_t cols, int64_t ld,
@@ -223,13 +287,10 @@ qii_status qii_quantize_nvfp4(const void *x, qii_dtype dt, int64_t rows, int64_t
     int64_t R, C;
     qii_status st = dense_source(x, dt, rows, cols, ld, transpose, rht_group, &src, &R, &C);
     if (st != QII_OK) return st;
-    float *slot = nullptr;
-    if (!amax_in) {
-        if (!ws || ws_bytes < kSlot || !aligned(ws, 4))
-            return fail(QII_WORKSPACE_TOO_SMALL, "need %zu bytes of workspace without amax_in", kSlot);
-        slot = reinterpret_cast<float *>(ws);
-    }
-    return quantize_source(src, R, C, mode, rht_group, seed_rht, seed_sr, amax_in, out, slot,
+    float *slot, *tbuf;
+    st = carve_quantize_ws(mode, amax_in, R, C, ws, ws_bytes, &slot, &tbuf);
+    if (st != QII_OK) return st;
+    return quantize_source(src, R, C, mode, rht_group, seed_rht, seed_sr, amax_in, out, slot, tbuf,
                            (hipStream_t)stream);
 }
 
@@ -241,13 +302,10 @@ qii_status qii_requantize_nvfp4(const qii_nvfp4 *in, int transpose, qii_mode mod
     int64_t R, C;
     qii_status st = nvfp4_source(in, transpose, rht_group, &src, &R, &C);
     if (st != QII_OK) return st;
-    float *slot = nullptr;
-    if (!amax_in) {
-        if (!ws || ws_bytes < kSlot || !aligned(ws, 4))
-            return fail(QII_WORKSPACE_TOO_SMALL, "need %zu bytes of workspace without amax_in", kSlot);
-        slot = reinterpret_cast<float *>(ws);
-    }
-    return quantize_source(src, R, C, mode, rht_group, seed_rht, seed_sr, amax_in, out, slot,
+    float *slot, *tbuf;
+    st = carve_quantize_ws(mode, amax_in, R, C, ws, ws_bytes, &slot, &tbuf);
+    if (st != QII_OK) return st;
+    return quantize_source(src, R, C, mode, rht_group, seed_rht, seed_sr, amax_in, out, slot, tbuf,
                            (hipStream_t)stream);
 }
 
@@ -307,10 +365,12 @@ qii_status qii_linear_fwd(const void *X, const void *W, qii_dtype dt, int64_t T,
     return qii_linear_fwd_mode(X, W, dt, T, d_in, d_out, QII_RTN, Y, y_dt, Xq, Wq, ws, ws_bytes, stream);
 }
 
-qii_status qii_linear_bwd(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq, const qii_nvfp4 *Wq,
-                          uint64_t seed, void *dX, void *dW, qii_dtype g_dt, void *ws,
-                          size_t ws_bytes, void *stream)
+qii_status qii_linear_bwd_mode(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq, const qii_nvfp4 *Wq,
+                               uint64_t seed, qii_mode mode, void *dX, void *dW, qii_dtype g_dt, void *ws,
+                               size_t ws_bytes, void *stream)
 {
+    if (mode != QII_MS_EDEN && mode != QII_MS_EDEN_PH)
+        return fail(QII_INVALID_ARG, "the backward pass takes QII_MS_EDEN or QII_MS_EDEN_PH, not mode %d", (int)mode);
     qii_status st = check_nvfp4(Xq, "Xq_saved");
     if (st != QII_OK) return st;
     st = check_nvfp4(Wq, "Wq_saved");
@@ -318,12 +378,15 @@ qii_status qii_linear_bwd(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq, con
     const int64_t T = Xq->rows, d_in = Xq->cols, d_out = Wq->rows;
     if (Wq->cols != d_in) return fail(QII_BAD_SHAPE, "Xq is %lld x %lld but Wq is %lld x %lld", (long long)T, (long long)d_in, (long long)d_out, (long long)Wq->cols);
     if (T % 128 != 0 || d_out % 128 != 0) return fail(QII_BAD_SHAPE, "T and d_out must be multiples of 128");
-    const size_t need = qii_linear_bwd_workspace_bytes(T, d_in, d_out);
+    const size_t need = qii_linear_bwd_mode_workspace_bytes(T, d_in, d_out, mode);
     if (!ws || ws_bytes < need || !aligned(ws, kSlot))
         return fail(QII_WORKSPACE_TOO_SMALL, "linear_bwd needs %zu bytes of 256-byte aligned workspace", need);
     uint8_t *p = reinterpret_cast<uint8_t *>(ws);
-    float *slots = reinterpret_cast<float *>(p);
-    p += 4 * kSlot;
+    // one quantizer workspace, used by the four quantizers one after the other on the stream:
+    // the abs-max slot and, for the post hoc scheme, the per-group f32 buffer of the largest tensor
+    uint8_t *qws = p;
+    const size_t qws_bytes = posthoc_region_bytes(T, d_in, d_out, mode);
+    p += qws_bytes;
     qii_nvfp4 Eq = carve_nvfp4(p, T, d_out);
     qii_nvfp4 WTq = carve_nvfp4(p, d_in, d_out);
     qii_nvfp4 ETq = carve_nvfp4(p, d_out, T);
@@ -332,20 +395,26 @@ qii_status qii_linear_bwd(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq, con
     const size_t gws_bytes = reinterpret_cast<uint8_t *>(ws) + ws_bytes - p;
     uint64_t sd[6];
     for (uint32_t i = 0; i < 6; ++i) sd[i] = qii_derive_seed(seed, i);
-    const size_t slot_floats = kSlot / sizeof(float);
     // dX = Q(E) Q(W^T)^T : rotation sd[0] on the inner dimension d_out
-    st = qii_quantize_nvfp4(dY, dt, T, d_out, d_out, 0, QII_MS_EDEN, 128, sd[0], sd[2], nullptr, &Eq, slots, kSlot, stream);
+    st = qii_quantize_nvfp4(dY, dt, T, d_out, d_out, 0, mode, 128, sd[0], sd[2], nullptr, &Eq, qws, qws_bytes, stream);
     if (st != QII_OK) return st;
-    st = qii_requantize_nvfp4(Wq, 1, QII_MS_EDEN, 128, sd[0], sd[3], nullptr, &WTq, slots + slot_floats, kSlot, stream);
+    st = qii_requantize_nvfp4(Wq, 1, mode, 128, sd[0], sd[3], nullptr, &WTq, qws, qws_bytes, stream);
     if (st != QII_OK) return st;
     st = qii_gemm_nvfp4(&Eq, &WTq, dX, g_dt, d_in, gws, gws_bytes, stream);
     if (st != QII_OK) return st;
     // dW = Q(E^T) Q(X^T)^T : rotation sd[1] on the inner dimension T
-    st = qii_quantize_nvfp4(dY, dt, T, d_out, d_out, 1, QII_MS_EDEN, 128, sd[1], sd[4], nullptr, &ETq, slots + 2 * slot_floats, kSlot, stream);
+    st = qii_quantize_nvfp4(dY, dt, T, d_out, d_out, 1, mode, 128, sd[1], sd[4], nullptr, &ETq, qws, qws_bytes, stream);
     if (st != QII_OK) return st;
-    st = qii_requantize_nvfp4(Xq, 1, QII_MS_EDEN, 128, sd[1], sd[5], nullptr, &XTq, slots + 3 * slot_floats, kSlot, stream);
+    st = qii_requantize_nvfp4(Xq, 1, mode, 128, sd[1], sd[5], nullptr, &XTq, qws, qws_bytes, stream);
     if (st != QII_OK) return st;
     return qii_gemm_nvfp4(&ETq, &XTq, dW, g_dt, d_in, gws, gws_bytes, stream);
+}
+
+qii_status qii_linear_bwd(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq, const qii_nvfp4 *Wq,
+                          uint64_t seed, void *dX, void *dW, qii_dtype g_dt, void *ws,
+                          size_t ws_bytes, void *stream)
+{
+    return qii_linear_bwd_mode(dY, dt, Xq, Wq, seed, QII_MS_EDEN, dX, dW, g_dt, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

@@ -239,12 +239,15 @@ template <class Loader, int kMode, bool kRht>
 __global__ __launch_bounds__(256) void quantize_kernel(Loader load, int64_t R, int64_t C,
                                                        uint64_t seed_rht, uint64_t seed_sr,
                                                        const float *amax_ptr, uint8_t *codes,
-                                                       uint8_t *scales, float *tensor_scale)
+                                                       uint8_t *scales, float *tensor_scale,
+                                                       float *tbuf, uint32_t *amax_accum)
 {
     const int64_t G = C / 16;
     const Lane L = lane_geometry(R, G);
-    const TensorConsts tc = tensor_consts(kMode, *amax_ptr);
-    if (blockIdx.x == 0 && threadIdx.x == 0) *tensor_scale = tc.x32;
+    // (the heavy pass of the post hoc scheme knows no tensor maximum: tc stays unused there)
+    const TensorConsts tc = kMode == QII_MS_EDEN_PH ? TensorConsts{} : tensor_consts(kMode, *amax_ptr);
+    if (kMode != QII_MS_EDEN_PH && blockIdx.x == 0 && threadIdx.x == 0) *tensor_scale = tc.x32;
+    float m = 0.0f;
     const uint32_t sign16 = kRht ? lane_sign16(seed_rht, L.blk) : 0u;
     uint32_t draw[4] = {0, 0, 0, 0};
     if (kMode == QII_MS_EDEN) {
@@ -264,11 +267,64 @@ __global__ __launch_bounds__(256) void quantize_kernel(Loader load, int64_t R, i
         if (kRht) rht128(v, sign16, L.blk);
         // the per-group arithmetic of all schemes (an all-zero group gives scale byte 0, zero codes)
         uint32_t packed[2];
+        if (kMode == QII_MS_EDEN_PH) {
+            float gmax;
+            const float t = posthoc_group16(v, packed, gmax);
+            if (ok) {
+                *reinterpret_cast<uint2 *>(codes + (row * C + L.g * 16) / 2) = make_uint2(packed[0], packed[1]);
+                tbuf[row * G + L.g] = t;
+                m = fmaxf(m, gmax);
+            }
+            continue;
+        }
         const uint32_t b = quantize_group16<kMode>(v, tc, it == 0 ? draw[0] : it == 1 ? draw[1] : it == 2 ? draw[2] : draw[3],
                                                    seed_sr, row, L.g, packed);
         if (ok) {
             *reinterpret_cast<uint2 *>(codes + (row * C + L.g * 16) / 2) = make_uint2(packed[0], packed[1]);
             scales[row * G + L.g] = (uint8_t)b;
+        }
+    }
+    if (kMode == QII_MS_EDEN_PH && amax_accum) wave_max_to_global(m, amax_accum);
+}
+
+// Second pass of the post hoc scheme (Sec. 7): scales only.  x^FP32 = max|x| / (s * 256); the
+// byte of group (row, g) is SR_E4M3(t / x^FP32) with the 20-bit draw of (seed, row, g), the one
+// Algorithm 1 uses.  One thread takes 4 rows x 4 groups: four Philox calls (a call serves the
+// four rows of one group) and, when whole, one 16-byte load and one 4-byte store per row.
+__global__ __launch_bounds__(256) void posthoc_scales_kernel(const float *__restrict__ tbuf,
+                                                             const float *__restrict__ amax_ptr,
+                                                             int64_t R, int64_t G, uint64_t seed_sr,
+                                                             uint8_t *__restrict__ scales,
+                                                             float *__restrict__ tensor_scale)
+{
+    const float amax = *amax_ptr;
+    const float s = (float)(96.0 / 17.0 / 0.93);
+    const float x32 = amax > 0.0f ? amax / (s * 256.0f) : 1.0f;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx == 0) *tensor_scale = x32;
+    const int64_t gq = (G + 3) / 4;
+    if (idx >= ((R + 3) / 4) * gq) return;
+    const int64_t quad = idx / gq, g0 = (idx % gq) * 4;
+    uint32_t draw[4][4];   // [group][row]
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const U4 w = philox_seeded(seed_sr, (uint32_t)(g0 + j), (uint32_t)quad, 0, kStreamScale);
+        draw[j][0] = w.x >> 12; draw[j][1] = w.y >> 12; draw[j][2] = w.z >> 12; draw[j][3] = w.w >> 12;
+    }
+    const bool whole = (G % 4 == 0);
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int64_t row = quad * 4 + it;
+        if (row >= R) break;
+        if (whole) {
+            const float4 t = *reinterpret_cast<const float4 *>(tbuf + row * G + g0);
+            const uint32_t b = e4m3_sr(t.x / x32, draw[0][it]) | (e4m3_sr(t.y / x32, draw[1][it]) << 8) |
+                               (e4m3_sr(t.z / x32, draw[2][it]) << 16) | (e4m3_sr(t.w / x32, draw[3][it]) << 24);
+            *reinterpret_cast<uint32_t *>(scales + row * G + g0) = b;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (g0 + j < G) scales[row * G + g0 + j] = (uint8_t)e4m3_sr(tbuf[row * G + g0 + j] / x32, draw[j][it]);
         }
     }
 }
@@ -356,14 +412,26 @@ hipError_t launch_quantize(const QuantizeArgs &a, hipStream_t s)
         using L = decltype(load);
 #define QII_LAUNCH(MODE, RHT)                                                                     \
     hipLaunchKernelGGL((quantize_kernel<L, MODE, RHT>), grid, block, 0, s, load, a.R, a.C,        \
-                       a.seed_rht, a.seed_sr, a.amax, a.codes, a.scales, a.tensor_scale)
+                       a.seed_rht, a.seed_sr, a.amax, a.codes, a.scales, a.tensor_scale, a.tbuf,  \
+                       a.amax_accum)
         if (a.mode == QII_RTN) { if (a.rht) QII_LAUNCH(QII_RTN, true); else QII_LAUNCH(QII_RTN, false); }
         else if (a.mode == QII_RTN_46) { if (a.rht) QII_LAUNCH(QII_RTN_46, true); else QII_LAUNCH(QII_RTN_46, false); }
+        else if (a.mode == QII_MS_EDEN_PH) { if (a.rht) QII_LAUNCH(QII_MS_EDEN_PH, true); else QII_LAUNCH(QII_MS_EDEN_PH, false); }
         else if (a.mode == QII_SR) { if (a.rht) QII_LAUNCH(QII_SR, true); else QII_LAUNCH(QII_SR, false); }
         else { if (a.rht) QII_LAUNCH(QII_MS_EDEN, true); else QII_LAUNCH(QII_MS_EDEN, false); }
 #undef QII_LAUNCH
         return hipGetLastError();
     });
+}
+
+hipError_t launch_posthoc_scales(const float *tbuf, const float *amax, int64_t R, int64_t C,
+                                 uint64_t seed_sr, uint8_t *scales, float *tensor_scale, hipStream_t s)
+{
+    const int64_t G = C / 16, threads = ((R + 3) / 4) * ((G + 3) / 4);
+    if (threads == 0) return hipSuccess;
+    hipLaunchKernelGGL(posthoc_scales_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, tbuf,
+                       amax, R, G, seed_sr, scales, tensor_scale);
+    return hipGetLastError();
 }
 
 hipError_t launch_dequantize(const uint8_t *codes, const uint8_t *scales, const float *ts,

@@ -40,7 +40,8 @@ struct ColsArgs {
     uint8_t *codes;
     uint8_t *scales;
     float *tensor_scale;
-    uint32_t *amax_out;
+    uint32_t *amax_out;  // abs-max kernel, and the heavy pass of the post hoc scheme (nullable there)
+    float *tbuf;         // post hoc scheme: corrected pseudo-scales [R][C/16]
 };
 
 // load this lane's 32 rows (rows 32q .. 32q+31 of the chunk) of columns j0 and j0+1 (j0 even),
@@ -185,8 +186,9 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(ColsArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;   // wave-uniform
     const int64_t j0 = (int64_t)blockIdx.y * 32 + 2 * (lane >> 2);
-    const TensorConsts tc = tensor_consts(kMode, *a.amax);
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *a.tensor_scale = tc.x32;
+    // (the heavy pass of the post hoc scheme knows no tensor maximum: tc stays unused there)
+    const TensorConsts tc = kMode == QII_MS_EDEN_PH ? TensorConsts{} : tensor_consts(kMode, *a.amax);
+    if (kMode != QII_MS_EDEN_PH && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *a.tensor_scale = tc.x32;
     if (chunk * 128 >= a.C) return;
     if (tc.zero) {  // uniform: an all-zero tensor is emitted as zero bytes
 #pragma unroll
@@ -204,6 +206,28 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(ColsArgs a)
     if (kRht) {
         fwht128_quad(v[0], q);
         fwht128_quad(v[1], q);
+    }
+    if (kMode == QII_MS_EDEN_PH) {
+        // heavy pass of the post hoc scheme: codes, corrected pseudo-scales, running maximum
+        float m = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            uint32_t codes[4];
+            float t[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                float gmax;
+                t[h] = posthoc_group16(v[e] + 16 * h, codes + 2 * h, gmax);
+                if (j0 + e < a.R) m = fmaxf(m, gmax);
+            }
+            if (j0 + e < a.R) {
+                *reinterpret_cast<uint4 *>(a.codes + (j0 + e) * (a.C / 2) + chunk * 64 + 16 * q) =
+                    make_uint4(codes[0], codes[1], codes[2], codes[3]);
+                *reinterpret_cast<float2 *>(a.tbuf + (j0 + e) * (a.C / 16) + chunk * 8 + 2 * q) = make_float2(t[0], t[1]);
+            }
+        }
+        if (a.amax_out) wave_max_to_global(m, a.amax_out);
+        return;
     }
     uint32_t draw[2][2] = {{0u, 0u}, {0u, 0u}};
     if (kMode == QII_MS_EDEN) octet_draws(draw, a.seed_sr, chunk, j0, q);
@@ -267,6 +291,7 @@ ColsArgs make_args(const Source &src, int64_t R, int64_t C, uint64_t seed_rht, u
     a.sign[0] = w.x; a.sign[1] = w.y; a.sign[2] = w.z; a.sign[3] = w.w;
     a.seed_sr = seed_sr;
     a.amax = nullptr; a.codes = nullptr; a.scales = nullptr; a.tensor_scale = nullptr; a.amax_out = nullptr;
+    a.tbuf = nullptr;
     return a;
 }
 
@@ -310,6 +335,7 @@ hipError_t launch_quantize_cols(const QuantizeArgs &q, hipStream_t s)
 {
     ColsArgs a = make_args(q.src, q.R, q.C, q.seed_rht, q.seed_sr);
     a.amax = q.amax; a.codes = q.codes; a.scales = q.scales; a.tensor_scale = q.tensor_scale;
+    a.tbuf = q.tbuf; a.amax_out = q.amax_accum;
     const dim3 grid = cols_grid(q.R, q.C), block(256);
 #define QII_COLS(SRC, MODE, RHT) hipLaunchKernelGGL((quantize_cols_kernel<SRC, MODE, RHT>), grid, block, 0, s, a)
 #define QII_COLS_MODE(SRC, RHT)                                   \
@@ -317,6 +343,7 @@ hipError_t launch_quantize_cols(const QuantizeArgs &q, hipStream_t s)
         if (q.mode == QII_RTN) QII_COLS(SRC, QII_RTN, RHT);       \
         else if (q.mode == QII_SR) QII_COLS(SRC, QII_SR, RHT);    \
         else if (q.mode == QII_RTN_46) QII_COLS(SRC, QII_RTN_46, RHT); \
+        else if (q.mode == QII_MS_EDEN_PH) QII_COLS(SRC, QII_MS_EDEN_PH, RHT); \
         else QII_COLS(SRC, QII_MS_EDEN, RHT);                     \
     } while (0)
 #define QII_COLS_SRC(SRC)                                         \

@@ -130,6 +130,58 @@ __device__ __forceinline__ uint32_t rtn_candidate(const float y[16], float r, co
     return b;
 }
 
+// Internal mode number of MS-EDEN with post hoc range alignment (QII_MS_EDEN_PH of the C ABI).
+// E8M3 (Sec. 7): a non-negative binary32 rounded to three mantissa bits, nearest even.
+__device__ __forceinline__ float e8m3_rtn(float u)
+{
+    const uint32_t b = f2u(u);
+    return u2f((b + 0x7FFFFu + ((b >> 20) & 1u)) & 0xFFF00000u);
+}
+
+// Heavy pass of the post hoc scheme (Sec. 7) for one group; needs no tensor maximum.
+// Pseudo-scale p = RTN_E8M3(gmax / s), codes RTN_FP4(y_i / p), returns the corrected
+// pseudo-scale t = <y,y> / <y, codes> (p cancels; t = p when the denominator is not positive,
+// 0 for an all-zero group).  The divisions are full IEEE divisions: without the tensor maximum
+// nothing is known about the range of the operands.
+__device__ __forceinline__ float posthoc_group16(const float y[16], uint32_t packed[2], float &gmax)
+{
+    packed[0] = 0u;
+    packed[1] = 0u;
+    gmax = group_absmax(y);
+    const float p = e8m3_rtn(gmax / (float)(96.0 / 17.0 / 0.93));
+    if (!(p > 0.0f)) return 0.0f;
+    const float inv = 1.0f / p;
+#define QII_ENC(H, I)                                                                             \
+    packed[H] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed[H], y[8 * H + 2 * I] * inv,       \
+                                                         y[8 * H + 2 * I + 1] * inv, 1.0f, I)
+    QII_ENC(0, 0); QII_ENC(0, 1); QII_ENC(0, 2); QII_ENC(0, 3);
+    QII_ENC(1, 0); QII_ENC(1, 1); QII_ENC(1, 2); QII_ENC(1, 3);
+#undef QII_ENC
+    float num = 0.0f, den = 0.0f;
+#define QII_DOT(H, I)                                                                             \
+    do {                                                                                          \
+        const float2_t c = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(packed[H], 1.0f, I);          \
+        const float y0 = y[8 * H + 2 * I], y1 = y[8 * H + 2 * I + 1];                             \
+        num = __builtin_fmaf(y0, y0, num);                                                        \
+        den = __builtin_fmaf(y0, c[0], den);                                                      \
+        num = __builtin_fmaf(y1, y1, num);                                                        \
+        den = __builtin_fmaf(y1, c[1], den);                                                      \
+    } while (0)
+    QII_DOT(0, 0); QII_DOT(0, 1); QII_DOT(0, 2); QII_DOT(0, 3);
+    QII_DOT(1, 0); QII_DOT(1, 1); QII_DOT(1, 2); QII_DOT(1, 3);
+#undef QII_DOT
+    return den > 0.0f ? num / den : p;
+}
+
+// a wave's maximum into the global running maximum (non-negative floats order like their bits)
+__device__ __forceinline__ void wave_max_to_global(float m, uint32_t *amax_bits)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    // the running maximum only grows, so a stale read can only cause a redundant atomic
+    if ((threadIdx.x & 63) == 0 && f2u(m) > __atomic_load_n(amax_bits, __ATOMIC_RELAXED)) atomicMax(amax_bits, f2u(m));
+}
+
 // Quantize one group.  y: rotated values; draw20: the 20 scale-rounding bits of this group
 // (MS-EDEN); (seed_sr, row, g): identify the element draws (SR).  Returns the scale byte and
 // fills packed[2] with the 16 codes (element 2j in the low nibble of byte j).

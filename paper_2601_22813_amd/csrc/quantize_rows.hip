@@ -33,7 +33,8 @@ struct RowsArgs {
     uint8_t *codes;
     uint8_t *scales;
     float *tensor_scale;
-    uint32_t *amax_out;  // abs-max kernel only
+    uint32_t *amax_out;  // abs-max kernel, and the heavy pass of the post hoc scheme (nullable there)
+    float *tbuf;         // post hoc scheme: corrected pseudo-scales [R][C/16]
 };
 
 struct LaneSetup {
@@ -193,7 +194,7 @@ __device__ __forceinline__ void make_masks(uint32_t sign16, uint32_t mask[kBf16 
 template <bool kBf16, int kMode, bool kRht, bool kPrefetch>
 __device__ __forceinline__ void quantize_quad(const RowsArgs &a, const LaneSetup &L, const TensorConsts &tc,
                                               const uint32_t *mask, Raw<kBf16> raw[4], int64_t quad,
-                                              int64_t qn, int64_t G, int64_t gc)
+                                              int64_t qn, int64_t G, int64_t gc, float &m)
 {
     uint32_t draw[4] = {0u, 0u, 0u, 0u};
     if (kMode == QII_MS_EDEN) {
@@ -211,6 +212,17 @@ __device__ __forceinline__ void quantize_quad(const RowsArgs &a, const LaneSetup
         }
         if (kRht) rht128_lane(v, L);
         uint32_t packed[2];
+        if (kMode == QII_MS_EDEN_PH) {
+            // heavy pass of the post hoc scheme: codes, corrected pseudo-scale, running maximum
+            float gmax;
+            const float t = posthoc_group16(v, packed, gmax);
+            if (L.col_ok && row < a.R) {
+                *reinterpret_cast<uint2 *>(a.codes + (row * a.C + L.g * 16) / 2) = make_uint2(packed[0], packed[1]);
+                a.tbuf[row * G + L.g] = t;
+                m = fmaxf(m, gmax);
+            }
+            continue;
+        }
         const uint32_t b = quantize_group16<kMode>(v, tc, draw[it], a.seed_sr, row, L.g, packed);
         if (L.col_ok && row < a.R)
             *reinterpret_cast<uint2 *>(a.codes + (row * a.C + L.g * 16) / 2) = make_uint2(packed[0], packed[1]);
@@ -229,8 +241,9 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowsArgs a)
 {
     const int64_t G = a.C / 16;
     const LaneSetup L = lane_setup(a, G);
-    const TensorConsts tc = tensor_consts(kMode, *a.amax);
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *a.tensor_scale = tc.x32;
+    // (the heavy pass of the post hoc scheme knows no tensor maximum: tc stays unused there)
+    const TensorConsts tc = kMode == QII_MS_EDEN_PH ? TensorConsts{} : tensor_consts(kMode, *a.amax);
+    if (kMode != QII_MS_EDEN_PH && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *a.tensor_scale = tc.x32;
     const int64_t quads = (a.R + 3) / 4;
     if (tc.zero) {  // uniform: an all-zero tensor is emitted as zero bytes
         for (int64_t quad = blockIdx.x; quad < quads; quad += gridDim.x)
@@ -249,9 +262,11 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowsArgs a)
     Raw<kBf16> raw[4];
     int64_t quad = blockIdx.x;             // the grid never has more blocks than quads
     load_quad<kBf16>(raw, a, quad, gc);
+    float m = 0.0f;
     for (; quad + gridDim.x < quads; quad += gridDim.x)
-        quantize_quad<kBf16, kMode, kRht, true>(a, L, tc, mask, raw, quad, quad + gridDim.x, G, gc);
-    quantize_quad<kBf16, kMode, kRht, false>(a, L, tc, mask, raw, quad, quad, G, gc);
+        quantize_quad<kBf16, kMode, kRht, true>(a, L, tc, mask, raw, quad, quad + gridDim.x, G, gc, m);
+    quantize_quad<kBf16, kMode, kRht, false>(a, L, tc, mask, raw, quad, quad, G, gc, m);
+    if (kMode == QII_MS_EDEN_PH && a.amax_out) wave_max_to_global(m, a.amax_out);
 }
 
 template <bool kBf16, bool kRht>
@@ -316,6 +331,7 @@ RowsArgs make_args(const Source &src, int64_t R, int64_t C, uint64_t seed_rht, u
     a.sign[0] = w.x; a.sign[1] = w.y; a.sign[2] = w.z; a.sign[3] = w.w;
     a.seed_sr = seed_sr;
     a.amax = nullptr; a.codes = nullptr; a.scales = nullptr; a.tensor_scale = nullptr; a.amax_out = nullptr;
+    a.tbuf = nullptr;
     return a;
 }
 
@@ -342,6 +358,7 @@ hipError_t launch_quantize_rows(const QuantizeArgs &q, hipStream_t s)
 {
     RowsArgs a = make_args(q.src, q.R, q.C, q.seed_rht, q.seed_sr);
     a.amax = q.amax; a.codes = q.codes; a.scales = q.scales; a.tensor_scale = q.tensor_scale;
+    a.tbuf = q.tbuf; a.amax_out = q.amax_accum;
     const dim3 grid = rows_grid(q.R, q.C), block(256);
     const bool bf = q.src.kind == kSrcBF16;
 #define QII_ROWS(BF, MODE, RHT) hipLaunchKernelGGL((quantize_rows_kernel<BF, MODE, RHT>), grid, block, 0, s, a)
@@ -350,6 +367,7 @@ hipError_t launch_quantize_rows(const QuantizeArgs &q, hipStream_t s)
         if (q.mode == QII_RTN) QII_ROWS(BF, QII_RTN, RHT);       \
         else if (q.mode == QII_SR) QII_ROWS(BF, QII_SR, RHT);    \
         else if (q.mode == QII_RTN_46) QII_ROWS(BF, QII_RTN_46, RHT); \
+        else if (q.mode == QII_MS_EDEN_PH) QII_ROWS(BF, QII_MS_EDEN_PH, RHT); \
         else QII_ROWS(BF, QII_MS_EDEN, RHT);                     \
     } while (0)
     if (bf) { if (q.rht) QII_ROWS_MODE(true, true); else QII_ROWS_MODE(true, false); }

@@ -121,6 +121,28 @@ def test_linear_forward_and_backward(oracle):
         check(dW.cpu().numpy().astype(np.float64), ref, absum, False)
 
 
+def test_linear_backward_with_post_hoc_range_alignment(oracle):
+    """Backward pass of Sec. 5 with the four quantizers in the two-kernel form of Sec. 7."""
+    T, d_in, d_out = 256, 384, 512
+    Xb, Wb, Eb = synth.linear_layer_bf16(T, d_in, d_out, seed=8)
+    E = to_dev(Eb)
+    oXq, oWq = oracle.linear_fwd(Xb, Wb)
+    Xq, Wq = nv_to_dev(oXq), nv_to_dev(oWq)
+    seed = 77
+    dX = torch.empty((T, d_in), dtype=torch.float32, device="cuda")
+    dW = torch.empty((d_out, d_in), dtype=torch.float32, device="cuda")
+    w = ws(qii.qii_linear_bwd_mode_workspace_bytes(T, d_in, d_out, qii.MS_EDEN_PH))
+    qii.qii_linear_bwd_mode(E, Xq, Wq, seed, qii.MS_EDEN_PH, dX, dW, w)
+    Eq, WTq, ETq, XTq = oracle.linear_bwd_operands(Eb, oXq, oWq, seed, mode=oracle.MS_EDEN_PH)
+    ref, absum = oracle.gemm(Eq, WTq, with_abs=True)
+    torch.cuda.synchronize()
+    check(dX.cpu().numpy().astype(np.float64), ref, absum, False)
+    ref, absum = oracle.gemm(ETq, XTq, with_abs=True)
+    check(dW.cpu().numpy().astype(np.float64), ref, absum, False)
+    with pytest.raises(qii.QiiError):
+        qii.qii_linear_bwd_mode(E, Xq, Wq, seed, qii.SR, dX, dW, w)
+
+
 def test_linear_forward_with_four_over_six(oracle):
     """Forward pass of Sec. 5 with the 4/6 choice of Sec. 4.1 on X and W; other modes are refused."""
     T, d_in, d_out = 384, 512, 256

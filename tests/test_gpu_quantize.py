@@ -11,7 +11,7 @@ from gpu_util import assert_nv_equal, nv_to_dev, to_dev, ws
 
 pytestmark = pytest.mark.gpu
 
-MODES = [qii.RTN, qii.SR, qii.MS_EDEN, qii.RTN_46]
+MODES = [qii.RTN, qii.SR, qii.MS_EDEN, qii.RTN_46, qii.MS_EDEN_PH]
 
 
 def make(kind, shape, seed):
@@ -36,8 +36,11 @@ def run_quantize(x_np, mode, transpose, rht_group, seed_rht, seed_sr, supply_ama
     if supply_amax:
         amax = torch.empty(1, dtype=torch.float32, device="cuda")
         qii.qii_absmax(x, transpose, rht_group, seed_rht, amax)
-    qii.qii_quantize_nvfp4(x, transpose, mode, rht_group, seed_rht, seed_sr, amax, out,
-                           None if supply_amax else ws(256))
+    if mode == qii.MS_EDEN_PH:   # the post hoc scheme always needs its per-group buffer
+        w = ws(qii.qii_quantize_posthoc_workspace_bytes(R, C))
+    else:
+        w = None if supply_amax else ws(256)
+    qii.qii_quantize_nvfp4(x, transpose, mode, rht_group, seed_rht, seed_sr, amax, out, w)
     return out
 
 
@@ -120,7 +123,8 @@ def test_requantize_and_dequantize_match_oracle(oracle):
         for mode in MODES:
             R, C = (384, 256) if transpose else (256, 384)
             out = qii.NVFP4Tensor.empty(R, C)
-            qii.qii_requantize_nvfp4(dev_saved, transpose, mode, 128, 51, 52, None, out, ws(256))
+            qii.qii_requantize_nvfp4(dev_saved, transpose, mode, 128, 51, 52, None, out,
+                                     ws(qii.qii_quantize_posthoc_workspace_bytes(R, C)))
             ref = oracle.requantize(saved, mode, transpose=transpose, seed_rht=51, seed_sr=52)
             assert_nv_equal(out, ref, f"requantize transpose {transpose} mode {mode}")
 
