@@ -284,7 +284,10 @@ __global__ __launch_bounds__(256) void quantize_kernel(Loader load, int64_t R, i
             scales[row * G + L.g] = (uint8_t)b;
         }
     }
-    if (kMode == QII_MS_EDEN_PH && amax_accum) wave_max_to_global(m, amax_accum);
+    if (kMode == QII_MS_EDEN_PH && amax_accum) {
+        m = wave_max(m);
+        if ((threadIdx.x & 63) == 0) max_to_global(m, amax_accum);
+    }
 }
 
 // Second pass of the post hoc scheme (Sec. 7): scales only.  x^FP32 = max|x| / (s * 256); the

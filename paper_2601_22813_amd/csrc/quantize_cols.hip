@@ -189,6 +189,45 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(ColsArgs a)
     // (the heavy pass of the post hoc scheme knows no tensor maximum: tc stays unused there)
     const TensorConsts tc = kMode == QII_MS_EDEN_PH ? TensorConsts{} : tensor_consts(kMode, *a.amax);
     if (kMode != QII_MS_EDEN_PH && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *a.tensor_scale = tc.x32;
+    if (kMode == QII_MS_EDEN_PH) {
+        // heavy pass of the post hoc scheme: codes, corrected pseudo-scales, and the block's
+        // maximum into the running maximum (a wave does one tile only, so the four waves of a
+        // block are combined first; waves beyond the last chunk take part with 0)
+        __shared__ float wave_m[4];
+        float m = 0.0f;
+        if (chunk * 128 < a.C) {
+            float v[2][32];
+            load_quarter_chunk<kSrc, kRht>(v, a, chunk, (uint32_t)(j0 < a.R ? j0 : a.R - 2), q);
+            if (kRht) {
+                fwht128_quad(v[0], q);
+                fwht128_quad(v[1], q);
+            }
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                uint32_t codes[4];
+                float t[2];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    float gmax;
+                    t[h] = posthoc_group16(v[e] + 16 * h, codes + 2 * h, gmax);
+                    if (j0 + e < a.R) m = fmaxf(m, gmax);
+                }
+                if (j0 + e < a.R) {
+                    *reinterpret_cast<uint4 *>(a.codes + (j0 + e) * (a.C / 2) + chunk * 64 + 16 * q) =
+                        make_uint4(codes[0], codes[1], codes[2], codes[3]);
+                    *reinterpret_cast<float2 *>(a.tbuf + (j0 + e) * (a.C / 16) + chunk * 8 + 2 * q) = make_float2(t[0], t[1]);
+                }
+            }
+        }
+        if (a.amax_out) {   // uniform
+            m = wave_max(m);
+            if (lane == 0) wave_m[wave] = m;
+            __syncthreads();
+            if (threadIdx.x == 0)
+                max_to_global(fmaxf(fmaxf(wave_m[0], wave_m[1]), fmaxf(wave_m[2], wave_m[3])), a.amax_out);
+        }
+        return;
+    }
     if (chunk * 128 >= a.C) return;
     if (tc.zero) {  // uniform: an all-zero tensor is emitted as zero bytes
 #pragma unroll
@@ -206,28 +245,6 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(ColsArgs a)
     if (kRht) {
         fwht128_quad(v[0], q);
         fwht128_quad(v[1], q);
-    }
-    if (kMode == QII_MS_EDEN_PH) {
-        // heavy pass of the post hoc scheme: codes, corrected pseudo-scales, running maximum
-        float m = 0.0f;
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            uint32_t codes[4];
-            float t[2];
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                float gmax;
-                t[h] = posthoc_group16(v[e] + 16 * h, codes + 2 * h, gmax);
-                if (j0 + e < a.R) m = fmaxf(m, gmax);
-            }
-            if (j0 + e < a.R) {
-                *reinterpret_cast<uint4 *>(a.codes + (j0 + e) * (a.C / 2) + chunk * 64 + 16 * q) =
-                    make_uint4(codes[0], codes[1], codes[2], codes[3]);
-                *reinterpret_cast<float2 *>(a.tbuf + (j0 + e) * (a.C / 16) + chunk * 8 + 2 * q) = make_float2(t[0], t[1]);
-            }
-        }
-        if (a.amax_out) wave_max_to_global(m, a.amax_out);
-        return;
     }
     uint32_t draw[2][2] = {{0u, 0u}, {0u, 0u}};
     if (kMode == QII_MS_EDEN) octet_draws(draw, a.seed_sr, chunk, j0, q);

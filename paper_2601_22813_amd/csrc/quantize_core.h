@@ -141,16 +141,20 @@ __device__ __forceinline__ float e8m3_rtn(float u)
 // Heavy pass of the post hoc scheme (Sec. 7) for one group; needs no tensor maximum.
 // Pseudo-scale p = RTN_E8M3(gmax / s), codes RTN_FP4(y_i / p), returns the corrected
 // pseudo-scale t = <y,y> / <y, codes> (p cancels; t = p when the denominator is not positive,
-// 0 for an all-zero group).  The divisions are full IEEE divisions: without the tensor maximum
-// nothing is known about the range of the operands.
+// 0 for an all-zero group).  The three divisions take the short exact sequences when every
+// lane of the wave has its group maximum in (2^-20, 2^20) or zero (then all operands are far
+// from the denormal and overflow ranges), else full IEEE divisions.  Call with all lanes active.
 __device__ __forceinline__ float posthoc_group16(const float y[16], uint32_t packed[2], float &gmax)
 {
+    constexpr float kS = (float)(96.0 / 17.0 / 0.93), kRs = (float)(1.0 / (double)kS);
     packed[0] = 0u;
     packed[1] = 0u;
     gmax = group_absmax(y);
-    const float p = e8m3_rtn(gmax / (float)(96.0 / 17.0 / 0.93));
+    const bool odd = !(gmax == 0.0f || (gmax > 0x1p-20f && gmax < 0x1p20f));
+    const bool fast = __builtin_amdgcn_ballot_w64(odd) == 0ull;   // wave-uniform
+    const float p = e8m3_rtn(div_by_const(gmax, kS, kRs, fast));
     if (!(p > 0.0f)) return 0.0f;
-    const float inv = 1.0f / p;
+    const float inv = fast ? div_safe_range(1.0f, p) : 1.0f / p;
 #define QII_ENC(H, I)                                                                             \
     packed[H] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed[H], y[8 * H + 2 * I] * inv,       \
                                                          y[8 * H + 2 * I + 1] * inv, 1.0f, I)
@@ -170,16 +174,22 @@ __device__ __forceinline__ float posthoc_group16(const float y[16], uint32_t pac
     QII_DOT(0, 0); QII_DOT(0, 1); QII_DOT(0, 2); QII_DOT(0, 3);
     QII_DOT(1, 0); QII_DOT(1, 1); QII_DOT(1, 2); QII_DOT(1, 3);
 #undef QII_DOT
-    return den > 0.0f ? num / den : p;
+    if (!(den > 0.0f)) return p;
+    return fast ? div_safe_range(num, den) : num / den;
 }
 
 // a wave's maximum into the global running maximum (non-negative floats order like their bits)
-__device__ __forceinline__ void wave_max_to_global(float m, uint32_t *amax_bits)
+__device__ __forceinline__ float wave_max(float m)
 {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    return m;
+}
+
+__device__ __forceinline__ void max_to_global(float m, uint32_t *amax_bits)
+{
     // the running maximum only grows, so a stale read can only cause a redundant atomic
-    if ((threadIdx.x & 63) == 0 && f2u(m) > __atomic_load_n(amax_bits, __ATOMIC_RELAXED)) atomicMax(amax_bits, f2u(m));
+    if (f2u(m) > __atomic_load_n(amax_bits, __ATOMIC_RELAXED)) atomicMax(amax_bits, f2u(m));
 }
 
 // Quantize one group.  y: rotated values; draw20: the 20 scale-rounding bits of this group

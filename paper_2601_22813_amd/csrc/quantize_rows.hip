@@ -266,7 +266,10 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowsArgs a)
     for (; quad + gridDim.x < quads; quad += gridDim.x)
         quantize_quad<kBf16, kMode, kRht, true>(a, L, tc, mask, raw, quad, quad + gridDim.x, G, gc, m);
     quantize_quad<kBf16, kMode, kRht, false>(a, L, tc, mask, raw, quad, quad, G, gc, m);
-    if (kMode == QII_MS_EDEN_PH && a.amax_out) wave_max_to_global(m, a.amax_out);
+    if (kMode == QII_MS_EDEN_PH && a.amax_out) {   // one atomic per wave at most; a wave covers many quads
+        m = wave_max(m);
+        if ((threadIdx.x & 63) == 0) max_to_global(m, a.amax_out);
+    }
 }
 
 template <bool kBf16, bool kRht>
