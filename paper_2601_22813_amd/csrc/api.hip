@@ -94,7 +94,8 @@ qii_status nvfp4_source(const qii_nvfp4 *in, int transpose, int rht_group, qii::
 // measure (if needed) and quantize one logical R x C source
 qii_status quantize_source(const qii::Source &src, int64_t R, int64_t C, qii_mode mode, int rht_group,
                            uint64_t seed_rht, uint64_t seed_sr, const float *amax_in,
-                           const qii_nvfp4 *out, float *amax_slot, float *tbuf, hipStream_t s)
+                           const qii_nvfp4 *out, float *amax_slot, float *tbuf, hipStream_t s,
+                           bool slot_zeroed = false)
 {
     if (mode != QII_RTN && mode != QII_SR && mode != QII_MS_EDEN && mode != QII_RTN_46 && mode != QII_MS_EDEN_PH)
         return fail(QII_INVALID_ARG, "bad mode %d", (int)mode);
@@ -107,8 +108,8 @@ qii_status quantize_source(const qii::Source &src, int64_t R, int64_t C, qii_mod
     if (mode == QII_MS_EDEN_PH) {
         // Sec. 7: heavy pass (codes, corrected pseudo-scales, running maximum), then scales only
         if (!tbuf) return fail(QII_WORKSPACE_TOO_SMALL, "the post hoc scheme needs qii_quantize_posthoc_workspace_bytes of workspace");
-        if (!amax_in) {
-            hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(amax_slot), 0u, s);
+        if (!amax_in && !slot_zeroed) {
+            hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(amax_slot), 0u, 1, 1, s);
             if (e != hipSuccess) return hip_fail(e, "fill");
         }
         qii::QuantizeArgs a;
@@ -126,7 +127,8 @@ qii_status quantize_source(const qii::Source &src, int64_t R, int64_t C, qii_mod
     const float *amax = amax_in;
     if (!amax) {
         if (!amax_slot) return fail(QII_WORKSPACE_TOO_SMALL, "workspace needed to measure the abs-max");
-        hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(amax_slot), 0u, s);
+        hipError_t e = hipSuccess;
+        if (!slot_zeroed) e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(amax_slot), 0u, 1, 1, s);
         if (e != hipSuccess) return hip_fail(e, "fill");
         e = qii::launch_absmax(src, R, C, rht_group == 128, seed_rht, amax_slot, s);
         if (e != hipSuccess) return hip_fail(e, "absmax");
@@ -164,15 +166,39 @@ qii_status carve_quantize_ws(qii_mode mode, const float *amax_in, int64_t R, int
     return QII_OK;
 }
 
-// quantizer workspace of a backward pass: the abs-max slot plus, for the post hoc scheme, one f32
+// the two quantizer front ends on caller-carved workspace pieces (layer passes: their abs-max
+// slots are cleared by one launch for the whole pass)
+qii_status quantize_dense(const void *x, qii_dtype dt, int64_t rows, int64_t cols, int64_t ld, int transpose,
+                          qii_mode mode, int rht_group, uint64_t seed_rht, uint64_t seed_sr,
+                          const qii_nvfp4 *out, float *slot, float *tbuf, hipStream_t s, bool slot_zeroed)
+{
+    qii::Source src;
+    int64_t R, C;
+    qii_status st = dense_source(x, dt, rows, cols, ld, transpose, rht_group, &src, &R, &C);
+    if (st != QII_OK) return st;
+    return quantize_source(src, R, C, mode, rht_group, seed_rht, seed_sr, nullptr, out, slot, tbuf, s, slot_zeroed);
+}
+
+qii_status requantize_saved(const qii_nvfp4 *in, int transpose, qii_mode mode, int rht_group, uint64_t seed_rht,
+                            uint64_t seed_sr, const qii_nvfp4 *out, float *slot, float *tbuf, hipStream_t s,
+                            bool slot_zeroed)
+{
+    qii::Source src;
+    int64_t R, C;
+    qii_status st = nvfp4_source(in, transpose, rht_group, &src, &R, &C);
+    if (st != QII_OK) return st;
+    return quantize_source(src, R, C, mode, rht_group, seed_rht, seed_sr, nullptr, out, slot, tbuf, s, slot_zeroed);
+}
+
+// quantizer workspace of a backward pass: four abs-max slots plus, for the post hoc scheme, one f32
 // per group of the largest of its four tensors (T x d_out and d_in x max(d_out, T))
 size_t posthoc_region_bytes(int64_t T, int64_t d_in, int64_t d_out, qii_mode mode)
 {
-    if (mode != QII_MS_EDEN_PH) return kSlot;
+    if (mode != QII_MS_EDEN_PH) return 4 * kSlot;
     int64_t groups = T * d_out / 16;
     if (d_in * d_out / 16 > groups) groups = d_in * d_out / 16;
     if (d_in * T / 16 > groups) groups = d_in * T / 16;
-    return kSlot + align_up((size_t)groups * 4);
+    return 4 * kSlot + align_up((size_t)groups * 4);
 }
 
 size_t nvfp4_bytes(int64_t rows, int64_t cols)
@@ -254,7 +280,7 @@ qii_status qii_rht(const void *x, qii_dtype dt, int64_t rows, int64_t cols, int6
     if (!y || !aligned(y, 16)) return fail(QII_INVALID_ARG, "y must be non-null and 16-byte aligned");
     hipStream_t s = (hipStream_t)stream;
     if (amax) {
-        hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(amax), 0u, s);
+        hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(amax), 0u, 1, 1, s);
         if (e != hipSuccess) return hip_fail(e, "fill");
     }
     hipError_t e = qii::launch_rht(src, R, C, seed_rht, y, amax, s);
@@ -271,7 +297,7 @@ qii_status qii_absmax(const void *x, qii_dtype dt, int64_t rows, int64_t cols, i
     if (st != QII_OK) return st;
     if (!amax) return fail(QII_INVALID_ARG, "null amax");
     hipStream_t s = (hipStream_t)stream;
-    hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(amax), 0u, s);
+    hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(amax), 0u, 1, 1, s);
     if (e != hipSuccess) return hip_fail(e, "fill");
     e = qii::launch_absmax(src, R, C, rht_group == 128, seed_rht, amax, s);
     if (e != hipSuccess) return hip_fail(e, "absmax");
@@ -351,9 +377,16 @@ qii_status qii_linear_fwd_mode(const void *X, const void *W, qii_dtype dt, int64
         return fail(QII_WORKSPACE_TOO_SMALL, "linear_fwd needs %zu bytes of 256-byte aligned workspace",
                     qii_linear_fwd_workspace_bytes(T, d_in, d_out));
     uint8_t *p = reinterpret_cast<uint8_t *>(ws);
-    qii_status st = qii_quantize_nvfp4(X, dt, T, d_in, d_in, 0, mode, 0, 0, 0, nullptr, Xq, p, kSlot, stream);
+    hipStream_t s = (hipStream_t)stream;
+    float *slots = reinterpret_cast<float *>(p);
+    const int slot_words = (int)(kSlot / 4);
+    if (T * d_in > 0 || d_out * d_in > 0) {
+        hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(slots), 0u, 2, slot_words, s);
+        if (e != hipSuccess) return hip_fail(e, "fill");
+    }
+    qii_status st = quantize_dense(X, dt, T, d_in, d_in, 0, mode, 0, 0, 0, Xq, slots, nullptr, s, true);
     if (st != QII_OK) return st;
-    st = qii_quantize_nvfp4(W, dt, d_out, d_in, d_in, 0, mode, 0, 0, 0, nullptr, Wq, p + kSlot, kSlot, stream);
+    st = quantize_dense(W, dt, d_out, d_in, d_in, 0, mode, 0, 0, 0, Wq, slots + slot_words, nullptr, s, true);
     if (st != QII_OK) return st;
     return qii_gemm_nvfp4(Xq, Wq, Y, y_dt, d_out, p + 2 * kSlot, ws_bytes - 2 * kSlot, stream);
 }
@@ -382,11 +415,14 @@ qii_status qii_linear_bwd_mode(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq
     if (!ws || ws_bytes < need || !aligned(ws, kSlot))
         return fail(QII_WORKSPACE_TOO_SMALL, "linear_bwd needs %zu bytes of 256-byte aligned workspace", need);
     uint8_t *p = reinterpret_cast<uint8_t *>(ws);
-    // one quantizer workspace, used by the four quantizers one after the other on the stream:
-    // the abs-max slot and, for the post hoc scheme, the per-group f32 buffer of the largest tensor
-    uint8_t *qws = p;
-    const size_t qws_bytes = posthoc_region_bytes(T, d_in, d_out, mode);
-    p += qws_bytes;
+    // quantizer workspace: four abs-max slots, cleared by one launch, and, for the post hoc
+    // scheme, one per-group f32 buffer sized for the largest tensor and used by the four
+    // quantizers one after the other on the stream
+    hipStream_t s = (hipStream_t)stream;
+    float *slots = reinterpret_cast<float *>(p);
+    const int slot_words = (int)(kSlot / 4);
+    float *tbuf = mode == QII_MS_EDEN_PH ? reinterpret_cast<float *>(p + 4 * kSlot) : nullptr;
+    p += posthoc_region_bytes(T, d_in, d_out, mode);
     qii_nvfp4 Eq = carve_nvfp4(p, T, d_out);
     qii_nvfp4 WTq = carve_nvfp4(p, d_in, d_out);
     qii_nvfp4 ETq = carve_nvfp4(p, d_out, T);
@@ -395,17 +431,19 @@ qii_status qii_linear_bwd_mode(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq
     const size_t gws_bytes = reinterpret_cast<uint8_t *>(ws) + ws_bytes - p;
     uint64_t sd[6];
     for (uint32_t i = 0; i < 6; ++i) sd[i] = qii_derive_seed(seed, i);
+    hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(slots), 0u, 4, slot_words, s);
+    if (e != hipSuccess) return hip_fail(e, "fill");
     // dX = Q(E) Q(W^T)^T : rotation sd[0] on the inner dimension d_out
-    st = qii_quantize_nvfp4(dY, dt, T, d_out, d_out, 0, mode, 128, sd[0], sd[2], nullptr, &Eq, qws, qws_bytes, stream);
+    st = quantize_dense(dY, dt, T, d_out, d_out, 0, mode, 128, sd[0], sd[2], &Eq, slots, tbuf, s, true);
     if (st != QII_OK) return st;
-    st = qii_requantize_nvfp4(Wq, 1, mode, 128, sd[0], sd[3], nullptr, &WTq, qws, qws_bytes, stream);
+    st = requantize_saved(Wq, 1, mode, 128, sd[0], sd[3], &WTq, slots + slot_words, tbuf, s, true);
     if (st != QII_OK) return st;
     st = qii_gemm_nvfp4(&Eq, &WTq, dX, g_dt, d_in, gws, gws_bytes, stream);
     if (st != QII_OK) return st;
     // dW = Q(E^T) Q(X^T)^T : rotation sd[1] on the inner dimension T
-    st = qii_quantize_nvfp4(dY, dt, T, d_out, d_out, 1, mode, 128, sd[1], sd[4], nullptr, &ETq, qws, qws_bytes, stream);
+    st = quantize_dense(dY, dt, T, d_out, d_out, 1, mode, 128, sd[1], sd[4], &ETq, slots + 2 * slot_words, tbuf, s, true);
     if (st != QII_OK) return st;
-    st = qii_requantize_nvfp4(Xq, 1, mode, 128, sd[1], sd[5], nullptr, &XTq, qws, qws_bytes, stream);
+    st = requantize_saved(Xq, 1, mode, 128, sd[1], sd[5], &XTq, slots + 3 * slot_words, tbuf, s, true);
     if (st != QII_OK) return st;
     return qii_gemm_nvfp4(&ETq, &XTq, dW, g_dt, d_in, gws, gws_bytes, stream);
 }

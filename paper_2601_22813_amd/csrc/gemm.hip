@@ -424,13 +424,22 @@ constexpr int BK4 = 256;
 constexpr int kOff4A = 0, kOff4B = 32768, kOff4As = 65536, kOff4Bs = 69632, kStage4Bytes = 73728;
 constexpr int kSmem4 = 2 * kStage4Bytes;   // 144 KiB
 
-// scales[rows][K/16] -> tiled[(rt * (K/256) + ks) * 256 + r][16], one 16-byte piece per thread
-__global__ void retile_scales_kernel(const uint8_t *__restrict__ scales, uint8_t *__restrict__ tiled,
-                                     int64_t rows, int64_t K)
+// scales[rows][K/16] -> tiled[(rt * (K/256) + ks) * 256 + r][16], one 16-byte piece per thread;
+// both operands in one launch (threads [0, na) take A, [na, na + nb) take B)
+__global__ void retile_scales_kernel(const uint8_t *__restrict__ a_scales, uint8_t *__restrict__ a_tiled,
+                                     int64_t M, const uint8_t *__restrict__ b_scales,
+                                     uint8_t *__restrict__ b_tiled, int64_t N, int64_t K)
 {
     const int64_t ksn = K / 256;
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // (row, ks)
-    if (idx >= rows * ksn) return;
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // (row, ks)
+    const uint8_t *scales = a_scales;
+    uint8_t *tiled = a_tiled;
+    if (idx >= M * ksn) {
+        idx -= M * ksn;
+        if (idx >= N * ksn) return;
+        scales = b_scales;
+        tiled = b_tiled;
+    }
     const int64_t row = idx / ksn, ks = idx % ksn;
     const uint4 v = *reinterpret_cast<const uint4 *>(scales + row * (K / 16) + ks * 16);
     *reinterpret_cast<uint4 *>(tiled + (((row >> 8) * ksn + ks) * 256 + (row & 255)) * 16) = v;
@@ -680,8 +689,8 @@ hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is
         uint8_t *a_tiled = reinterpret_cast<uint8_t *>(ws);
         uint8_t *b_tiled = a_tiled + (M + 255) / 256 * 256 * (K / 16);
         const int64_t na = M * (K / 256), nb = N * (K / 256);
-        hipLaunchKernelGGL(retile_scales_kernel, dim3((unsigned)((na + 255) / 256)), dim3(256), 0, s, A.scales, a_tiled, M, K);
-        hipLaunchKernelGGL(retile_scales_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, s, B.scales, b_tiled, N, K);
+        hipLaunchKernelGGL(retile_scales_kernel, dim3((unsigned)((na + nb + 255) / 256)), dim3(256), 0, s, A.scales,
+                           a_tiled, M, B.scales, b_tiled, N, K);
         hipError_t e;
         if (c_is_bf16) {
             e = hipFuncSetAttribute((const void *)gemm_kernel_v4<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kSmem4);

@@ -40,7 +40,9 @@ struct QuantizeArgs {
     uint32_t *amax_accum;
 };
 
-hipError_t launch_fill_u32(uint32_t *p, uint32_t v, hipStream_t s);
+// p[i * stride_words] = v for i < count (count <= 256); a kernel, not a memset node, so that the
+// calls can be captured in a HIP graph
+hipError_t launch_fill_u32(uint32_t *p, uint32_t v, int count, int stride_words, hipStream_t s);
 hipError_t launch_absmax(const Source &src, int64_t R, int64_t C, int rht, uint64_t seed_rht,
                          float *amax /* must hold 0 */, hipStream_t s);
 hipError_t launch_rht(const Source &src, int64_t R, int64_t C, uint64_t seed_rht, float *y,

@@ -178,7 +178,8 @@ __device__ __forceinline__ void block_max_to_global(float m, uint32_t *amax_bits
 }
 
 // ------------------------------------------------------------------ kernels
-__global__ void fill_u32_kernel(uint32_t *p, uint32_t v) { *p = v; }
+// one word per thread, `stride` words apart (the abs-max slots of a layer pass in one launch)
+__global__ void fill_u32_kernel(uint32_t *p, uint32_t v, int stride) { p[threadIdx.x * stride] = v; }
 
 template <class Loader, bool kRht>
 __global__ __launch_bounds__(256) void absmax_kernel(Loader load, int64_t R, int64_t C,
@@ -372,9 +373,9 @@ hipError_t with_loader(const Source &src, F &&f)
 
 }  // namespace
 
-hipError_t launch_fill_u32(uint32_t *p, uint32_t v, hipStream_t s)
+hipError_t launch_fill_u32(uint32_t *p, uint32_t v, int count, int stride_words, hipStream_t s)
 {
-    hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(1), 0, s, p, v);
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(count), 0, s, p, v, stride_words);
     return hipGetLastError();
 }
 
