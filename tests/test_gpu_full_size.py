@@ -66,3 +66,49 @@ def test_linear_layer_at_benchmark_size(oracle):
     out = qii.NVFP4Tensor.empty(T, d_out)
     qii.qii_quantize_nvfp4(E, False, qii.MS_EDEN, 128, s[0], s[2], None, out, ws(256))
     assert_nv_equal(out, Eq, "Q(E)")
+
+
+def test_paper_recipe_layer_at_benchmark_size(oracle):
+    """The same layer as the paper runs it and as bench.py also times it: 4/6 on the forward pass
+    (Sec. 4.1), post hoc range alignment on the backward pass (Sec. 7)."""
+    T, d_in, d_out = 16384, 2048, 8192
+    rng = np.random.default_rng(1)
+    Xb, Wb, Eb = synth.linear_layer_bf16(T, d_in, d_out, seed=2)
+    X, W, E = to_dev(Xb), to_dev(Wb), to_dev(Eb)
+    Xq, Wq = qii.NVFP4Tensor.empty(T, d_in), qii.NVFP4Tensor.empty(d_out, d_in)
+    Y = torch.empty((T, d_out), dtype=torch.bfloat16, device="cuda")
+    print("forward 4/6", flush=True)
+    qii.qii_linear_fwd_mode(X, W, qii.RTN_46, Y, Xq, Wq, ws(qii.qii_linear_fwd_workspace_bytes(T, d_in, d_out)))
+    oXq, oWq = oracle.linear_fwd(Xb, Wb, mode=oracle.RTN_46)
+    assert_nv_equal(Xq, oXq, "saved X (4/6)")
+    assert_nv_equal(Wq, oWq, "saved W (4/6)")
+    ms, ns = sample_pairs(T, d_out, 4096, rng)
+    check_samples(Y, oXq, oWq, ms, ns, oracle, True, "Y (4/6)")
+    print("backward post hoc", flush=True)
+    dX = torch.empty((T, d_in), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((d_out, d_in), dtype=torch.bfloat16, device="cuda")
+    seed = 77
+    qii.qii_linear_bwd_mode(E, Xq, Wq, seed, qii.MS_EDEN_PH, dX, dW,
+                            ws(qii.qii_linear_bwd_mode_workspace_bytes(T, d_in, d_out, qii.MS_EDEN_PH)))
+    torch.cuda.synchronize()
+    print("oracle operands", flush=True)
+    Eq, WTq, ETq, XTq = oracle.linear_bwd_operands(Eb, oXq, oWq, seed, mode=oracle.MS_EDEN_PH)
+    ms, ns = sample_pairs(T, d_in, 4096, rng)
+    check_samples(dX, Eq, WTq, ms, ns, oracle, True, "dX (post hoc)")
+    ms, ns = sample_pairs(d_out, d_in, 4096, rng)
+    check_samples(dW, ETq, XTq, ms, ns, oracle, True, "dW (post hoc)")
+    # the four quantized operands, byte for byte, through the public quantizer with the derived seeds
+    s = [qii.qii_derive_seed(seed, i) for i in range(6)]
+    w = ws(qii.qii_quantize_posthoc_workspace_bytes(T, d_out))
+    out = qii.NVFP4Tensor.empty(T, d_out)
+    qii.qii_quantize_nvfp4(E, False, qii.MS_EDEN_PH, 128, s[0], s[2], None, out, w)
+    assert_nv_equal(out, Eq, "Q(E) post hoc")
+    out = qii.NVFP4Tensor.empty(d_out, T)
+    qii.qii_quantize_nvfp4(E, True, qii.MS_EDEN_PH, 128, s[1], s[4], None, out, w)
+    assert_nv_equal(out, ETq, "Q(E^T) post hoc")
+    out = qii.NVFP4Tensor.empty(d_in, d_out)
+    qii.qii_requantize_nvfp4(Wq, True, qii.MS_EDEN_PH, 128, s[0], s[3], None, out, w)
+    assert_nv_equal(out, WTq, "Q(W^T) post hoc")
+    out = qii.NVFP4Tensor.empty(d_in, T)
+    qii.qii_requantize_nvfp4(Xq, True, qii.MS_EDEN_PH, 128, s[1], s[5], None, out, w)
+    assert_nv_equal(out, XTq, "Q(X^T) post hoc")
