@@ -33,6 +33,74 @@ BYTES_PER_ELEM_POSTHOC = 2 + 0.5 + 0.25 + 0.25 + 0.0625
 TRAFFIC_QUANT_ROWS_BYTES = 172_278_000       # measured, see the roofline entry below
 
 
+# Weight shapes [d_in, d_out] of Llama-like models (App. D, table of linear shapes), 8 x 2048 tokens.
+PAPER_SHAPES = {
+    "800M": {"QKV": (2048, 6144), "Out": (2048, 2048), "UpGate": (2048, 11264), "Down": (5632, 2048)},
+    "3B": {"QKV": (3072, 9216), "Out": (3072, 3072), "UpGate": (3072, 16384), "Down": (8192, 3072)},
+    "7B": {"QKV": (4096, 12288), "Out": (4096, 4096), "UpGate": (4096, 22016), "Down": (11008, 4096)},
+    "22B": {"QKV": (6144, 18432), "Out": (6144, 6144), "UpGate": (6144, 32768), "Down": (16384, 6144)},
+}
+
+
+def paper_shapes(torch, qii, synth, dev):
+    """Latency of forward + backward per model size, summed over its four layer shapes (the
+    aggregation of the paper's linear-layer speed-up figure), for the NVFP4 layer of this library
+    and for three plain bf16 matmuls (Y, dX, dW) of the same shapes."""
+    T = 8 * 2048
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    out = {}
+    for model, layers in PAPER_SHAPES.items():
+        tot_q, tot_b, flop = 0.0, 0.0, 0.0
+        per_layer = {}
+        for name, (d_in, d_out) in layers.items():
+            g = torch.Generator(device=dev).manual_seed(1)
+            X = torch.randn((T, d_in), device=dev, dtype=torch.float32, generator=g).to(torch.bfloat16)
+            W = (0.02 * torch.randn((d_out, d_in), device=dev, dtype=torch.float32, generator=g)).to(torch.bfloat16)
+            E = (1e-3 * torch.randn((T, d_out), device=dev, dtype=torch.float32, generator=g)).to(torch.bfloat16)
+            Xq, Wq = qii.NVFP4Tensor.empty(T, d_in), qii.NVFP4Tensor.empty(d_out, d_in)
+            Y = torch.empty((T, d_out), dtype=torch.bfloat16, device=dev)
+            dX = torch.empty((T, d_in), dtype=torch.bfloat16, device=dev)
+            dW = torch.empty((d_out, d_in), dtype=torch.bfloat16, device=dev)
+            ws_f = torch.empty(qii.qii_linear_fwd_workspace_bytes(T, d_in, d_out), dtype=torch.uint8, device=dev)
+            ws_b = torch.empty(qii.qii_linear_bwd_mode_workspace_bytes(T, d_in, d_out, qii.MS_EDEN_PH),
+                               dtype=torch.uint8, device=dev)
+
+            def nvfp4(i):
+                qii.qii_linear_fwd_mode(X, W, qii.RTN_46, Y, Xq, Wq, ws_f)
+                qii.qii_linear_bwd_mode(E, Xq, Wq, i, qii.MS_EDEN_PH, dX, dW, ws_b)
+
+            def bf16(i):
+                torch.matmul(X, W.t(), out=Y)
+                torch.matmul(E, W, out=dX)
+                torch.matmul(E.t(), X, out=dW)
+
+            ms = []
+            for fn in (nvfp4, bf16):
+                for i in range(2):
+                    fn(i)
+                torch.cuda.synchronize()
+                e0, e1 = ev(), ev()
+                e0.record()
+                for i in range(5):
+                    fn(i)
+                e1.record()
+                torch.cuda.synchronize()
+                ms.append(e0.elapsed_time(e1) / 5)
+            per_layer[name] = {"d_in": d_in, "d_out": d_out, "nvfp4_ms": round(ms[0], 4), "bf16_ms": round(ms[1], 4)}
+            tot_q += ms[0]
+            tot_b += ms[1]
+            flop += 6.0 * T * d_in * d_out
+            del X, W, E, Xq, Wq, Y, dX, dW, ws_f, ws_b
+        out[model] = {"nvfp4_ms": round(tot_q, 4), "bf16_ms": round(tot_b, 4),
+                      "nvfp4_TFLOPs": round(flop / (tot_q * 1e-3) / 1e12, 1),
+                      "bf16_TFLOPs": round(flop / (tot_b * 1e-3) / 1e12, 1),
+                      "speedup_over_bf16": round(tot_b / tot_q, 3), "layers": per_layer}
+    out["note"] = ("tokens 16384; NVFP4 = 4/6 forward + post hoc MS-EDEN backward incl. all quantizers; bf16 = three "
+                   "torch.matmul calls (vendor GEMM), no quantization; on this GPU the NVFP4 products run on the f16 "
+                   "matrix instruction, whose peak equals the bf16 peak, so no speed-up over bf16 is possible here")
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -47,6 +115,12 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=16384)
     ap.add_argument("--d-in", type=int, default=2048)
     ap.add_argument("--d-out", type=int, default=8192)
+    ap.add_argument("--paper-shapes", action="store_true",
+                    help="after the timed steps, also time one layer forward + backward (4/6 forward, "
+                         "post hoc backward) for every weight shape of the paper's table of Llama-like "
+                         "layers (App. D) at 8 x 2048 tokens, next to a plain bf16 matmul of the same "
+                         "shapes (torch.matmul, i.e. the vendor GEMM library) as the 'speedup over BF16' "
+                         "denominator; adds a paper_shapes object to the JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives, no sharding); "
@@ -244,6 +318,9 @@ def main() -> int:
             "frac": round(gemm_tflops / MFMA_F16_PEAK_TFLOPS, 4),
         },
     }
+
+    if args.paper_shapes:
+        result["paper_shapes"] = paper_shapes(torch, qii, synth, dev)
 
     if not args.no_cpu_baseline:
         import oracle
