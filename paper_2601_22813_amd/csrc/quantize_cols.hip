@@ -228,6 +228,8 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(ColsArgs a)
         }
         return;
     }
+    __shared__ float inv_tab[128];
+    fill_inv_table(inv_tab, tc);   // before any wave leaves: it ends in a block-wide barrier
     if (chunk * 128 >= a.C) return;
     if (tc.zero) {  // uniform: an all-zero tensor is emitted as zero bytes
 #pragma unroll
@@ -255,7 +257,7 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(ColsArgs a)
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const uint32_t b = quantize_group16<kMode>(v[e] + 16 * h, tc, draw[e][h], a.seed_sr, j0 + e,
-                                                       chunk * 8 + 2 * q + h, codes + 2 * h);
+                                                       chunk * 8 + 2 * q + h, codes + 2 * h, inv_tab);
             sc |= b << (8 * h);
         }
         const uint2 s8 = gather_quad_scales(sc, q);

@@ -94,17 +94,44 @@ __device__ __forceinline__ float group_absmax(const float y[16])
     return fmaxf(m0, m1);
 }
 
+// The reciprocal 1 / (x^FP8 * x^FP32) only depends on the scale byte once the tensor scale is
+// known: a block fills a 128-entry table in LDS with full IEEE divisions at its start and every
+// group then reads its reciprocal instead of decoding the byte and dividing.  Entry 0 is unused.
+__device__ __forceinline__ void fill_inv_table(float *inv_tab, const TensorConsts &tc)
+{
+    if (threadIdx.x < 128) {
+        const float p = e4m3_decode(threadIdx.x) * tc.x32;
+        inv_tab[threadIdx.x] = threadIdx.x == 0 ? 0.0f : 1.0f / p;
+    }
+    __syncthreads();
+}
+
+__device__ __forceinline__ float group_inv(uint32_t b, const TensorConsts &tc, const float *inv_tab)
+{
+    if (inv_tab) return inv_tab[b];
+    return div_ieee(1.0f, e4m3_decode(b) * tc.x32, tc);
+}
+
+// e4m3_sr with the rare range below 2^-6 behind a wave-uniform branch
+__device__ __forceinline__ uint32_t e4m3_sr_wave(float t, uint32_t r20)
+{
+    const uint32_t bn = ((f2u(t) + r20) >> 20) - 960u;
+    const uint32_t b = bn > 0x7Eu ? 0x7Eu : bn;
+    if (__builtin_amdgcn_ballot_w64(t < 0x1p-6f) == 0ull) return b;
+    return t < 0x1p-6f ? ((uint32_t)(t * 0x1p29f) + r20) >> 20 : b;
+}
+
 // One candidate of the 4/6 choice (Sec. 4.1): round the group to nearest with the scale byte
 // RTN_FP8(r), r = group maximum / (x^FP32 * level).  Fills packed[2]; err = sum of
 // (x_i - c_i * (x^FP8 * x^FP32))^2, each difference one fused multiply-add, summed as a fused
 // multiply-add chain in index order.  A scale byte of 0 gives zero codes and err = <x, x>.
 __device__ __forceinline__ uint32_t rtn_candidate(const float y[16], float r, const TensorConsts &tc,
-                                                  uint32_t packed[2], float &err)
+                                                  const float *inv_tab, uint32_t packed[2], float &err)
 {
     const uint32_t b = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(fminf(r, 448.0f), 0.0f, 0, false) & 0xFFu;
     // with b == 0 the arithmetic below runs on a stand-in scale and its results are dropped
     const float p = b == 0u ? 1.0f : e4m3_decode(b) * tc.x32;
-    const float inv = div_ieee(1.0f, p, tc);
+    const float inv = inv_tab ? inv_tab[b] : div_ieee(1.0f, p, tc);   // (entry 0: results are dropped)
     packed[0] = 0u;
     packed[1] = 0u;
 #define QII_ENC(H, I)                                                                             \
@@ -198,7 +225,8 @@ __device__ __forceinline__ void max_to_global(float m, uint32_t *amax_bits)
 template <int kMode>
 __device__ __forceinline__ uint32_t quantize_group16(const float y[16], const TensorConsts &tc,
                                                      uint32_t draw20, uint64_t seed_sr, int64_t row,
-                                                     int64_t g, uint32_t packed[2])
+                                                     int64_t g, uint32_t packed[2],
+                                                     const float *inv_tab = nullptr)
 {
     packed[0] = 0u;
     packed[1] = 0u;
@@ -207,8 +235,8 @@ __device__ __forceinline__ uint32_t quantize_group16(const float y[16], const Te
         const float gmax = group_absmax(y);
         uint32_t p6[2], p4[2];
         float e6, e4;
-        const uint32_t b6 = rtn_candidate(y, div_by_const(gmax, tc.d, tc.rd, tc.fast), tc, p6, e6);
-        const uint32_t b4 = rtn_candidate(y, div_by_const(gmax, tc.d4, tc.rd4, tc.fast), tc, p4, e4);
+        const uint32_t b6 = rtn_candidate(y, div_by_const(gmax, tc.d, tc.rd, tc.fast), tc, inv_tab, p6, e6);
+        const uint32_t b4 = rtn_candidate(y, div_by_const(gmax, tc.d4, tc.rd4, tc.fast), tc, inv_tab, p4, e4);
         const bool use4 = e4 < e6;
         packed[0] = use4 ? p4[0] : p6[0];
         packed[1] = use4 ? p4[1] : p6[1];
@@ -218,8 +246,7 @@ __device__ __forceinline__ uint32_t quantize_group16(const float y[16], const Te
     const float r = div_by_tensor_const(group_absmax(y), tc);
     uint32_t b = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(fminf(r, 448.0f), 0.0f, 0, false) & 0xFFu;
     if (b == 0u) return 0u;
-    const float x8 = e4m3_decode(b);
-    const float inv = div_ieee(1.0f, x8 * tc.x32, tc);
+    const float inv = group_inv(b, tc, inv_tab);
     if (kMode == QII_SR) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -257,7 +284,7 @@ __device__ __forceinline__ uint32_t quantize_group16(const float y[16], const Te
         QII_DOT(0, 0); QII_DOT(0, 1); QII_DOT(0, 2); QII_DOT(0, 3);
         QII_DOT(1, 0); QII_DOT(1, 1); QII_DOT(1, 2); QII_DOT(1, 3);
 #undef QII_DOT
-        if (den > 0.0f) b = e4m3_sr(div_ieee(num, den * tc.x32, tc), draw20);
+        if (den > 0.0f) b = e4m3_sr_wave(div_ieee(num, den * tc.x32, tc), draw20);
     }
     return b;
 }

@@ -194,7 +194,8 @@ __device__ __forceinline__ void make_masks(uint32_t sign16, uint32_t mask[kBf16 
 template <bool kBf16, int kMode, bool kRht, bool kPrefetch>
 __device__ __forceinline__ void quantize_quad(const RowsArgs &a, const LaneSetup &L, const TensorConsts &tc,
                                               const uint32_t *mask, Raw<kBf16> raw[4], int64_t quad,
-                                              int64_t qn, int64_t G, int64_t gc, float &m)
+                                              int64_t qn, int64_t G, int64_t gc, float &m,
+                                              const float *inv_tab)
 {
     uint32_t draw[4] = {0u, 0u, 0u, 0u};
     if (kMode == QII_MS_EDEN) {
@@ -217,21 +218,24 @@ __device__ __forceinline__ void quantize_quad(const RowsArgs &a, const LaneSetup
             float gmax;
             const float t = posthoc_group16(v, packed, gmax);
             if (L.col_ok && row < a.R) {
-                *reinterpret_cast<uint2 *>(a.codes + (row * a.C + L.g * 16) / 2) = make_uint2(packed[0], packed[1]);
-                a.tbuf[row * G + L.g] = t;
+                *reinterpret_cast<uint2 *>(a.codes + row * (a.C / 2) + (uint32_t)L.g * 8u) = make_uint2(packed[0], packed[1]);
+                (a.tbuf + row * G)[(uint32_t)L.g] = t;
                 m = fmaxf(m, gmax);
             }
             continue;
         }
-        const uint32_t b = quantize_group16<kMode>(v, tc, draw[it], a.seed_sr, row, L.g, packed);
+        const uint32_t b = quantize_group16<kMode>(v, tc, draw[it], a.seed_sr, row, L.g, packed, inv_tab);
+        // row base pointers are wave-uniform (scalar registers); the lane adds a 32-bit offset
+        uint8_t *crow = a.codes + row * (a.C / 2), *srow = a.scales + row * G;
+        const uint32_t goff = (uint32_t)L.g;
         if (L.col_ok && row < a.R)
-            *reinterpret_cast<uint2 *>(a.codes + (row * a.C + L.g * 16) / 2) = make_uint2(packed[0], packed[1]);
+            *reinterpret_cast<uint2 *>(crow + goff * 8u) = make_uint2(packed[0], packed[1]);
         if (G % 8 == 0) {   // whole octets: one 8-byte store per chunk
             const uint2 sc = gather_scale_bytes(b, L.blk);
             if (L.col_ok && row < a.R && L.blk == 0)
-                *reinterpret_cast<uint2 *>(a.scales + row * G + L.g) = sc;
+                *reinterpret_cast<uint2 *>(srow + goff) = sc;
         } else if (L.col_ok && row < a.R) {
-            a.scales[row * G + L.g] = (uint8_t)b;
+            srow[goff] = (uint8_t)b;
         }
     }
 }
@@ -256,6 +260,8 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowsArgs a)
             }
         return;
     }
+    __shared__ float inv_tab[128];
+    if (kMode != QII_MS_EDEN_PH) fill_inv_table(inv_tab, tc);
     uint32_t mask[kBf16 ? 8 : 16];
     make_masks<kBf16>(L.sign16, mask);
     const int64_t gc = L.col_ok ? L.g : G - 1;
@@ -264,8 +270,8 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowsArgs a)
     load_quad<kBf16>(raw, a, quad, gc);
     float m = 0.0f;
     for (; quad + gridDim.x < quads; quad += gridDim.x)
-        quantize_quad<kBf16, kMode, kRht, true>(a, L, tc, mask, raw, quad, quad + gridDim.x, G, gc, m);
-    quantize_quad<kBf16, kMode, kRht, false>(a, L, tc, mask, raw, quad, quad, G, gc, m);
+        quantize_quad<kBf16, kMode, kRht, true>(a, L, tc, mask, raw, quad, quad + gridDim.x, G, gc, m, inv_tab);
+    quantize_quad<kBf16, kMode, kRht, false>(a, L, tc, mask, raw, quad, quad, G, gc, m, inv_tab);
     if (kMode == QII_MS_EDEN_PH && a.amax_out) {   // one atomic per wave at most; a wave covers many quads
         m = wave_max(m);
         if ((threadIdx.x & 63) == 0) max_to_global(m, a.amax_out);
