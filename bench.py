@@ -115,6 +115,10 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=16384)
     ap.add_argument("--d-in", type=int, default=2048)
     ap.add_argument("--d-out", type=int, default=8192)
+    ap.add_argument("--parts", choices=["all", "quantize", "linear"], default="all",
+                    help="run only the quantize-only parts or only the layer parts of a step (for profiles in "
+                         "which every launch of a kernel has the same tensor size); the JSON line then reports "
+                         "the skipped parts as null timings")
     ap.add_argument("--paper-shapes", action="store_true",
                     help="after the timed steps, also time one layer forward + backward (4/6 forward, "
                          "post hoc backward) for every weight shape of the paper's table of Llama-like "
@@ -179,37 +183,51 @@ def main() -> int:
              "posthoc_rows", "posthoc_cols", "linear_fwd", "linear_bwd", "linear_fwd_46", "linear_bwd_ph"]
     kernel_ms = {k: [] for k in names}
 
+    do_q, do_l = args.parts in ("all", "quantize"), args.parts in ("all", "linear")
+
     def step(i: int, record: bool):
         e = [ev() for _ in range(len(names) + 1)]
         a, b, c, d = (i * 4) % n_rot, (i * 4 + 1) % n_rot, (i * 4 + 2) % n_rot, (i * 4 + 3) % n_rot
         e[0].record()
-        qii.qii_quantize_nvfp4(xs[a], False, qii.MS_EDEN, 128, 0, i, amax_rows[a], out_rows, None)
+        if do_q:
+            qii.qii_quantize_nvfp4(xs[a], False, qii.MS_EDEN, 128, 0, i, amax_rows[a], out_rows, None)
         e[1].record()
-        qii.qii_quantize_nvfp4(xs[b], True, qii.MS_EDEN, 128, 0, i, amax_cols[b], out_cols, None)
+        if do_q:
+            qii.qii_quantize_nvfp4(xs[b], True, qii.MS_EDEN, 128, 0, i, amax_cols[b], out_cols, None)
         e[2].record()
-        qii.qii_absmax(xs[c], False, 128, 0, amax)
+        if do_q:
+            qii.qii_absmax(xs[c], False, 128, 0, amax)
         e[3].record()
-        qii.qii_quantize_nvfp4(xs[c], False, qii.MS_EDEN, 128, 0, i, amax, out_rows, None)
+        if do_q:
+            qii.qii_quantize_nvfp4(xs[c], False, qii.MS_EDEN, 128, 0, i, amax, out_rows, None)
         e[4].record()
-        qii.qii_absmax(xs[d], True, 128, 0, amax)
+        if do_q:
+            qii.qii_absmax(xs[d], True, 128, 0, amax)
         e[5].record()
-        qii.qii_quantize_nvfp4(xs[d], True, qii.MS_EDEN, 128, 0, i, amax, out_cols, None)
+        if do_q:
+            qii.qii_quantize_nvfp4(xs[d], True, qii.MS_EDEN, 128, 0, i, amax, out_cols, None)
         e[6].record()
         # the same two tensors without a known abs-max, in the two-kernel form of Sec. 7
-        qii.qii_quantize_nvfp4(xs[a], False, qii.MS_EDEN_PH, 128, 0, i, None, out_rows, ws_ph)
+        if do_q:
+            qii.qii_quantize_nvfp4(xs[a], False, qii.MS_EDEN_PH, 128, 0, i, None, out_rows, ws_ph)
         e[7].record()
-        qii.qii_quantize_nvfp4(xs[b], True, qii.MS_EDEN_PH, 128, 0, i, None, out_cols, ws_ph)
+        if do_q:
+            qii.qii_quantize_nvfp4(xs[b], True, qii.MS_EDEN_PH, 128, 0, i, None, out_cols, ws_ph)
         e[8].record()
         j = i % 3
-        qii.qii_linear_fwd(Xs[j], Ws[j], Y, Xq, Wq, ws_f)
+        if do_l:
+            qii.qii_linear_fwd(Xs[j], Ws[j], Y, Xq, Wq, ws_f)
         e[9].record()
-        qii.qii_linear_bwd(Es[j], Xq, Wq, i, dX, dW, ws_b)
+        if do_l:
+            qii.qii_linear_bwd(Es[j], Xq, Wq, i, dX, dW, ws_b)
         e[10].record()
         # the layer as the paper runs it: 4/6 on the forward pass, post hoc range alignment on the backward pass
         k = (i + 1) % 3
-        qii.qii_linear_fwd_mode(Xs[k], Ws[k], qii.RTN_46, Y, Xq, Wq, ws_f)
+        if do_l:
+            qii.qii_linear_fwd_mode(Xs[k], Ws[k], qii.RTN_46, Y, Xq, Wq, ws_f)
         e[11].record()
-        qii.qii_linear_bwd_mode(Es[k], Xq, Wq, i, qii.MS_EDEN_PH, dX, dW, ws_b)
+        if do_l:
+            qii.qii_linear_bwd_mode(Es[k], Xq, Wq, i, qii.MS_EDEN_PH, dX, dW, ws_b)
         e[12].record()
         return e if record else None
 
@@ -237,7 +255,7 @@ def main() -> int:
     # after the timed steps: the forward GEMM alone (the layer's dominant kernel), for its roofline line
     gemm_ws = torch.empty(max(256, qii.qii_gemm_workspace_bytes(T, d_out, d_in)), dtype=torch.uint8, device=dev)
     gemm_ms = []
-    for i in range(6):
+    for i in range(6 if do_l else 0):
         e0, e1 = ev(), ev()
         e0.record()
         qii.qii_gemm_nvfp4(Xq, Wq, Y, gemm_ws)
@@ -245,7 +263,7 @@ def main() -> int:
         torch.cuda.synchronize()
         if i:
             gemm_ms.append(e0.elapsed_time(e1))
-    gemm_tflops = 2.0 * T * d_in * d_out / (float(np.mean(gemm_ms)) * 1e-3) / 1e12
+    gemm_tflops = 2.0 * T * d_in * d_out / (float(np.mean(gemm_ms)) * 1e-3) / 1e12 if do_l else 0.0
 
     n = R * C
     bytes_a1 = 2 * n * BYTES_PER_ELEM_QUANT
@@ -319,10 +337,19 @@ def main() -> int:
         },
     }
 
+    if args.parts != "all":   # partial runs are for profiles: no figures for what did not run
+        result["config"]["parts"] = args.parts
+        if not do_q:
+            result["value"] = None
+            result["quantize"] = None
+            result["roofline"] = None
+        if not do_l:
+            result["linear_fwd_bwd"] = None
+            result["roofline_gemm"] = None
     if args.paper_shapes:
         result["paper_shapes"] = paper_shapes(torch, qii, synth, dev)
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and do_q:
         import oracle
         oracle.build()
         reps = 0
