@@ -2,8 +2,9 @@
 // (the contiguous case: Q(E), and the forward-pass RTN of X and W).
 //
 // Layout of the work: a lane owns one 16-element scale group, 8 lanes one 128-chunk, a wave
-// 8 consecutive chunks of a row (1024 elements, 2 KiB of bf16), a block 4 waves side by
-// side.  blockIdx.y selects the column range, blockIdx.x strides over row quads, so the
+// 8 consecutive chunks of a row (1024 elements, 2 KiB of bf16), a block 4 waves: side by
+// side on wide tensors, or, when a row needs fewer than 4 waves, 2 or 4 row quads at once.
+// blockIdx.y selects the column range, blockIdx.x strides over row quads, so the
 // per-thread set-up (lane constants, sign masks) is paid once for many groups.  The four
 // rows of a quad are loaded together (32 B per lane and row) before any arithmetic.
 //
@@ -35,10 +36,12 @@ struct RowsArgs {
     float *tensor_scale;
     uint32_t *amax_out;  // abs-max kernel, and the heavy pass of the post hoc scheme (nullable there)
     float *tbuf;         // post hoc scheme: corrected pseudo-scales [R][C/16]
+    int wpr;             // waves of a block that sit side by side on a row: 1, 2 or 4
 };
 
 struct LaneSetup {
     int blk;              // 16-block of the chunk owned by this lane
+    int64_t first, step;  // this wave's first row quad and its stride (quads)
     int64_t g;            // scale group within the row
     bool col_ok;
     float s16, s32, s64;  // +-1 multipliers of the three cross-lane stages
@@ -52,7 +55,11 @@ __device__ __forceinline__ LaneSetup lane_setup(const RowsArgs &a, int64_t G)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane & 7;
     L.blk = (sub & 4) ? (sub ^ 3) : sub;
-    const int64_t chunk = ((int64_t)blockIdx.y * 4 + wave) * 8 + (lane >> 3);
+    // wpr waves side by side, 4 / wpr row quads per block
+    const int wcol = wave & (a.wpr - 1), wq = wave / a.wpr, qpb = 4 / a.wpr;
+    L.first = (int64_t)blockIdx.x * qpb + wq;
+    L.step = (int64_t)gridDim.x * qpb;
+    const int64_t chunk = ((int64_t)blockIdx.y * a.wpr + wcol) * 8 + (lane >> 3);
     L.g = chunk * 8 + L.blk;
     L.col_ok = L.g < G;
     L.s16 = (L.blk & 1) ? -1.0f : 1.0f;
@@ -250,7 +257,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowsArgs a)
     if (kMode != QII_MS_EDEN_PH && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *a.tensor_scale = tc.x32;
     const int64_t quads = (a.R + 3) / 4;
     if (tc.zero) {  // uniform: an all-zero tensor is emitted as zero bytes
-        for (int64_t quad = blockIdx.x; quad < quads; quad += gridDim.x)
+        for (int64_t quad = L.first; quad < quads; quad += L.step)
             for (int it = 0; it < 4; ++it) {
                 const int64_t row = quad * 4 + it;
                 if (L.col_ok && row < a.R) {
@@ -266,11 +273,11 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowsArgs a)
     make_masks<kBf16>(L.sign16, mask);
     const int64_t gc = L.col_ok ? L.g : G - 1;
     Raw<kBf16> raw[4];
-    int64_t quad = blockIdx.x;             // the grid never has more blocks than quads
+    int64_t quad = L.first;   // (a wave whose first quad lies beyond the tensor stores nothing)
     load_quad<kBf16>(raw, a, quad, gc);
     float m = 0.0f;
-    for (; quad + gridDim.x < quads; quad += gridDim.x)
-        quantize_quad<kBf16, kMode, kRht, true>(a, L, tc, mask, raw, quad, quad + gridDim.x, G, gc, m, inv_tab);
+    for (; quad + L.step < quads; quad += L.step)
+        quantize_quad<kBf16, kMode, kRht, true>(a, L, tc, mask, raw, quad, quad + L.step, G, gc, m, inv_tab);
     quantize_quad<kBf16, kMode, kRht, false>(a, L, tc, mask, raw, quad, quad, G, gc, m, inv_tab);
     if (kMode == QII_MS_EDEN_PH && a.amax_out) {   // one atomic per wave at most; a wave covers many quads
         m = wave_max(m);
@@ -290,10 +297,10 @@ __global__ __launch_bounds__(256, 4) void absmax_rows_kernel(RowsArgs a)
     const int64_t gc = L.col_ok ? L.g : G - 1;
     float m = 0.0f;
     Raw<kBf16> raw[4];
-    load_quad<kBf16>(raw, a, blockIdx.x, gc);
-    for (int64_t quad = blockIdx.x; quad < quads; quad += gridDim.x) {
+    load_quad<kBf16>(raw, a, L.first, gc);
+    for (int64_t quad = L.first; quad < quads; quad += L.step) {
         Raw<kBf16> nxt[4];
-        const int64_t qn = quad + gridDim.x;
+        const int64_t qn = quad + L.step;
         load_quad<kBf16>(nxt, a, qn < quads ? qn : quad, gc);
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
@@ -318,16 +325,24 @@ __global__ __launch_bounds__(256, 4) void absmax_rows_kernel(RowsArgs a)
     }
 }
 
+// waves of a block side by side on a row: as many as the row needs, at most 4
+int rows_wpr(int64_t C)
+{
+    const int64_t nch = (C / 16 + 7) / 8;   // 128-chunks per row; a wave takes 8
+    return nch <= 8 ? 1 : nch <= 16 ? 2 : 4;
+}
+
 // blocks: as many as stay resident at once (4 per CU), with the row quads split evenly
 dim3 rows_grid(int64_t R, int64_t C)
 {
     const int64_t G = C / 16, nch = (G + 7) / 8;
-    const int64_t gy = (nch + 31) / 32;            // 4 waves x 8 chunks per block
-    const int64_t quads = (R + 3) / 4;
+    const int wpr = rows_wpr(C);
+    const int64_t gy = (nch + 8 * wpr - 1) / (8 * wpr);
+    const int64_t quads = (R + 3) / 4, qpb = 4 / wpr, bquads = (quads + qpb - 1) / qpb;
     int64_t cap = (256 * 4) / gy;                  // 256 CUs x 4 resident blocks
     if (cap < 1) cap = 1;
-    const int64_t iters = (quads + cap - 1) / cap; // iterations per block
-    int64_t gx = (quads + iters - 1) / iters;      // even split
+    const int64_t iters = (bquads + cap - 1) / cap; // iterations per block
+    int64_t gx = (bquads + iters - 1) / iters;      // even split
     if (gx < 1) gx = 1;
     return dim3((unsigned)gx, (unsigned)gy);
 }
@@ -341,6 +356,7 @@ RowsArgs make_args(const Source &src, int64_t R, int64_t C, uint64_t seed_rht, u
     a.seed_sr = seed_sr;
     a.amax = nullptr; a.codes = nullptr; a.scales = nullptr; a.tensor_scale = nullptr; a.amax_out = nullptr;
     a.tbuf = nullptr;
+    a.wpr = rows_wpr(C);
     return a;
 }
 
