@@ -23,6 +23,7 @@ namespace {
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 256, BN = 256, BK = 128;
 constexpr int kPitch = 80;   // bytes per LDS row of codes: 64 data + 16 pad (bank spread)
@@ -309,7 +310,8 @@ __device__ __forceinline__ void store_tile_through_lds(floatx16 (&acc)[4][4], ui
             if (grow < M) {
                 uint8_t *dst = reinterpret_cast<uint8_t *>(Cout) + (grow * ldc + gcol) * esz;
                 if (gcol + 16 / esz <= N && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
-                    *reinterpret_cast<uint4 *>(dst) = v;
+                    // C is written once and not read again here: a streaming (non-temporal) store
+                    __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4 *>(dst));
                 } else {
                     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -477,7 +479,6 @@ __device__ __forceinline__ void issue_tile_loads4(uint8_t *stage, const uint8_t 
 // K tile with the multiplication of the current one.  The fragment reads are therefore
 // written as inline assembly, with their own wait: a read block only names its
 // destination registers, and the matching wait "produces" them for the code that follows.
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 struct RawFrag4 {
     u32x4 a[4], b[4];       // 32 codes (16 bytes) of K for 4 row blocks of A and of B
     uint32_t sa[4], sb[4];  // their two scale bytes
