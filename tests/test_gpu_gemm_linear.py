@@ -160,3 +160,53 @@ def test_linear_forward_with_four_over_six(oracle):
     check(Y.cpu().numpy().astype(np.float64), ref, absum, False)
     with pytest.raises(qii.QiiError):
         qii.qii_linear_fwd_mode(X, W, qii.MS_EDEN, Y, Xq, Wq, w)
+
+
+def test_layer_passes_replay_from_a_hip_graph(oracle):
+    """Nothing in the library allocates, synchronises or uses memset nodes, so a forward + backward
+    pass can be captured once and replayed; every replay (with eager work and synchronisations in
+    between) must reproduce the eager results bit for bit, on fresh inputs written into the same
+    buffers."""
+    T, d_in, d_out = 256, 256, 384
+    X = torch.empty((T, d_in), dtype=torch.bfloat16, device="cuda")
+    W = torch.empty((d_out, d_in), dtype=torch.bfloat16, device="cuda")
+    E = torch.empty((T, d_out), dtype=torch.bfloat16, device="cuda")
+    Xq, Wq = qii.NVFP4Tensor.empty(T, d_in), qii.NVFP4Tensor.empty(d_out, d_in)
+    Y = torch.empty((T, d_out), dtype=torch.float32, device="cuda")
+    dX = torch.empty((T, d_in), dtype=torch.float32, device="cuda")
+    dW = torch.empty((d_out, d_in), dtype=torch.float32, device="cuda")
+    wf = ws(qii.qii_linear_fwd_workspace_bytes(T, d_in, d_out))
+    wb = ws(qii.qii_linear_bwd_mode_workspace_bytes(T, d_in, d_out, qii.MS_EDEN_PH))
+
+    def run():
+        qii.qii_linear_fwd_mode(X, W, qii.RTN_46, Y, Xq, Wq, wf)
+        qii.qii_linear_bwd_mode(E, Xq, Wq, 5, qii.MS_EDEN_PH, dX, dW, wb)
+
+    def fill(seed):
+        Xb, Wb, Eb = synth.linear_layer_bf16(T, d_in, d_out, seed=seed)
+        X.copy_(to_dev(Xb)); W.copy_(to_dev(Wb)); E.copy_(to_dev(Eb))
+
+    fill(100)
+    run()                       # warm-up outside the capture (function attributes, module load)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            run()
+    torch.cuda.current_stream().wait_stream(side)
+    for seed in (101, 102, 103):
+        fill(seed)
+        run()
+        torch.cuda.synchronize()
+        want = [t.clone() for t in (Y, dX, dW, Xq.codes, Xq.scales, Wq.codes, Wq.scales)]
+        for t in (Y, dX, dW):
+            t.zero_()
+        Xq.codes.zero_(); Wq.scales.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (Y, dX, dW, Xq.codes, Xq.scales, Wq.codes, Wq.scales)
+        for k, (g, w_) in enumerate(zip(got, want)):
+            assert torch.equal(g, w_), f"replay with seed {seed}: tensor {k} differs from the eager run"
