@@ -44,6 +44,17 @@ struct ColsArgs {
     float *tbuf;         // post hoc scheme: corrected pseudo-scales [R][C/16]
 };
 
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Buffer descriptor of the 128 source rows of one chunk: the loads below then take their
+// wave-uniform part (base, row offset) from scalar registers and only a 32-bit lane offset from
+// a vector register, with no per-lane 64-bit address arithmetic.  `bytes` covers exactly the
+// rows and columns a chunk reads; an offset beyond it would read 0, never fault.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t chunk_rsrc(const void *base, int64_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+
 // load this lane's 32 rows (rows 32q .. 32q+31 of the chunk) of columns j0 and j0+1 (j0 even),
 // widen to f32 and apply the rotation signs.  `chunk` is wave-uniform; j0 is clamped into the
 // tensor by the caller, so every lane loads from a valid address.
@@ -52,15 +63,17 @@ __device__ __forceinline__ void load_quarter_chunk(float v[2][32], const ColsArg
 {
     const uint32_t sw = q == 0 ? a.sign[0] : q == 1 ? a.sign[1] : q == 2 ? a.sign[2] : a.sign[3];
     if (kSrc == kSrcNVFP4) {
+        // buffer loads: wave-uniform base and row offset in scalar registers, 32-bit lane offset
         const int64_t cstride = a.ld / 2, sstride = a.ld / 16;
-        const uint8_t *pc = (const uint8_t *)a.x + (chunk * 128 + 32 * q) * cstride + j0 / 2;
-        const uint8_t *ps = a.in_scales + (chunk * 128 + 32 * q) * sstride + j0 / 16;
+        const __amdgpu_buffer_rsrc_t rc_rsrc = chunk_rsrc((const uint8_t *)a.x + chunk * 128 * cstride, 127 * cstride + a.R / 2);
+        const __amdgpu_buffer_rsrc_t rs_rsrc = chunk_rsrc(a.in_scales + chunk * 128 * sstride, 127 * sstride + a.R / 16);
+        const int oc = (int)(32 * q * cstride + j0 / 2), os = (int)(32 * q * sstride + j0 / 16);
         const float x32 = *a.in_ts;
         uint32_t rc[32], rs[32];
 #pragma unroll
         for (int i = 0; i < 32; ++i) {
-            rc[i] = pc[(int64_t)i * cstride];
-            rs[i] = ps[(int64_t)i * sstride];
+            rc[i] = __builtin_amdgcn_raw_buffer_load_b8(rc_rsrc, oc, (int)(i * cstride), 0);
+            rs[i] = __builtin_amdgcn_raw_buffer_load_b8(rs_rsrc, os, (int)(i * sstride), 0);
         }
 #pragma unroll
         for (int i = 0; i < 32; ++i) {
@@ -73,10 +86,11 @@ __device__ __forceinline__ void load_quarter_chunk(float v[2][32], const ColsArg
         return;
     }
     if (kSrc == kSrcBF16) {
-        const char *base = (const char *)a.x + ((chunk * 128 + 32 * q) * a.ld + j0) * 2;
+        const __amdgpu_buffer_rsrc_t rsrc = chunk_rsrc((const char *)a.x + chunk * 128 * a.ld * 2, (127 * a.ld + a.R) * 2);
+        const int off = (int)((32 * q * a.ld + j0) * 2);
         uint32_t raw[32];
 #pragma unroll
-        for (int i = 0; i < 32; ++i) raw[i] = *reinterpret_cast<const uint32_t *>(base + (int64_t)i * a.ld * 2);
+        for (int i = 0; i < 32; ++i) raw[i] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, off, (int)(i * a.ld * 2), 0);
 #pragma unroll
         for (int i = 0; i < 32; ++i) {
             const uint32_t flip = kRht ? (((sw >> i) & 1u) << 31) : 0u;
@@ -84,15 +98,16 @@ __device__ __forceinline__ void load_quarter_chunk(float v[2][32], const ColsArg
             v[1][i] = u2f((raw[i] & 0xFFFF0000u) ^ flip);
         }
     } else {
-        const char *base = (const char *)a.x + ((chunk * 128 + 32 * q) * a.ld + j0) * 4;
-        uint2 raw[32];
+        const __amdgpu_buffer_rsrc_t rsrc = chunk_rsrc((const char *)a.x + chunk * 128 * a.ld * 4, (127 * a.ld + a.R) * 4);
+        const int off = (int)((32 * q * a.ld + j0) * 4);
+        u32x2 raw[32];
 #pragma unroll
-        for (int i = 0; i < 32; ++i) raw[i] = *reinterpret_cast<const uint2 *>(base + (int64_t)i * a.ld * 4);
+        for (int i = 0; i < 32; ++i) raw[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off, (int)(i * a.ld * 4), 0);
 #pragma unroll
         for (int i = 0; i < 32; ++i) {
             const uint32_t flip = kRht ? (((sw >> i) & 1u) << 31) : 0u;
-            v[0][i] = u2f(raw[i].x ^ flip);
-            v[1][i] = u2f(raw[i].y ^ flip);
+            v[0][i] = u2f(raw[i][0] ^ flip);
+            v[1][i] = u2f(raw[i][1] ^ flip);
         }
     }
 }
@@ -326,6 +341,7 @@ dim3 cols_grid(int64_t R, int64_t C)
 bool cols_kernels_apply(const Source &src, int64_t R, int64_t C)
 {
     if (!src.transpose || C % 128 != 0 || R % 2 != 0 || (R + 31) / 32 > 65535) return false;
+    if (src.ld > (int64_t)1 << 21) return false;   // offsets within a chunk (128 rows, in bytes) stay below 2^31
     const uintptr_t p = reinterpret_cast<uintptr_t>(src.x);
     if (src.kind == kSrcBF16) return src.ld % 2 == 0 && p % 4 == 0;
     if (src.kind == kSrcF32) return src.ld % 2 == 0 && p % 8 == 0;
