@@ -143,7 +143,10 @@ QII_PAIR_STAGE(dpp_xor2_stage16, "quad_perm:[2,3,0,1]")
 #undef QII_PAIR_STAGE
 
 // y = H v / sqrt(128) over the 128 values of one column held by a lane quad: stages over
-// index bits 0..4 in-lane, bits 5 and 6 across the quad, then the scaling
+// index bits 0..4 in-lane, bits 5 and 6 across the quad, then the scaling (kScale = false: left
+// to the caller; the abs-max pass scales its maximum once, which is the same number because
+// rounding is monotone and symmetric)
+template <bool kScale = true>
 __device__ __forceinline__ void fwht128_quad(float v[32], int q)
 {
 #pragma unroll
@@ -161,8 +164,9 @@ __device__ __forceinline__ void fwht128_quad(float v[32], int q)
     dpp_xor2_stage16(v, s6);
     dpp_xor2_stage16(v + 16, s6);
     const float c = (q == 1 || q == 2) ? -kInvSqrt128 : kInvSqrt128;
+    if (kScale)
 #pragma unroll
-    for (int i = 0; i < 32; ++i) v[i] = __builtin_fmaf(v[i], c, 0.0f);  // +0 for exact zeros
+        for (int i = 0; i < 32; ++i) v[i] = __builtin_fmaf(v[i], c, 0.0f);  // +0 for exact zeros
 }
 
 // draws of this lane's groups: draw[e][h] for column j0+e, column group 8*chunk + 2q + h.
@@ -298,13 +302,14 @@ __global__ __launch_bounds__(256) void absmax_cols_kernel(ColsArgs a)
         // a clamped duplicate of a real column pair cannot change the maximum
         load_quarter_chunk<kSrc, kRht>(v, a, chunk, (uint32_t)(j0 < a.R ? j0 : a.R - 2), q);
         if (kRht) {
-            fwht128_quad(v[0], q);
-            fwht128_quad(v[1], q);
+            fwht128_quad<false>(v[0], q);
+            fwht128_quad<false>(v[1], q);
         }
 #pragma unroll
         for (int e = 0; e < 2; ++e)
 #pragma unroll
             for (int h = 0; h < 2; ++h) m = fmaxf(m, group_absmax(v[e] + 16 * h));
+        if (kRht) m = __builtin_fmaf(m, kInvSqrt128, 0.0f);   // the scaling the rotation left out
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));

@@ -100,6 +100,9 @@ __device__ __forceinline__ void dpp_stage_xor2(float v[16], float s) { QII_DPP_S
 __device__ __forceinline__ void dpp_stage_xor7(float v[16], float s) { QII_DPP_STAGE("row_half_mirror"); }
 
 // stages over index bits 0..3 (in-lane) then 4..6 (cross-lane), then the scaling
+// kScale = false leaves out the final scaling: for the abs-max pass, where rounding is monotone
+// and symmetric, max |fma(v, c, 0)| = fma(max |v|, |c|, 0), so one scaling of the maximum does
+template <bool kScale = true>
 __device__ __forceinline__ void rht128_lane(float v[16], const LaneSetup &L)
 {
 #pragma unroll
@@ -114,8 +117,9 @@ __device__ __forceinline__ void rht128_lane(float v[16], const LaneSetup &L)
     dpp_stage_xor1(v, L.s16);
     dpp_stage_xor2(v, L.s32);
     dpp_stage_xor7(v, L.s64);
+    if (kScale)
 #pragma unroll
-    for (int k = 0; k < 16; ++k) v[k] = __builtin_fmaf(v[k], L.cfin, 0.0f);  // +0 for exact zeros
+        for (int k = 0; k < 16; ++k) v[k] = __builtin_fmaf(v[k], L.cfin, 0.0f);  // +0 for exact zeros
 }
 
 // The 8 scale bytes of an octet's chunk are consecutive in memory; single-byte stores are
@@ -306,7 +310,7 @@ __global__ __launch_bounds__(256, 4) void absmax_rows_kernel(RowsArgs a)
         for (int it = 0; it < 4; ++it) {
             float v[16];
             unpack_signed<kBf16, kRht>(raw[it], v, mask);
-            if (kRht) rht128_lane(v, L);
+            if (kRht) rht128_lane<false>(v, L);
             // a clamped duplicate of a real row cannot change the maximum; lanes beyond the
             // last column hold a made-up chunk and are left out
             if (L.col_ok) m = fmaxf(m, group_absmax(v));
@@ -314,6 +318,7 @@ __global__ __launch_bounds__(256, 4) void absmax_rows_kernel(RowsArgs a)
 #pragma unroll
         for (int it = 0; it < 4; ++it) raw[it] = nxt[it];
     }
+    if (kRht) m = __builtin_fmaf(m, kInvSqrt128, 0.0f);   // the scaling the rotation left out
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
     if ((threadIdx.x & 63) == 0) wave_m[threadIdx.x >> 6] = m;
