@@ -28,6 +28,8 @@ HBM_PEAK_GBPS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2500.0
 BYTES_PER_ELEM_QUANT = 2 + 0.5 + 0.0625      # bf16 in, packed FP4 + E4M3 scale out
 BYTES_PER_ELEM_ABSMAX = 2.0                  # bf16 in
+ALU_FLOPS_PER_ELEM = 16.5                    # arithmetic the contract asks of MS-EDEN with RHT-128, per element
+VALU_F32_PEAK_TFLOPS = 157.3
 # post hoc scheme: bf16 in, FP4 + one f32 per group out; then that f32 in, E4M3 scale out
 BYTES_PER_ELEM_POSTHOC = 2 + 0.5 + 0.25 + 0.25 + 0.0625
 TRAFFIC_QUANT_ROWS_BYTES = 172_278_000       # measured, see the roofline entry below
@@ -115,8 +117,8 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=16384)
     ap.add_argument("--d-in", type=int, default=2048)
     ap.add_argument("--d-out", type=int, default=8192)
-    ap.add_argument("--parts", choices=["all", "quantize", "linear"], default="all",
-                    help="run only the quantize-only parts or only the layer parts of a step (for profiles in "
+    ap.add_argument("--parts", choices=["all", "value", "quantize", "linear"], default="all",
+                    help="run only the two launches behind `value`, only the quantize-only parts or only the layer parts of a step (for profiles in "
                          "which every launch of a kernel has the same tensor size); the JSON line then reports "
                          "the skipped parts as null timings")
     ap.add_argument("--paper-shapes", action="store_true",
@@ -183,16 +185,17 @@ def main() -> int:
              "posthoc_rows", "posthoc_cols", "linear_fwd", "linear_bwd", "linear_fwd_46", "linear_bwd_ph"]
     kernel_ms = {k: [] for k in names}
 
+    do_v = args.parts in ("all", "value", "quantize")     # the two single-pass launches behind `value`
     do_q, do_l = args.parts in ("all", "quantize"), args.parts in ("all", "linear")
 
     def step(i: int, record: bool):
         e = [ev() for _ in range(len(names) + 1)]
         a, b, c, d = (i * 4) % n_rot, (i * 4 + 1) % n_rot, (i * 4 + 2) % n_rot, (i * 4 + 3) % n_rot
         e[0].record()
-        if do_q:
+        if do_v:
             qii.qii_quantize_nvfp4(xs[a], False, qii.MS_EDEN, 128, 0, i, amax_rows[a], out_rows, None)
         e[1].record()
-        if do_q:
+        if do_v:
             qii.qii_quantize_nvfp4(xs[b], True, qii.MS_EDEN, 128, 0, i, amax_cols[b], out_cols, None)
         e[2].record()
         if do_q:
@@ -330,6 +333,20 @@ def main() -> int:
             "traffic": {"bytes": TRAFFIC_QUANT_ROWS_BYTES, "algorithmic_bytes": int(n * BYTES_PER_ELEM_QUANT),
                         "valid_for": "8192x8192 bf16"} if (R, C) == (8192, 8192) else None,
         },
+        # the same launch against the vector-ALU peak: what the arithmetic contract asks per element
+        # (7 butterfly add/sub, scaling fma 2, abs/max 1, quotient 1, FP4 rounding 1, two EDEN fma 4,
+        # per-group divisions and roundings ~0.5) over the fp32 vector peak (256 CUs x 4 SIMDs x 32
+        # lanes x 2 flops of a fused multiply-add x 2.4 GHz = 157.3 TFLOP/s)
+        "roofline_alu": {
+            "kernel": "quantize_rows_kernel<bf16, MS_EDEN, RHT>", "bound": "alu",
+            "achieved": round(n * ALU_FLOPS_PER_ELEM / (avg["single_rows"] * 1e-3) / 1e12, 2),
+            "peak": VALU_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(n * ALU_FLOPS_PER_ELEM / (avg["single_rows"] * 1e-3) / 1e12 / VALU_F32_PEAK_TFLOPS, 4),
+            "flops_per_element": ALU_FLOPS_PER_ELEM,
+            "note": "mostly single adds in binary32 (1 flop per lane-instruction against the 2 of an fma; several "
+                    "conversion and cross-lane instructions issue at half or quarter rate); "
+                    "measured VALU issue occupancy 75-78 % (profiles/bench_sq_counters.txt)",
+        },
         "roofline_gemm": {
             "kernel": f"gemm_kernel_v4<bf16 out> M={T} N={d_out} K={d_in} (incl. the scale re-tiling launch)",
             "bound": "mfma", "achieved": round(gemm_tflops, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -339,17 +356,19 @@ def main() -> int:
 
     if args.parts != "all":   # partial runs are for profiles: no figures for what did not run
         result["config"]["parts"] = args.parts
-        if not do_q:
+        if not do_v:
             result["value"] = None
-            result["quantize"] = None
             result["roofline"] = None
+            result["roofline_alu"] = None
+        if not do_q:
+            result["quantize"] = None
         if not do_l:
             result["linear_fwd_bwd"] = None
             result["roofline_gemm"] = None
     if args.paper_shapes:
         result["paper_shapes"] = paper_shapes(torch, qii, synth, dev)
 
-    if not args.no_cpu_baseline and do_q:
+    if not args.no_cpu_baseline and do_v:
         import oracle
         oracle.build()
         reps = 0
