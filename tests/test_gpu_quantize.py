@@ -182,3 +182,21 @@ def test_full_size_config_matches_oracle(oracle):
         out = run_quantize(x, qii.MS_EDEN, transpose, 128, 0, 0)
         ref = oracle.quantize(x, qii.MS_EDEN, transpose=transpose, seed_rht=0, seed_sr=0)
         assert_nv_equal(out, ref, f"8192^2 transpose {transpose}")
+
+
+@pytest.mark.parametrize("mode", [qii.MS_EDEN, qii.MS_EDEN_PH, qii.RTN_46])
+@pytest.mark.parametrize("transpose", [False, True])
+def test_leading_dimension_larger_than_the_row(oracle, mode, transpose):
+    """A sub-matrix of a wider buffer (leading dimension 640, 384 columns used): the kernels address
+    rows by the leading dimension and must not touch the columns beyond the sub-matrix."""
+    full = make("t3_bf16", (256, 640), seed=23)
+    sub = np.ascontiguousarray(full[:, 128:512])
+    xfull = to_dev(full)
+    x = xfull[:, 128:512]                      # a view: stride(0) = 640
+    assert x.stride(0) == 640 and not x.is_contiguous()
+    R, C = (384, 256) if transpose else (256, 384)
+    out = qii.NVFP4Tensor.empty(R, C)
+    qii.qii_quantize_nvfp4(x, transpose, mode, 128, 31, 32, None, out,
+                           ws(qii.qii_quantize_posthoc_workspace_bytes(R, C)))
+    ref = oracle.quantize(sub, mode, transpose=transpose, rht_group=128, seed_rht=31, seed_sr=32)
+    assert_nv_equal(out, ref, f"strided input, mode {mode}, transpose {transpose}")
