@@ -105,7 +105,8 @@ qii_status qii_absmax(const void *x, qii_dtype dt, int64_t rows, int64_t cols, i
                       int transpose, int rht_group, uint64_t seed_rht, float *amax, void *stream);
 
 /* Q(x) or Q(x^T) -> NVFP4 (Sec. 3.1 equations for QII_SR, Sec. 3.3 equations and
- * Algorithm 1 for QII_MS_EDEN, Table 1 "RTN 1x16" for QII_RTN).
+ * Algorithm 1 for QII_MS_EDEN, Table 1 "RTN 1x16" for QII_RTN, Sec. 4.1 for QII_RTN_46,
+ * Sec. 7 "Post Hoc Range Alignment" for QII_MS_EDEN_PH).
  *   x          rows x cols, leading dimension ld >= cols (elements); with transpose == 0
  *              every row must start 16-byte aligned.
  *   transpose  0: quantize x, groups along cols;  out is rows x cols.
@@ -118,7 +119,12 @@ qii_status qii_absmax(const void *x, qii_dtype dt, int64_t rows, int64_t cols, i
  *   amax_in    nullable.  Non-null: device float holding max|.| of the rotated tensor,
  *              supplied by the caller (App. D assumes this); the tensor is then read
  *              once.  Null: the library measures it first (a second read of x) and
- *              needs 256 bytes of workspace.
+ *              needs 256 bytes of workspace.  With QII_MS_EDEN_PH the tensor is read
+ *              once either way (the maximum is reduced during the heavy pass unless
+ *              supplied) and ws must hold qii_quantize_posthoc_workspace_bytes(out.rows,
+ *              out.cols) bytes, 256-byte aligned.
+ *   errors     QII_INVALID_ARG / QII_BAD_SHAPE / QII_WORKSPACE_TOO_SMALL before anything
+ *              is launched; the outputs are then untouched.
  *   out        caller-allocated; out.rows/out.cols must equal the shape stated above. */
 qii_status qii_quantize_nvfp4(const void *x, qii_dtype dt, int64_t rows, int64_t cols, int64_t ld,
                               int transpose, qii_mode mode, int rht_group, uint64_t seed_rht,
