@@ -86,3 +86,31 @@ def test_bad_arguments_are_rejected_without_a_device(libqii):
     # empty tensors are accepted and do nothing
     out = _NVFP4(None, None, None, 0, 128)
     assert L.qii_quantize_nvfp4(None, 1, 0, 128, 128, 0, 2, 128, 0, 0, 0x2000, ctypes.byref(out), None, 0, None) == 0
+
+
+def test_new_modes_and_layer_variants_reject_bad_arguments(libqii):
+    L = libqii.lib()
+    from paper_2601_22813_amd.binding import _NVFP4
+    out = _NVFP4(0x1000, 0x1000, 0x1000, 4, 128)
+    # post hoc scheme: needs its per-group buffer even when the abs-max is supplied
+    assert L.qii_quantize_nvfp4(0x1000, 1, 4, 128, 128, 0, 4, 128, 0, 0, 0x2000, ctypes.byref(out), None, 0, None) == 4
+    assert L.qii_quantize_nvfp4(0x1000, 1, 4, 128, 128, 0, 4, 128, 0, 0, 0x2000, ctypes.byref(out), 0x4000, 256, None) == 4
+    assert libqii.qii_quantize_posthoc_workspace_bytes(4, 128) == 256 + 256      # one slot + 32 floats, padded
+    assert libqii.qii_quantize_posthoc_workspace_bytes(8192, 8192) == 256 + 8192 * 512 * 4
+    # the layer variants only take the modes that make sense for their pass
+    xq = _NVFP4(0x1000, 0x1000, 0x1000, 256, 128)
+    wq = _NVFP4(0x1000, 0x1000, 0x1000, 384, 128)
+    big = 1 << 30
+    assert L.qii_linear_fwd_mode(0x1000, 0x1000, 1, 256, 128, 384, 2, 0x1000, 1, ctypes.byref(xq), ctypes.byref(wq), 0x1000, big, None) == 1
+    assert L.qii_linear_bwd_mode(0x1000, 1, ctypes.byref(xq), ctypes.byref(wq), 0, 1, 0x1000, 0x1000, 1, 0x1000, big, None) == 1
+    assert L.qii_linear_bwd_mode(0x1000, 1, ctypes.byref(xq), ctypes.byref(wq), 0, 4, 0x1000, 0x1000, 1, 0x1000, 16, None) == 4
+    plain = libqii.qii_linear_bwd_mode_workspace_bytes(256, 128, 384, 2)
+    assert plain == libqii.qii_linear_bwd_workspace_bytes(256, 128, 384)
+    assert libqii.qii_linear_bwd_mode_workspace_bytes(256, 128, 384, 4) == plain + 256 * 384 // 16 * 4
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr
