@@ -161,11 +161,14 @@ qii_status qii_linear_fwd(const void *X, const void *W, qii_dtype dt, int64_t T,
 
 /* The same forward pass with the rounding scheme of X and W chosen by the caller:
  * QII_RTN (as qii_linear_fwd) or QII_RTN_46, the forward pass of Sec. 5 with the 4/6
- * choice of Sec. 4.1.  Other modes are rejected (the forward pass is deterministic).   */
+ * choice of Sec. 4.1.  Other modes are rejected (the forward pass is deterministic).
+ * amax_x, amax_w (each nullable): device floats holding max|X| and max|W|, for callers
+ * that have them from the producing kernel (App. D assumes so); the matching abs-max
+ * pass is then skipped.                                                                */
 qii_status qii_linear_fwd_mode(const void *X, const void *W, qii_dtype dt, int64_t T, int64_t d_in,
-                               int64_t d_out, qii_mode mode, void *Y, qii_dtype y_dt,
-                               const qii_nvfp4 *Xq_saved, const qii_nvfp4 *Wq_saved, void *ws,
-                               size_t ws_bytes, void *stream);
+                               int64_t d_out, qii_mode mode, const float *amax_x, const float *amax_w,
+                               void *Y, qii_dtype y_dt, const qii_nvfp4 *Xq_saved,
+                               const qii_nvfp4 *Wq_saved, void *ws, size_t ws_bytes, void *stream);
 
 /* Backward pass of one linear layer (Sec. 5): with six sub-seeds derived from `seed`
  * (0: rotation of the dX GEMM, 1: rotation of the dW GEMM, 2..5: rounding seeds of

@@ -58,7 +58,7 @@ def lib() -> ctypes.CDLL:
         L.qii_dequantize_nvfp4.argtypes = [nv, vp, vp]
         L.qii_gemm_nvfp4.argtypes = [nv, nv, vp, c.c_int, i64, vp, sz, vp]
         L.qii_linear_fwd.argtypes = [vp, vp, c.c_int, i64, i64, i64, vp, c.c_int, nv, nv, vp, sz, vp]
-        L.qii_linear_fwd_mode.argtypes = [vp, vp, c.c_int, i64, i64, i64, c.c_int, vp, c.c_int, nv, nv, vp, sz, vp]
+        L.qii_linear_fwd_mode.argtypes = [vp, vp, c.c_int, i64, i64, i64, c.c_int, vp, vp, vp, c.c_int, nv, nv, vp, sz, vp]
         L.qii_linear_bwd.argtypes = [vp, c.c_int, nv, nv, u64, vp, vp, c.c_int, vp, sz, vp]
         L.qii_linear_bwd_mode.argtypes = [vp, c.c_int, nv, nv, u64, c.c_int, vp, vp, c.c_int, vp, sz, vp]
         L.qii_linear_bwd_mode.restype = c.c_int
@@ -216,13 +216,14 @@ def qii_linear_fwd(X: torch.Tensor, W: torch.Tensor, Y: torch.Tensor, Xq: NVFP4T
 
 
 def qii_linear_fwd_mode(X: torch.Tensor, W: torch.Tensor, mode: int, Y: torch.Tensor, Xq: NVFP4Tensor,
-                        Wq: NVFP4Tensor, ws: torch.Tensor):
+                        Wq: NVFP4Tensor, ws: torch.Tensor, amax_x: torch.Tensor | None = None,
+                        amax_w: torch.Tensor | None = None):
     T, d_in = X.shape
     d_out = W.shape[0]
     sx, sw = Xq.c_struct(), Wq.c_struct()
-    _check(lib().qii_linear_fwd_mode(X.data_ptr(), W.data_ptr(), _dt(X), T, d_in, d_out, mode, Y.data_ptr(),
-                                     _dt(Y), ctypes.byref(sx), ctypes.byref(sw), ws.data_ptr(),
-                                     ws.numel() * ws.element_size(), _stream()))
+    _check(lib().qii_linear_fwd_mode(X.data_ptr(), W.data_ptr(), _dt(X), T, d_in, d_out, mode, _ptr(amax_x),
+                                     _ptr(amax_w), Y.data_ptr(), _dt(Y), ctypes.byref(sx), ctypes.byref(sw),
+                                     ws.data_ptr(), ws.numel() * ws.element_size(), _stream()))
 
 
 def qii_linear_bwd(dY: torch.Tensor, Xq: NVFP4Tensor, Wq: NVFP4Tensor, seed: int, dX: torch.Tensor,

@@ -170,13 +170,14 @@ qii_status carve_quantize_ws(qii_mode mode, const float *amax_in, int64_t R, int
 // slots are cleared by one launch for the whole pass)
 qii_status quantize_dense(const void *x, qii_dtype dt, int64_t rows, int64_t cols, int64_t ld, int transpose,
                           qii_mode mode, int rht_group, uint64_t seed_rht, uint64_t seed_sr,
-                          const qii_nvfp4 *out, float *slot, float *tbuf, hipStream_t s, bool slot_zeroed)
+                          const float *amax_in, const qii_nvfp4 *out, float *slot, float *tbuf, hipStream_t s,
+                          bool slot_zeroed)
 {
     qii::Source src;
     int64_t R, C;
     qii_status st = dense_source(x, dt, rows, cols, ld, transpose, rht_group, &src, &R, &C);
     if (st != QII_OK) return st;
-    return quantize_source(src, R, C, mode, rht_group, seed_rht, seed_sr, nullptr, out, slot, tbuf, s, slot_zeroed);
+    return quantize_source(src, R, C, mode, rht_group, seed_rht, seed_sr, amax_in, out, slot, tbuf, s, slot_zeroed);
 }
 
 qii_status requantize_saved(const qii_nvfp4 *in, int transpose, qii_mode mode, int rht_group, uint64_t seed_rht,
@@ -367,7 +368,8 @@ qii_status qii_gemm_nvfp4(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_d
 }
 
 qii_status qii_linear_fwd_mode(const void *X, const void *W, qii_dtype dt, int64_t T, int64_t d_in,
-                               int64_t d_out, qii_mode mode, void *Y, qii_dtype y_dt, const qii_nvfp4 *Xq,
+                               int64_t d_out, qii_mode mode, const float *amax_x, const float *amax_w,
+                               void *Y, qii_dtype y_dt, const qii_nvfp4 *Xq,
                                const qii_nvfp4 *Wq, void *ws, size_t ws_bytes, void *stream)
 {
     if (mode != QII_RTN && mode != QII_RTN_46)
@@ -380,13 +382,13 @@ qii_status qii_linear_fwd_mode(const void *X, const void *W, qii_dtype dt, int64
     hipStream_t s = (hipStream_t)stream;
     float *slots = reinterpret_cast<float *>(p);
     const int slot_words = (int)(kSlot / 4);
-    if (T * d_in > 0 || d_out * d_in > 0) {
+    if ((!amax_x || !amax_w) && (T * d_in > 0 || d_out * d_in > 0)) {
         hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(slots), 0u, 2, slot_words, s);
         if (e != hipSuccess) return hip_fail(e, "fill");
     }
-    qii_status st = quantize_dense(X, dt, T, d_in, d_in, 0, mode, 0, 0, 0, Xq, slots, nullptr, s, true);
+    qii_status st = quantize_dense(X, dt, T, d_in, d_in, 0, mode, 0, 0, 0, amax_x, Xq, slots, nullptr, s, true);
     if (st != QII_OK) return st;
-    st = quantize_dense(W, dt, d_out, d_in, d_in, 0, mode, 0, 0, 0, Wq, slots + slot_words, nullptr, s, true);
+    st = quantize_dense(W, dt, d_out, d_in, d_in, 0, mode, 0, 0, 0, amax_w, Wq, slots + slot_words, nullptr, s, true);
     if (st != QII_OK) return st;
     return qii_gemm_nvfp4(Xq, Wq, Y, y_dt, d_out, p + 2 * kSlot, ws_bytes - 2 * kSlot, stream);
 }
@@ -395,7 +397,7 @@ qii_status qii_linear_fwd(const void *X, const void *W, qii_dtype dt, int64_t T,
                           int64_t d_out, void *Y, qii_dtype y_dt, const qii_nvfp4 *Xq,
                           const qii_nvfp4 *Wq, void *ws, size_t ws_bytes, void *stream)
 {
-    return qii_linear_fwd_mode(X, W, dt, T, d_in, d_out, QII_RTN, Y, y_dt, Xq, Wq, ws, ws_bytes, stream);
+    return qii_linear_fwd_mode(X, W, dt, T, d_in, d_out, QII_RTN, nullptr, nullptr, Y, y_dt, Xq, Wq, ws, ws_bytes, stream);
 }
 
 qii_status qii_linear_bwd_mode(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq, const qii_nvfp4 *Wq,
@@ -434,14 +436,14 @@ qii_status qii_linear_bwd_mode(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq
     hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(slots), 0u, 4, slot_words, s);
     if (e != hipSuccess) return hip_fail(e, "fill");
     // dX = Q(E) Q(W^T)^T : rotation sd[0] on the inner dimension d_out
-    st = quantize_dense(dY, dt, T, d_out, d_out, 0, mode, 128, sd[0], sd[2], &Eq, slots, tbuf, s, true);
+    st = quantize_dense(dY, dt, T, d_out, d_out, 0, mode, 128, sd[0], sd[2], nullptr, &Eq, slots, tbuf, s, true);
     if (st != QII_OK) return st;
     st = requantize_saved(Wq, 1, mode, 128, sd[0], sd[3], &WTq, slots + slot_words, tbuf, s, true);
     if (st != QII_OK) return st;
     st = qii_gemm_nvfp4(&Eq, &WTq, dX, g_dt, d_in, gws, gws_bytes, stream);
     if (st != QII_OK) return st;
     // dW = Q(E^T) Q(X^T)^T : rotation sd[1] on the inner dimension T
-    st = quantize_dense(dY, dt, T, d_out, d_out, 1, mode, 128, sd[1], sd[4], &ETq, slots + 2 * slot_words, tbuf, s, true);
+    st = quantize_dense(dY, dt, T, d_out, d_out, 1, mode, 128, sd[1], sd[4], nullptr, &ETq, slots + 2 * slot_words, tbuf, s, true);
     if (st != QII_OK) return st;
     st = requantize_saved(Xq, 1, mode, 128, sd[1], sd[5], &XTq, slots + 3 * slot_words, tbuf, s, true);
     if (st != QII_OK) return st;

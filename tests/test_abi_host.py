@@ -101,7 +101,7 @@ def test_new_modes_and_layer_variants_reject_bad_arguments(libqii):
     xq = _NVFP4(0x1000, 0x1000, 0x1000, 256, 128)
     wq = _NVFP4(0x1000, 0x1000, 0x1000, 384, 128)
     big = 1 << 30
-    assert L.qii_linear_fwd_mode(0x1000, 0x1000, 1, 256, 128, 384, 2, 0x1000, 1, ctypes.byref(xq), ctypes.byref(wq), 0x1000, big, None) == 1
+    assert L.qii_linear_fwd_mode(0x1000, 0x1000, 1, 256, 128, 384, 2, None, None, 0x1000, 1, ctypes.byref(xq), ctypes.byref(wq), 0x1000, big, None) == 1
     assert L.qii_linear_bwd_mode(0x1000, 1, ctypes.byref(xq), ctypes.byref(wq), 0, 1, 0x1000, 0x1000, 1, 0x1000, big, None) == 1
     assert L.qii_linear_bwd_mode(0x1000, 1, ctypes.byref(xq), ctypes.byref(wq), 0, 4, 0x1000, 0x1000, 1, 0x1000, 16, None) == 4
     plain = libqii.qii_linear_bwd_mode_workspace_bytes(256, 128, 384, 2)

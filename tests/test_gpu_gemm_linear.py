@@ -160,6 +160,15 @@ def test_linear_forward_with_four_over_six(oracle):
     check(Y.cpu().numpy().astype(np.float64), ref, absum, False)
     with pytest.raises(qii.QiiError):
         qii.qii_linear_fwd_mode(X, W, qii.MS_EDEN, Y, Xq, Wq, w)
+    # with the two maxima supplied by the caller the result is the same
+    ax = torch.zeros(1, dtype=torch.float32, device="cuda"); aw = torch.zeros(1, dtype=torch.float32, device="cuda")
+    qii.qii_absmax(X, False, 0, 0, ax); qii.qii_absmax(W, False, 0, 0, aw)
+    Xq2, Wq2 = qii.NVFP4Tensor.empty(T, d_in), qii.NVFP4Tensor.empty(d_out, d_in)
+    Y2 = torch.empty_like(Y)
+    qii.qii_linear_fwd_mode(X, W, qii.RTN_46, Y2, Xq2, Wq2, w, amax_x=ax, amax_w=aw)
+    assert_nv_equal(Xq2, oXq, "saved X (4/6, supplied maximum)")
+    assert_nv_equal(Wq2, oWq, "saved W (4/6, supplied maximum)")
+    assert torch.equal(Y2, Y)
 
 
 def test_layer_passes_replay_from_a_hip_graph(oracle):
