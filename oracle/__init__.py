@@ -199,7 +199,7 @@ def rht(x: np.ndarray, transpose: bool = False, rht_group: int = 128, seed_rht: 
 def quantize(x: np.ndarray, mode: int, transpose: bool = False, rht_group: int = 128,
              seed_rht: int = 0, seed_sr: int = 0, amax: float | None = None,
              s_override: float = 0.0) -> NVFP4:
-    """Q(x) (or Q(x^T)) with mode RTN | SR | MS_EDEN; output lives in rotated space."""
+    """Q(x) (or Q(x^T)) with mode RTN | SR | MS_EDEN | RTN_46 | MS_EDEN_PH; output lives in rotated space."""
     x = np.ascontiguousarray(x)
     rows, cols = x.shape
     R, C = (cols, rows) if transpose else (rows, cols)

@@ -508,7 +508,8 @@ static void quantize_rotated(const float *y, int64_t R, int64_t C, int mode, flo
         }
 }
 
-/* Q(x) or Q(x^T): mode RTN | SR | MS_EDEN.  Output is in rotated space:    */
+/* Q(x) or Q(x^T): mode RTN | SR | MS_EDEN | RTN_46 | MS_EDEN_PH.  Output is */
+/* in rotated space:                                                        */
 /* codes R*C/2 bytes (element 2j in the low nibble), scales R*C/16 bytes    */
 /* row-major, one f32 tensor scale.  amax_in (nullable) replaces the        */
 /* measured max of the rotated tensor.                                      */
