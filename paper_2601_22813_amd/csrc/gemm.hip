@@ -9,7 +9,12 @@
 // v_mfma_f32_32x32x16_f16; every product and the f32 accumulation are those of the
 // dequantized operands.  The two tensor scales are applied once in the epilogue.
 //
-// Tiling: 256 x 256 block tile, K tile 128, 4 waves (2 x 2) each owning 128 x 128 =
+// Three kernels share this scheme (launch_gemm picks one): gemm_kernel_v4, the main one
+// (K a multiple of 256, scale bytes re-tiled into a workspace, LDS-direct loads, explicit
+// software pipeline); gemm_kernel_v2 (K a multiple of 128, no workspace); gemm_kernel (any
+// K that is a multiple of 32, ragged everything).
+//
+// Tiling: 256 x 256 block tile, K tile 128 or 256, 4 waves (2 x 2) each owning 128 x 128 =
 // 4 x 4 MFMA tiles (256 accumulator registers).  One 32x32x16 MFMA consumes exactly
 // one scale group per lane: lanes 0..31 supply k 0..31 of a 64-element K slice and
 // lanes 32..63 supply k 32..63, four MFMAs walk the four dwords of a lane's 16 bytes
