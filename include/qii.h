@@ -144,17 +144,20 @@ qii_status qii_dequantize_nvfp4(const qii_nvfp4 *in, float *y, void *stream);
 /* Block-scaled GEMM of Sec. 5:  C = A_hat * B_hat^T  with A (M x K) and B (N x K) both
  * K-contiguous NVFP4, products accumulated in f32.  C is M x N, leading dimension ldc,
  * dtype QII_F32 or QII_BF16 (rounded to nearest even from the f32 accumulator).
- * K = A.cols = B.cols must be a multiple of 32.  ws (nullable): qii_gemm_workspace_bytes
- * bytes, 16-byte aligned; with it (and K a multiple of 256) the fast kernel runs, which first
- * copies the scale bytes into a tile-contiguous layout; without it a slower kernel is used.
- * Results are identical either way.                                                     */
+ * K = A.cols = B.cols is any multiple of 16 (NVFP4's own rule).  ws (nullable):
+ * qii_gemm_workspace_bytes bytes, 16-byte aligned; with it (and K a multiple of 256) the fast
+ * kernel runs, which first copies the scale bytes into a tile-contiguous layout; without it a
+ * slower kernel is used.  Either way every product is formed exactly and accumulated in f32.
+ * errors: QII_INVALID_ARG / QII_BAD_SHAPE before anything is launched; C is then untouched. */
 qii_status qii_gemm_nvfp4(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_dtype c_dt,
                           int64_t ldc, void *ws, size_t ws_bytes, void *stream);
 
 /* Forward pass of one linear layer (Sec. 5): Xq = RTN(X) and Wq = RTN(W) with 1x16
  * scales along d_in and no rotation, Y = Xq * Wq^T.  X is T x d_in, W is d_out x d_in,
  * Y is T x d_out (contiguous, dtype y_dt).  Xq_saved (T x d_in) and Wq_saved
- * (d_out x d_in) are caller-allocated and are the state kept for the backward pass.   */
+ * (d_out x d_in) are caller-allocated and are the state kept for the backward pass.
+ * d_in must be a multiple of 16.  All arguments of the pass (inputs, outputs, descriptors,
+ * workspace) are checked before the first launch; on an error nothing has been written.  */
 qii_status qii_linear_fwd(const void *X, const void *W, qii_dtype dt, int64_t T, int64_t d_in,
                           int64_t d_out, void *Y, qii_dtype y_dt, const qii_nvfp4 *Xq_saved,
                           const qii_nvfp4 *Wq_saved, void *ws, size_t ws_bytes, void *stream);
@@ -175,8 +178,9 @@ qii_status qii_linear_fwd_mode(const void *X, const void *W, qii_dtype dt, int64
  * Q(E), Q(W^T), Q(E^T), Q(X^T)), all quantizers MS-EDEN:
  *   dX = Q(E) * Q(W^T)^T   (T x d_in,    inner dimension d_out)
  *   dW = Q(E^T) * Q(X^T)^T (d_out x d_in, inner dimension T)
- * dY is T x d_out (dtype dt).  T and d_out must be multiples of 128.
- * dX, dW contiguous, dtype g_dt.                                                       */
+ * dY is T x d_out (dtype dt).  T and d_out must be multiples of 128 and non-zero.
+ * dX, dW contiguous, dtype g_dt.  All arguments of the pass are checked before the first
+ * launch; on an error nothing has been written.                                        */
 qii_status qii_linear_bwd(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq_saved,
                           const qii_nvfp4 *Wq_saved, uint64_t seed, void *dX, void *dW,
                           qii_dtype g_dt, void *ws, size_t ws_bytes, void *stream);

@@ -110,6 +110,19 @@ def _ptr(t):
     return None if t is None else t.data_ptr()
 
 
+def _contig(*tensors):
+    """The layer passes and GEMM outputs take dense row-major buffers: refuse a view whose rows
+    are not contiguous instead of reading it with the wrong stride."""
+    for t in tensors:
+        if not t.is_contiguous():
+            raise QiiError("this call takes contiguous tensors (got strides %s)" % (tuple(t.stride()),))
+
+
+def _rows_contig(t):
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise QiiError("this call takes a 2-D tensor with unit column stride (got strides %s)" % (tuple(t.stride()),))
+
+
 @dataclass
 class NVFP4Tensor:
     """Device buffers of one NVFP4 tensor (caller-owned, see qii_nvfp4 in include/qii.h)."""
@@ -159,12 +172,15 @@ def qii_linear_bwd_workspace_bytes(T: int, d_in: int, d_out: int) -> int:
 
 
 def qii_rht(x: torch.Tensor, transpose: bool, seed_rht: int, y: torch.Tensor, amax: torch.Tensor | None):
+    _rows_contig(x)
+    _contig(y)
     rows, cols = x.shape
     _check(lib().qii_rht(x.data_ptr(), _dt(x), rows, cols, x.stride(0), int(transpose), seed_rht,
                          y.data_ptr(), _ptr(amax), _stream()))
 
 
 def qii_absmax(x: torch.Tensor, transpose: bool, rht_group: int, seed_rht: int, amax: torch.Tensor):
+    _rows_contig(x)
     rows, cols = x.shape
     _check(lib().qii_absmax(x.data_ptr(), _dt(x), rows, cols, x.stride(0), int(transpose), rht_group,
                             seed_rht, amax.data_ptr(), _stream()))
@@ -173,6 +189,7 @@ def qii_absmax(x: torch.Tensor, transpose: bool, rht_group: int, seed_rht: int, 
 def qii_quantize_nvfp4(x: torch.Tensor, transpose: bool, mode: int, rht_group: int, seed_rht: int,
                        seed_sr: int, amax_in: torch.Tensor | None, out: NVFP4Tensor,
                        ws: torch.Tensor | None):
+    _rows_contig(x)
     rows, cols = x.shape
     s = out.c_struct()
     _check(lib().qii_quantize_nvfp4(x.data_ptr(), _dt(x), rows, cols, x.stride(0), int(transpose), mode,
@@ -200,6 +217,7 @@ def qii_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
 
 
 def qii_gemm_nvfp4(A: NVFP4Tensor, B: NVFP4Tensor, C: torch.Tensor, ws: torch.Tensor | None = None):
+    _rows_contig(C)
     sa, sb = A.c_struct(), B.c_struct()
     _check(lib().qii_gemm_nvfp4(ctypes.byref(sa), ctypes.byref(sb), C.data_ptr(), _dt(C), C.stride(0),
                                 _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(), _stream()))
@@ -207,6 +225,7 @@ def qii_gemm_nvfp4(A: NVFP4Tensor, B: NVFP4Tensor, C: torch.Tensor, ws: torch.Te
 
 def qii_linear_fwd(X: torch.Tensor, W: torch.Tensor, Y: torch.Tensor, Xq: NVFP4Tensor,
                    Wq: NVFP4Tensor, ws: torch.Tensor):
+    _contig(X, W, Y)
     T, d_in = X.shape
     d_out = W.shape[0]
     sx, sw = Xq.c_struct(), Wq.c_struct()
@@ -218,6 +237,7 @@ def qii_linear_fwd(X: torch.Tensor, W: torch.Tensor, Y: torch.Tensor, Xq: NVFP4T
 def qii_linear_fwd_mode(X: torch.Tensor, W: torch.Tensor, mode: int, Y: torch.Tensor, Xq: NVFP4Tensor,
                         Wq: NVFP4Tensor, ws: torch.Tensor, amax_x: torch.Tensor | None = None,
                         amax_w: torch.Tensor | None = None):
+    _contig(X, W, Y)
     T, d_in = X.shape
     d_out = W.shape[0]
     sx, sw = Xq.c_struct(), Wq.c_struct()
@@ -228,6 +248,9 @@ def qii_linear_fwd_mode(X: torch.Tensor, W: torch.Tensor, mode: int, Y: torch.Te
 
 def qii_linear_bwd(dY: torch.Tensor, Xq: NVFP4Tensor, Wq: NVFP4Tensor, seed: int, dX: torch.Tensor,
                    dW: torch.Tensor, ws: torch.Tensor):
+    _contig(dY, dX, dW)
+    if dW.dtype != dX.dtype:
+        raise QiiError("dX and dW must have the same dtype")
     sx, sw = Xq.c_struct(), Wq.c_struct()
     _check(lib().qii_linear_bwd(dY.data_ptr(), _dt(dY), ctypes.byref(sx), ctypes.byref(sw), seed,
                                 dX.data_ptr(), dW.data_ptr(), _dt(dX), ws.data_ptr(),
@@ -236,6 +259,9 @@ def qii_linear_bwd(dY: torch.Tensor, Xq: NVFP4Tensor, Wq: NVFP4Tensor, seed: int
 
 def qii_linear_bwd_mode(dY: torch.Tensor, Xq: NVFP4Tensor, Wq: NVFP4Tensor, seed: int, mode: int,
                         dX: torch.Tensor, dW: torch.Tensor, ws: torch.Tensor):
+    _contig(dY, dX, dW)
+    if dW.dtype != dX.dtype:
+        raise QiiError("dX and dW must have the same dtype")
     sx, sw = Xq.c_struct(), Wq.c_struct()
     _check(lib().qii_linear_bwd_mode(dY.data_ptr(), _dt(dY), ctypes.byref(sx), ctypes.byref(sw), seed, mode,
                                      dX.data_ptr(), dW.data_ptr(), _dt(dX), ws.data_ptr(),

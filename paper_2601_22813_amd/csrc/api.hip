@@ -217,6 +217,23 @@ qii_nvfp4 carve_nvfp4(uint8_t *&p, int64_t rows, int64_t cols)
     return t;
 }
 
+// every argument rule of the GEMM, checked before anything is launched
+qii_status check_gemm_args(const qii_nvfp4 *A, const qii_nvfp4 *B, const void *C, qii_dtype c_dt, int64_t ldc)
+{
+    qii_status st = check_nvfp4(A, "A");
+    if (st != QII_OK) return st;
+    st = check_nvfp4(B, "B");
+    if (st != QII_OK) return st;
+    if (A->cols != B->cols) return fail(QII_BAD_SHAPE, "inner dimensions differ: %lld vs %lld", (long long)A->cols, (long long)B->cols);
+    if (c_dt != QII_F32 && c_dt != QII_BF16) return fail(QII_INVALID_ARG, "bad output dtype");
+    if (ldc < B->rows) return fail(QII_BAD_SHAPE, "ldc %lld < N %lld", (long long)ldc, (long long)B->rows);
+    if (A->rows * B->rows == 0) return QII_OK;
+    if (!C) return fail(QII_INVALID_ARG, "null C");
+    if (!aligned(C, c_dt == QII_BF16 ? 2 : 4)) return fail(QII_INVALID_ARG, "misaligned C");
+    if (A->cols == 0) return fail(QII_BAD_SHAPE, "K = 0");
+    return QII_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -351,17 +368,9 @@ qii_status qii_dequantize_nvfp4(const qii_nvfp4 *in, float *y, void *stream)
 qii_status qii_gemm_nvfp4(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_dtype c_dt,
                           int64_t ldc, void *ws, size_t ws_bytes, void *stream)
 {
-    qii_status st = check_nvfp4(A, "A");
+    const qii_status st = check_gemm_args(A, B, C, c_dt, ldc);
     if (st != QII_OK) return st;
-    st = check_nvfp4(B, "B");
-    if (st != QII_OK) return st;
-    if (A->cols != B->cols) return fail(QII_BAD_SHAPE, "inner dimensions differ: %lld vs %lld", (long long)A->cols, (long long)B->cols);
-    if (A->cols % 32 != 0) return fail(QII_BAD_SHAPE, "K = %lld must be a multiple of 32", (long long)A->cols);
-    if (c_dt != QII_F32 && c_dt != QII_BF16) return fail(QII_INVALID_ARG, "bad output dtype");
-    if (ldc < B->rows) return fail(QII_BAD_SHAPE, "ldc %lld < N %lld", (long long)ldc, (long long)B->rows);
     if (A->rows * B->rows == 0) return QII_OK;
-    if (!C) return fail(QII_INVALID_ARG, "null C");
-    if (A->cols == 0) return fail(QII_BAD_SHAPE, "K = 0");
     hipError_t e = qii::launch_gemm(*A, *B, C, c_dt == QII_BF16, ldc, ws, ws_bytes, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, "gemm");
     return QII_OK;
@@ -372,9 +381,25 @@ qii_status qii_linear_fwd_mode(const void *X, const void *W, qii_dtype dt, int64
                                void *Y, qii_dtype y_dt, const qii_nvfp4 *Xq,
                                const qii_nvfp4 *Wq, void *ws, size_t ws_bytes, void *stream)
 {
+    // every argument of the whole pass is checked before the first launch
     if (mode != QII_RTN && mode != QII_RTN_46)
         return fail(QII_INVALID_ARG, "the forward pass takes QII_RTN or QII_RTN_46, not mode %d", (int)mode);
-    if (d_in % 32 != 0) return fail(QII_BAD_SHAPE, "d_in must be a multiple of 32");
+    if (T < 0 || d_in < 0 || d_out < 0) return fail(QII_BAD_SHAPE, "negative dimension");
+    qii::Source sx, sw;
+    int64_t R, C;
+    qii_status st = dense_source(X, dt, T, d_in, d_in, 0, 0, &sx, &R, &C);
+    if (st != QII_OK) return st;
+    st = dense_source(W, dt, d_out, d_in, d_in, 0, 0, &sw, &R, &C);
+    if (st != QII_OK) return st;
+    st = check_nvfp4(Xq, "Xq_saved");
+    if (st != QII_OK) return st;
+    st = check_nvfp4(Wq, "Wq_saved");
+    if (st != QII_OK) return st;
+    if (Xq->rows != T || Xq->cols != d_in || Wq->rows != d_out || Wq->cols != d_in)
+        return fail(QII_BAD_SHAPE, "Xq_saved must be %lld x %lld and Wq_saved %lld x %lld", (long long)T,
+                    (long long)d_in, (long long)d_out, (long long)d_in);
+    st = check_gemm_args(Xq, Wq, Y, y_dt, d_out);
+    if (st != QII_OK) return st;
     if (!ws || ws_bytes < qii_linear_fwd_workspace_bytes(T, d_in, d_out) || !aligned(ws, kSlot))
         return fail(QII_WORKSPACE_TOO_SMALL, "linear_fwd needs %zu bytes of 256-byte aligned workspace",
                     qii_linear_fwd_workspace_bytes(T, d_in, d_out));
@@ -386,9 +411,9 @@ qii_status qii_linear_fwd_mode(const void *X, const void *W, qii_dtype dt, int64
         hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(slots), 0u, 2, slot_words, s);
         if (e != hipSuccess) return hip_fail(e, "fill");
     }
-    qii_status st = quantize_dense(X, dt, T, d_in, d_in, 0, mode, 0, 0, 0, amax_x, Xq, slots, nullptr, s, true);
+    st = quantize_source(sx, T, d_in, mode, 0, 0, 0, amax_x, Xq, slots, nullptr, s, true);
     if (st != QII_OK) return st;
-    st = quantize_dense(W, dt, d_out, d_in, d_in, 0, mode, 0, 0, 0, amax_w, Wq, slots + slot_words, nullptr, s, true);
+    st = quantize_source(sw, d_out, d_in, mode, 0, 0, 0, amax_w, Wq, slots + slot_words, nullptr, s, true);
     if (st != QII_OK) return st;
     return qii_gemm_nvfp4(Xq, Wq, Y, y_dt, d_out, p + 2 * kSlot, ws_bytes - 2 * kSlot, stream);
 }
@@ -413,6 +438,17 @@ qii_status qii_linear_bwd_mode(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq
     const int64_t T = Xq->rows, d_in = Xq->cols, d_out = Wq->rows;
     if (Wq->cols != d_in) return fail(QII_BAD_SHAPE, "Xq is %lld x %lld but Wq is %lld x %lld", (long long)T, (long long)d_in, (long long)d_out, (long long)Wq->cols);
     if (T % 128 != 0 || d_out % 128 != 0) return fail(QII_BAD_SHAPE, "T and d_out must be multiples of 128");
+    // every argument of the whole pass is checked before the first launch
+    qii::Source se, set;
+    int64_t R, C;
+    st = dense_source(dY, dt, T, d_out, d_out, 0, 128, &se, &R, &C);
+    if (st != QII_OK) return st;
+    st = dense_source(dY, dt, T, d_out, d_out, 1, 128, &set, &R, &C);
+    if (st != QII_OK) return st;
+    if (g_dt != QII_F32 && g_dt != QII_BF16) return fail(QII_INVALID_ARG, "bad gradient dtype");
+    if (T * d_in > 0 && (!dX || !aligned(dX, g_dt == QII_BF16 ? 2 : 4))) return fail(QII_INVALID_ARG, "dX is null or misaligned");
+    if (d_out * d_in > 0 && (!dW || !aligned(dW, g_dt == QII_BF16 ? 2 : 4))) return fail(QII_INVALID_ARG, "dW is null or misaligned");
+    if (T * d_out == 0) return fail(QII_BAD_SHAPE, "the backward pass needs a non-empty inner dimension (T and d_out)");
     const size_t need = qii_linear_bwd_mode_workspace_bytes(T, d_in, d_out, mode);
     if (!ws || ws_bytes < need || !aligned(ws, kSlot))
         return fail(QII_WORKSPACE_TOO_SMALL, "linear_bwd needs %zu bytes of 256-byte aligned workspace", need);

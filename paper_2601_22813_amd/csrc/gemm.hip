@@ -12,7 +12,7 @@
 // Three kernels share this scheme (launch_gemm picks one): gemm_kernel_v4, the main one
 // (K a multiple of 256, scale bytes re-tiled into a workspace, LDS-direct loads, explicit
 // software pipeline); gemm_kernel_v2 (K a multiple of 128, no workspace); gemm_kernel (any
-// K that is a multiple of 32, ragged everything).
+// K that is a multiple of 16, NVFP4's own rule; ragged everything).
 //
 // Tiling: 256 x 256 block tile, K tile 128 or 256, 4 waves (2 x 2) each owning 128 x 128 =
 // 4 x 4 MFMA tiles (256 accumulator registers).  One 32x32x16 MFMA consumes exactly
@@ -51,14 +51,13 @@ struct Staged {
     uint2 as, bs;
 };
 
-template <bool kAlignedK>
+// scale bytes of one row for the K tile at k0 (8 groups); groups beyond K read as 0
 __device__ __forceinline__ uint2 load_scales(const uint8_t *scales, int64_t row, int64_t nrows,
                                              int64_t K, int64_t k0)
 {
     uint2 r = make_uint2(0u, 0u);
     if (row >= nrows) return r;
     const uint8_t *p = scales + row * (K / 16) + k0 / 16;
-    if (kAlignedK) return *reinterpret_cast<const uint2 *>(p);
     uint32_t w[2] = {0u, 0u};
 #pragma unroll
     for (int i = 0; i < 8; ++i)
@@ -66,7 +65,9 @@ __device__ __forceinline__ uint2 load_scales(const uint8_t *scales, int64_t row,
     return make_uint2(w[0], w[1]);
 }
 
-template <bool kAlignedK>
+// A 16-byte piece of a code row holds two scale groups.  K is any multiple of 16 here: when it is
+// an odd multiple the last piece of a row is half valid and rows are only 8-byte aligned, so the
+// tile is moved in 8-byte halves; everything beyond M, N or K is zero (code 0, scale 0).
 __device__ __forceinline__ void load_tile(Staged &st, const uint8_t *a_codes, const uint8_t *a_scales,
                                           const uint8_t *b_codes, const uint8_t *b_scales, int64_t M,
                                           int64_t N, int64_t K, int64_t m0, int64_t n0, int64_t k0)
@@ -74,17 +75,21 @@ __device__ __forceinline__ void load_tile(Staged &st, const uint8_t *a_codes, co
     const int t = threadIdx.x;
     const int seg = t & 3, r = t >> 2;
     const int64_t kbyte = k0 / 2 + 16 * seg;
-    const bool k_ok = kAlignedK || (k0 + 32 * seg < K);
+    const bool lo_ok = k0 + 32 * seg < K, hi_ok = k0 + 32 * seg + 16 < K;
+    const uint2 z = make_uint2(0u, 0u);
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         const int64_t ra = m0 + p * 64 + r, rb = n0 + p * 64 + r;
-        st.a[p] = (k_ok && ra < M) ? *reinterpret_cast<const uint4 *>(a_codes + ra * (K / 2) + kbyte)
-                                   : make_uint4(0u, 0u, 0u, 0u);
-        st.b[p] = (k_ok && rb < N) ? *reinterpret_cast<const uint4 *>(b_codes + rb * (K / 2) + kbyte)
-                                   : make_uint4(0u, 0u, 0u, 0u);
+        const uint8_t *pa = a_codes + ra * (K / 2) + kbyte, *pb = b_codes + rb * (K / 2) + kbyte;
+        const uint2 al = (lo_ok && ra < M) ? *reinterpret_cast<const uint2 *>(pa) : z;
+        const uint2 ah = (hi_ok && ra < M) ? *reinterpret_cast<const uint2 *>(pa + 8) : z;
+        const uint2 bl = (lo_ok && rb < N) ? *reinterpret_cast<const uint2 *>(pb) : z;
+        const uint2 bh = (hi_ok && rb < N) ? *reinterpret_cast<const uint2 *>(pb + 8) : z;
+        st.a[p] = make_uint4(al.x, al.y, ah.x, ah.y);
+        st.b[p] = make_uint4(bl.x, bl.y, bh.x, bh.y);
     }
-    st.as = load_scales<kAlignedK>(a_scales, m0 + t, M, K, k0);
-    st.bs = load_scales<kAlignedK>(b_scales, n0 + t, N, K, k0);
+    st.as = load_scales(a_scales, m0 + t, M, K, k0);
+    st.bs = load_scales(b_scales, n0 + t, N, K, k0);
 }
 
 __device__ __forceinline__ void store_tile(const Staged &st, const StagePtr &sp)
@@ -122,7 +127,7 @@ __device__ __forceinline__ uint32_t scale_pair(uint32_t two_bytes, int which)
     return (b << 7) | (b << 23);
 }
 
-template <bool kAlignedK, bool kBf16Out>
+template <bool kBf16Out>
 __global__ __launch_bounds__(256, 1) void gemm_kernel(const uint8_t *__restrict__ a_codes,
                                                       const uint8_t *__restrict__ a_scales,
                                                       const float *__restrict__ a_ts,
@@ -149,14 +154,14 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const uint8_t *__restrict_
 
     const int64_t ktiles = (K + BK - 1) / BK;
     Staged st;
-    load_tile<kAlignedK>(st, a_codes, a_scales, b_codes, b_scales, M, N, K, m0, n0, 0);
+    load_tile(st, a_codes, a_scales, b_codes, b_scales, M, N, K, m0, n0, 0);
     store_tile(st, stage_ptr(smem, 0));
     __syncthreads();
 
     for (int64_t kt = 0; kt < ktiles; ++kt) {
         const StagePtr sp = stage_ptr(smem, (int)(kt & 1));
         if (kt + 1 < ktiles)
-            load_tile<kAlignedK>(st, a_codes, a_scales, b_codes, b_scales, M, N, K, m0, n0, (kt + 1) * BK);
+            load_tile(st, a_codes, a_scales, b_codes, b_scales, M, N, K, m0, n0, (kt + 1) * BK);
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             uint4 ra[4], rb[4];
@@ -432,7 +437,10 @@ constexpr int kOff4A = 0, kOff4B = 32768, kOff4As = 65536, kOff4Bs = 69632, kSta
 constexpr int kSmem4 = 2 * kStage4Bytes;   // 144 KiB
 
 // scales[rows][K/16] -> tiled[(rt * (K/256) + ks) * 256 + r][16], one 16-byte piece per thread;
-// both operands in one launch (threads [0, na) take A, [na, na + nb) take B)
+// both operands in one launch (threads [0, na) take A, [na, na + nb) take B).  Rows of the last
+// row tile beyond M (or N) are not written and keep whatever the workspace held: they only ever
+// scale operand rows beyond the matrix, whose products land in accumulator rows / columns that
+// the epilogue never stores (matrix-instruction rows are independent of one another).
 __global__ void retile_scales_kernel(const uint8_t *__restrict__ a_scales, uint8_t *__restrict__ a_tiled,
                                      int64_t M, const uint8_t *__restrict__ b_scales,
                                      uint8_t *__restrict__ b_tiled, int64_t N, int64_t K)
@@ -682,6 +690,22 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
     return (size_t)((mp + np) * (K / 16));
 }
 
+// The kernels need more dynamic LDS than the default limit; the attribute is set once per kernel
+// and device, not per launch (a launch may sit inside a stream capture).
+template <class Kern>
+hipError_t allow_dynamic_lds(Kern kern, int bytes)
+{
+    constexpr int kMaxDevices = 64;
+    static bool done[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < kMaxDevices && done[dev]) return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && dev >= 0 && dev < kMaxDevices) done[dev] = true;
+    return e;
+}
+
 hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is_bf16, int64_t ldc,
                        void *ws, size_t ws_bytes, hipStream_t s)
 {
@@ -699,47 +723,47 @@ hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is
                            a_tiled, M, B.scales, b_tiled, N, K);
         hipError_t e;
         if (c_is_bf16) {
-            e = hipFuncSetAttribute((const void *)gemm_kernel_v4<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kSmem4);
+            e = allow_dynamic_lds(gemm_kernel_v4<true>, kSmem4);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(gemm_kernel_v4<true>, grid, block, kSmem4, s, A.codes, a_tiled, A.tensor_scale,
                                B.codes, b_tiled, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n);
         } else {
-            e = hipFuncSetAttribute((const void *)gemm_kernel_v4<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kSmem4);
+            e = allow_dynamic_lds(gemm_kernel_v4<false>, kSmem4);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(gemm_kernel_v4<false>, grid, block, kSmem4, s, A.codes, a_tiled, A.tensor_scale,
                                B.codes, b_tiled, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n);
         }
         return hipGetLastError();
     }
-    const size_t smem = 2 * kStageBytes;
-    const bool aligned = (K % 128) == 0;
-    if (aligned) {
-        const size_t smem2 = kSmem2;
+    if ((K % 128) == 0) {
         hipError_t e;
         if (c_is_bf16) {
-            e = hipFuncSetAttribute((const void *)gemm_kernel_v2<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem2);
+            e = allow_dynamic_lds(gemm_kernel_v2<true>, kSmem2);
             if (e != hipSuccess) return e;
-            hipLaunchKernelGGL(gemm_kernel_v2<true>, grid, block, smem2, s, A.codes, A.scales, A.tensor_scale,
+            hipLaunchKernelGGL(gemm_kernel_v2<true>, grid, block, kSmem2, s, A.codes, A.scales, A.tensor_scale,
                                B.codes, B.scales, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n);
         } else {
-            e = hipFuncSetAttribute((const void *)gemm_kernel_v2<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem2);
+            e = allow_dynamic_lds(gemm_kernel_v2<false>, kSmem2);
             if (e != hipSuccess) return e;
-            hipLaunchKernelGGL(gemm_kernel_v2<false>, grid, block, smem2, s, A.codes, A.scales, A.tensor_scale,
+            hipLaunchKernelGGL(gemm_kernel_v2<false>, grid, block, kSmem2, s, A.codes, A.scales, A.tensor_scale,
                                B.codes, B.scales, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n);
         }
         return hipGetLastError();
     }
-#define QII_GEMM(AL, BF)                                                                          \
-    do {                                                                                          \
-        auto kern = gemm_kernel<AL, BF>;                                                          \
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
-        if (e != hipSuccess) return e;                                                            \
-        hipLaunchKernelGGL(kern, grid, block, smem, s, A.codes, A.scales, A.tensor_scale, B.codes, \
-                           B.scales, B.tensor_scale, M, N, K, C, ldc, (int)tiles_n);              \
-    } while (0)
-    if (aligned) { if (c_is_bf16) QII_GEMM(true, true); else QII_GEMM(true, false); }
-    else { if (c_is_bf16) QII_GEMM(false, true); else QII_GEMM(false, false); }
-#undef QII_GEMM
+    // any K that is a multiple of 16: the ragged kernel (8-byte pieces, predicated tails)
+    constexpr int smem = 2 * kStageBytes;
+    hipError_t e;
+    if (c_is_bf16) {
+        e = allow_dynamic_lds(gemm_kernel<true>, smem);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(gemm_kernel<true>, grid, block, smem, s, A.codes, A.scales, A.tensor_scale, B.codes,
+                           B.scales, B.tensor_scale, M, N, K, C, ldc, (int)tiles_n);
+    } else {
+        e = allow_dynamic_lds(gemm_kernel<false>, smem);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(gemm_kernel<false>, grid, block, smem, s, A.codes, A.scales, A.tensor_scale, B.codes,
+                           B.scales, B.tensor_scale, M, N, K, C, ldc, (int)tiles_n);
+    }
     return hipGetLastError();
 }
 

@@ -72,13 +72,19 @@ def test_bad_arguments_are_rejected_without_a_device(libqii):
     assert L.qii_quantize_nvfp4(0x1000, 1, 4, 128, 128, 1, 0, 0, 0, 0, 0x2000, ctypes.byref(out), None, 0, None) == 2
     # no amax and no workspace
     assert L.qii_quantize_nvfp4(0x1000, 1, 4, 128, 128, 0, 2, 128, 0, 0, None, ctypes.byref(out), None, 0, None) == 4
-    # GEMM: inner dimensions differ / K not a multiple of 32
+    # GEMM: inner dimensions differ / K not a multiple of 16 / ldc < N / bad dtype / null or misaligned C
     a = _NVFP4(0x1000, 0x1000, 0x1000, 8, 64)
     b = _NVFP4(0x1000, 0x1000, 0x1000, 8, 128)
     assert L.qii_gemm_nvfp4(ctypes.byref(a), ctypes.byref(b), 0x3000, 0, 8, None, 0, None) == 2
+    a = _NVFP4(0x1000, 0x1000, 0x1000, 8, 40)
+    b = _NVFP4(0x1000, 0x1000, 0x1000, 8, 40)
+    assert L.qii_gemm_nvfp4(ctypes.byref(a), ctypes.byref(b), 0x3000, 0, 8, None, 0, None) == 2
     a = _NVFP4(0x1000, 0x1000, 0x1000, 8, 48)
     b = _NVFP4(0x1000, 0x1000, 0x1000, 8, 48)
-    assert L.qii_gemm_nvfp4(ctypes.byref(a), ctypes.byref(b), 0x3000, 0, 8, None, 0, None) == 2
+    assert L.qii_gemm_nvfp4(ctypes.byref(a), ctypes.byref(b), 0x3000, 0, 7, None, 0, None) == 2
+    assert L.qii_gemm_nvfp4(ctypes.byref(a), ctypes.byref(b), 0x3000, 7, 8, None, 0, None) == 1
+    assert L.qii_gemm_nvfp4(ctypes.byref(a), ctypes.byref(b), None, 0, 8, None, 0, None) == 1
+    assert L.qii_gemm_nvfp4(ctypes.byref(a), ctypes.byref(b), 0x3002, 0, 8, None, 0, None) == 1
     # linear_bwd: workspace too small
     xq = _NVFP4(0x1000, 0x1000, 0x1000, 256, 128)
     wq = _NVFP4(0x1000, 0x1000, 0x1000, 384, 128)
@@ -107,6 +113,53 @@ def test_new_modes_and_layer_variants_reject_bad_arguments(libqii):
     plain = libqii.qii_linear_bwd_mode_workspace_bytes(256, 128, 384, 2)
     assert plain == libqii.qii_linear_bwd_workspace_bytes(256, 128, 384)
     assert libqii.qii_linear_bwd_mode_workspace_bytes(256, 128, 384, 4) == plain + 256 * 384 // 16 * 4
+
+
+def test_layer_passes_validate_everything_before_the_first_launch(libqii):
+    """No device is present here, so any launch would come back as QII_HIP_ERROR (5): getting the
+    argument status instead shows that the whole pass is checked before anything is enqueued."""
+    L = libqii.lib()
+    from paper_2601_22813_amd.binding import _NVFP4
+    T, d_in, d_out = 256, 128, 384
+    xq = _NVFP4(0x10000, 0x20000, 0x30000, T, d_in)
+    wq = _NVFP4(0x40000, 0x50000, 0x60000, d_out, d_in)
+    big = 1 << 30
+    fwd = lambda X=0x1000, W=0x2000, dt=1, Y=0x3000, ydt=1, xq_=xq, wq_=wq, ws=0x100000, wsb=big: L.qii_linear_fwd_mode(
+        X, W, dt, T, d_in, d_out, 0, None, None, Y, ydt, ctypes.byref(xq_), ctypes.byref(wq_), ws, wsb, None)
+    assert fwd(Y=None) == 1 and b"null C" in L.qii_last_error()
+    assert fwd(ydt=9) == 1
+    assert fwd(X=None) == 1
+    assert fwd(W=None) == 1
+    assert fwd(dt=9) == 1
+    assert fwd(xq_=_NVFP4(0x10000, 0x20000, 0x30000, T, d_in + 16)) == 2
+    assert fwd(wq_=_NVFP4(0x40000, 0x50000, None, d_out, d_in)) == 1
+    assert fwd(wsb=16) == 4
+    assert fwd(ws=0x100010) == 4
+    bwd = lambda dY=0x1000, dt=1, dX=0x3000, dW=0x5000, gdt=1, xq_=xq, wq_=wq, ws=0x100000, wsb=big, mode=2: L.qii_linear_bwd_mode(
+        dY, dt, ctypes.byref(xq_), ctypes.byref(wq_), 0, mode, dX, dW, gdt, ws, wsb, None)
+    assert bwd(dY=None) == 1
+    assert bwd(dt=3) == 1
+    assert bwd(dX=None) == 1
+    assert bwd(dW=None) == 1 and b"dW" in L.qii_last_error()
+    assert bwd(gdt=5) == 1
+    assert bwd(dX=0x3001) == 1
+    assert bwd(wq_=_NVFP4(0x40000, 0x50000, 0x60000, d_out, d_in + 16)) == 2
+    assert bwd(xq_=_NVFP4(0x10000, 0x20000, 0x30000, T + 64, d_in)) == 2      # T not a multiple of 128
+    assert bwd(wsb=16) == 4
+    assert bwd(mode=4, wsb=libqii.qii_linear_bwd_mode_workspace_bytes(T, d_in, d_out, 4) - 1) == 4
+
+
+def test_binding_refuses_strided_layer_tensors(libqii):
+    import torch
+    X = torch.zeros((8, 64), dtype=torch.bfloat16)[:, :32]      # row stride 64, 32 columns used
+    W = torch.zeros((16, 32), dtype=torch.bfloat16)
+    Y = torch.zeros((8, 16), dtype=torch.bfloat16)
+    xq, wq = libqii.NVFP4Tensor.empty(8, 32, device="cpu"), libqii.NVFP4Tensor.empty(16, 32, device="cpu")
+    with pytest.raises(libqii.QiiError, match="contiguous"):
+        libqii.qii_linear_fwd(X, W, Y, xq, wq, torch.zeros(4096, dtype=torch.uint8))
+    dX, dW = torch.zeros((8, 32), dtype=torch.bfloat16), torch.zeros((16, 32), dtype=torch.float32)
+    with pytest.raises(libqii.QiiError, match="same dtype"):
+        libqii.qii_linear_bwd(Y, xq, wq, 0, dX, dW, torch.zeros(4096, dtype=torch.uint8))
 
 
 def test_bench_refuses_more_than_one_gpu():
