@@ -202,6 +202,19 @@ size_t qii_linear_fwd_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out);
 size_t qii_linear_bwd_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out);
 size_t qii_linear_bwd_mode_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out, qii_mode mode);
 
+/* Device self-test (a maintenance aid, not an operation of the paper).  The tuned kernels
+ * realise the rounding rules of Sec. 3.1 / Sec. 3.3 with gfx950 conversion instructions and
+ * take their divisions as short Newton sequences; this call sweeps them against the rules
+ * they stand for and writes the number of disagreeing inputs into counts[0..7] (device):
+ *   0 FP4 encode (round to nearest even, saturating, sign kept): every finite binary32
+ *   1 E4M3 encode on [0, 448]: every binary32 in the interval
+ *   2 FP4 decode: every byte, all four byte positions
+ *   3 the GEMM's FP4 x E4M3 -> f16 dequantization: 16 codes x 127 scale bytes, exact products
+ *   4 division by a tensor constant, 5 general short division: 2^30 pseudo-random pairs each
+ *   6 E4M3 decode: every byte     7 reciprocals over 81 binades: every binary32 there
+ * All eight must read 0.  Takes a few hundred milliseconds.                              */
+qii_status qii_selftest_conversions(uint64_t *counts, void *stream);
+
 /* Host helpers.                                                                        */
 uint64_t qii_derive_seed(uint64_t seed, uint32_t i); /* backward sub-seed i (0..5)      */
 const char *qii_status_string(qii_status s);

@@ -24,7 +24,7 @@ EXPORTS = [
     "qii_gemm_nvfp4", "qii_linear_fwd", "qii_linear_fwd_mode", "qii_linear_bwd", "qii_linear_bwd_mode",
     "qii_quantize_workspace_bytes", "qii_quantize_posthoc_workspace_bytes", "qii_linear_bwd_mode_workspace_bytes",
     "qii_gemm_workspace_bytes", "qii_linear_fwd_workspace_bytes", "qii_linear_bwd_workspace_bytes",
-    "qii_derive_seed", "qii_status_string", "qii_last_error", "qii_version",
+    "qii_derive_seed", "qii_status_string", "qii_last_error", "qii_version", "qii_selftest_conversions",
 ]
 
 
@@ -76,6 +76,8 @@ def lib() -> ctypes.CDLL:
                      "qii_linear_bwd_workspace_bytes"):
             getattr(L, name).argtypes = [i64, i64, i64]
             getattr(L, name).restype = sz
+        L.qii_selftest_conversions.argtypes = [vp, vp]
+        L.qii_selftest_conversions.restype = c.c_int
         L.qii_derive_seed.argtypes = [u64, c.c_uint32]
         L.qii_derive_seed.restype = u64
         L.qii_status_string.argtypes = [c.c_int]
@@ -169,6 +171,11 @@ def qii_linear_bwd_mode_workspace_bytes(T: int, d_in: int, d_out: int, mode: int
 
 def qii_linear_bwd_workspace_bytes(T: int, d_in: int, d_out: int) -> int:
     return int(lib().qii_linear_bwd_workspace_bytes(T, d_in, d_out))
+
+
+def qii_selftest_conversions(counts: torch.Tensor):
+    """counts: 8 x int64 on the device; receives the mismatch counts (see include/qii.h)."""
+    _check(lib().qii_selftest_conversions(counts.data_ptr(), _stream()))
 
 
 def qii_rht(x: torch.Tensor, transpose: bool, seed_rht: int, y: torch.Tensor, amax: torch.Tensor | None):

@@ -486,6 +486,14 @@ qii_status qii_linear_bwd_mode(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq
     return qii_gemm_nvfp4(&ETq, &XTq, dW, g_dt, d_in, gws, gws_bytes, stream);
 }
 
+qii_status qii_selftest_conversions(uint64_t *counts, void *stream)
+{
+    if (!counts || !aligned(counts, 8)) return fail(QII_INVALID_ARG, "counts must be 8 device uint64, 8-byte aligned");
+    hipError_t e = qii::launch_selftest_conversions(reinterpret_cast<unsigned long long *>(counts), (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, "selftest");
+    return QII_OK;
+}
+
 qii_status qii_linear_bwd(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq, const qii_nvfp4 *Wq,
                           uint64_t seed, void *dX, void *dW, qii_dtype g_dt, void *ws,
                           size_t ws_bytes, void *stream)

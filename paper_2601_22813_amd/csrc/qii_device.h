@@ -76,7 +76,7 @@ __device__ __forceinline__ uint32_t e4m3_rtn(float r)
 // with its floor is the same test because R is an integer.
 __device__ __forceinline__ uint32_t e4m3_sr(float t, uint32_t r20)
 {
-    if (t < 0x1p-6f) return ((uint32_t)(t * 0x1p29f) + r20) >> 20;
+    if (!(t >= 0x1p-6f)) return ((uint32_t)(t * 0x1p29f) + r20) >> 20;   // (a NaN gives byte 0)
     const uint32_t b = ((f2u(t) + r20) >> 20) - 960u;
     return b > 0x7Eu ? 0x7Eu : b;
 }

@@ -68,4 +68,8 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is_bf16, int64_t ldc,
                        void *ws, size_t ws_bytes, hipStream_t s);
 
+// sweeps of the hardware conversions and short division sequences against their value-space
+// rules; counts[0..7] (device) receive the numbers of mismatches (selftest.hip)
+hipError_t launch_selftest_conversions(unsigned long long *counts, hipStream_t s);
+
 }  // namespace qii

@@ -112,13 +112,16 @@ __device__ __forceinline__ float group_inv(uint32_t b, const TensorConsts &tc, c
     return div_ieee(1.0f, e4m3_decode(b) * tc.x32, tc);
 }
 
-// e4m3_sr with the rare range below 2^-6 behind a wave-uniform branch
+// e4m3_sr with the rare range below 2^-6 behind a wave-uniform branch.  A NaN (0/0 when both
+// dot products of a group underflow, far outside the value range of real tensors) takes the small
+// branch and gives byte 0, as "not greater than zero" does in the value-space rule.
 __device__ __forceinline__ uint32_t e4m3_sr_wave(float t, uint32_t r20)
 {
     const uint32_t bn = ((f2u(t) + r20) >> 20) - 960u;
     const uint32_t b = bn > 0x7Eu ? 0x7Eu : bn;
-    if (__builtin_amdgcn_ballot_w64(t < 0x1p-6f) == 0ull) return b;
-    return t < 0x1p-6f ? ((uint32_t)(t * 0x1p29f) + r20) >> 20 : b;
+    const bool small = !(t >= 0x1p-6f);
+    if (__builtin_amdgcn_ballot_w64(small) == 0ull) return b;
+    return small ? ((uint32_t)(t * 0x1p29f) + r20) >> 20 : b;
 }
 
 // One candidate of the 4/6 choice (Sec. 4.1): round the group to nearest with the scale byte

@@ -112,3 +112,52 @@ def test_paper_recipe_layer_at_benchmark_size(oracle):
     out = qii.NVFP4Tensor.empty(d_in, T)
     qii.qii_requantize_nvfp4(Xq, True, qii.MS_EDEN_PH, 128, s[1], s[5], None, out, w)
     assert_nv_equal(out, XTq, "Q(X^T) post hoc")
+
+
+# Larger workloads: the per-layer linears of the 1.9B decoder at T = 32768 tokens, the two
+# roofline-stress shapes, and the 7B rows of the paper's table of Llama-like layer shapes (App. D)
+# at 8 x 2048 tokens.  Shapes whose tile counts are not multiples of 8 (22016 / 256 = 86,
+# 11008 / 256 = 43, 28672 / 256 = 112) also reach the tile walk without the XCD re-mapping and its
+# remainder group.
+LARGE_SHAPES = [
+    ("decoder-1.9B down, T=32768", 32768, 8192, 2048, "paper"),
+    ("decoder-1.9B qkv, T=32768", 32768, 2048, 6144, "plain"),
+    ("stress 16384^3", 16384, 16384, 16384, "paper"),
+    ("stress 16384x8192->28672", 16384, 8192, 28672, "plain"),
+    ("7B UpGate", 16384, 4096, 22016, "paper"),
+    ("7B Down", 16384, 11008, 4096, "paper"),
+]
+
+
+@pytest.mark.parametrize("name,T,d_in,d_out,recipe", LARGE_SHAPES, ids=[s[0] for s in LARGE_SHAPES])
+def test_layer_sampled_parity_at_large_shapes(oracle, name, T, d_in, d_out, recipe):
+    """Saved forward tensors byte for byte; Y, dX and dW on 4096 sampled entries each, against the
+    oracle's exact definition on its own quantized operands.  recipe "plain": RTN forward and
+    Algorithm 1 backward; "paper": 4/6 forward and post hoc range alignment backward."""
+    rng = np.random.default_rng(T + d_in + d_out)
+    fwd_mode, bwd_mode = (qii.RTN_46, qii.MS_EDEN_PH) if recipe == "paper" else (qii.RTN, qii.MS_EDEN)
+    print(f"{name}: inputs", flush=True)
+    Xb, Wb, Eb = synth.linear_layer_bf16(T, d_in, d_out, seed=3)
+    X, W, E = to_dev(Xb), to_dev(Wb), to_dev(Eb)
+    Xq, Wq = qii.NVFP4Tensor.empty(T, d_in), qii.NVFP4Tensor.empty(d_out, d_in)
+    Y = torch.empty((T, d_out), dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty((T, d_in), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((d_out, d_in), dtype=torch.bfloat16, device="cuda")
+    seed = 99
+    print(f"{name}: forward + backward on the GPU", flush=True)
+    qii.qii_linear_fwd_mode(X, W, fwd_mode, Y, Xq, Wq, ws(qii.qii_linear_fwd_workspace_bytes(T, d_in, d_out)))
+    qii.qii_linear_bwd_mode(E, Xq, Wq, seed, bwd_mode, dX, dW,
+                            ws(qii.qii_linear_bwd_mode_workspace_bytes(T, d_in, d_out, bwd_mode)))
+    torch.cuda.synchronize()
+    print(f"{name}: oracle forward", flush=True)
+    oXq, oWq = oracle.linear_fwd(Xb, Wb, mode=fwd_mode)
+    assert_nv_equal(Xq, oXq, f"{name}: saved X")
+    assert_nv_equal(Wq, oWq, f"{name}: saved W")
+    ms, ns = sample_pairs(T, d_out, 4096, rng)
+    check_samples(Y, oXq, oWq, ms, ns, oracle, True, f"{name}: Y")
+    print(f"{name}: oracle backward operands", flush=True)
+    Eq, WTq, ETq, XTq = oracle.linear_bwd_operands(Eb, oXq, oWq, seed, mode=bwd_mode)
+    ms, ns = sample_pairs(T, d_in, 4096, rng)
+    check_samples(dX, Eq, WTq, ms, ns, oracle, True, f"{name}: dX")
+    ms, ns = sample_pairs(d_out, d_in, 4096, rng)
+    check_samples(dW, ETq, XTq, ms, ns, oracle, True, f"{name}: dW")
