@@ -131,6 +131,19 @@ qii_status qii_quantize_nvfp4(const void *x, qii_dtype dt, int64_t rows, int64_t
                               uint64_t seed_sr, const float *amax_in, const qii_nvfp4 *out,
                               void *ws, size_t ws_bytes, void *stream);
 
+/* qii_quantize_nvfp4 for callers that cannot allocate device memory or bring a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the abs-max
+ * scalar and, for QII_MS_EDEN_PH, the per-group f32 buffer live in a buffer of 16 MiB + 256 bytes
+ * that the library holds in each GPU's memory from load time to the end of the process.  The
+ * tensor's maximum is always measured by the call (there is no amax_in).  Arguments, outputs and
+ * errors as qii_quantize_nvfp4; in addition QII_UNSUPPORTED for QII_MS_EDEN_PH on a tensor of more
+ * than 4194304 scale groups (8192 x 8192 elements); the other modes take any size.  Allocates
+ * nothing.  All calls on one GPU share that GPU's buffer: calls that overlap in time on the same
+ * GPU (different streams or threads) race; calls ordered on one stream do not.                 */
+qii_status qii_quantize_nvfp4_noalloc(const void *x, qii_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                                      int transpose, qii_mode mode, int rht_group, uint64_t seed_rht,
+                                      uint64_t seed_sr, const qii_nvfp4 *out, void *stream);
+
 /* Backward-pass re-quantization of a saved forward tensor (Sec. 5, "Backward Pass"):
  * dequantize `in` ((code*scale)*tensor_scale in f32), optionally transpose, quantize
  * as above.  in and out must not overlap.                                             */

@@ -25,6 +25,7 @@ EXPORTS = [
     "qii_quantize_workspace_bytes", "qii_quantize_posthoc_workspace_bytes", "qii_linear_bwd_mode_workspace_bytes",
     "qii_gemm_workspace_bytes", "qii_linear_fwd_workspace_bytes", "qii_linear_bwd_workspace_bytes",
     "qii_derive_seed", "qii_status_string", "qii_last_error", "qii_version", "qii_selftest_conversions",
+    "qii_quantize_nvfp4_noalloc",
 ]
 
 
@@ -54,6 +55,8 @@ def lib() -> ctypes.CDLL:
         L.qii_absmax.argtypes = [vp, c.c_int, i64, i64, i64, c.c_int, c.c_int, u64, vp, vp]
         L.qii_quantize_nvfp4.argtypes = [vp, c.c_int, i64, i64, i64, c.c_int, c.c_int, c.c_int, u64,
                                          u64, vp, nv, vp, sz, vp]
+        L.qii_quantize_nvfp4_noalloc.argtypes = [vp, c.c_int, i64, i64, i64, c.c_int, c.c_int, c.c_int, u64, u64, nv, vp]
+        L.qii_quantize_nvfp4_noalloc.restype = c.c_int
         L.qii_requantize_nvfp4.argtypes = [nv, c.c_int, c.c_int, c.c_int, u64, u64, vp, nv, vp, sz, vp]
         L.qii_dequantize_nvfp4.argtypes = [nv, vp, vp]
         L.qii_gemm_nvfp4.argtypes = [nv, nv, vp, c.c_int, i64, vp, sz, vp]
@@ -203,6 +206,15 @@ def qii_quantize_nvfp4(x: torch.Tensor, transpose: bool, mode: int, rht_group: i
                                     rht_group, seed_rht, seed_sr, _ptr(amax_in), ctypes.byref(s),
                                     _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
                                     _stream()))
+
+
+def qii_quantize_nvfp4_noalloc(x: torch.Tensor, transpose: bool, mode: int, rht_group: int, seed_rht: int,
+                               seed_sr: int, out: NVFP4Tensor):
+    _rows_contig(x)
+    rows, cols = x.shape
+    s = out.c_struct()
+    _check(lib().qii_quantize_nvfp4_noalloc(x.data_ptr(), _dt(x), rows, cols, x.stride(0), int(transpose), mode,
+                                            rht_group, seed_rht, seed_sr, ctypes.byref(s), _stream()))
 
 
 def qii_requantize_nvfp4(inp: NVFP4Tensor, transpose: bool, mode: int, rht_group: int, seed_rht: int,

@@ -3,6 +3,8 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <mutex>
+
 #include "qii_device.h"
 #include "qii_internal.h"
 
@@ -217,6 +219,38 @@ qii_nvfp4 carve_nvfp4(uint8_t *&p, int64_t rows, int64_t cols)
     return t;
 }
 
+// ---- library-owned scratch for qii_quantize_nvfp4_noalloc ---------------------------------
+// One abs-max slot plus one f32 per scale group of the post hoc scheme, for tensors of up to
+// kScratchGroups groups.  Every GPU the library runs on holds its own copy of the array at its
+// own address for the life of the process; in host code the array's name is only a handle for
+// hipGetSymbolAddress, never a device address.
+constexpr int64_t kScratchGroups = (int64_t)1 << 22;                       // 8192 x 8192 elements
+constexpr size_t kScratchBytes = kSlot + (size_t)kScratchGroups * 4;       // 16 MiB + 256 B
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// device address of the current device's copy of `scratch` (looked up once per device)
+qii_status scratch_address(void **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(QII_UNSUPPORTED, "device index %d beyond %d", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (!p) return fail(QII_HIP_ERROR, "hipGetSymbolAddress(scratch) returned a null address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return QII_OK;
+}
+
 // every argument rule of the GEMM, checked before anything is launched
 qii_status check_gemm_args(const qii_nvfp4 *A, const qii_nvfp4 *B, const void *C, qii_dtype c_dt, int64_t ldc)
 {
@@ -335,6 +369,29 @@ qii_status qii_quantize_nvfp4(const void *x, qii_dtype dt, int64_t rows, int64_t
     st = carve_quantize_ws(mode, amax_in, R, C, ws, ws_bytes, &slot, &tbuf);
     if (st != QII_OK) return st;
     return quantize_source(src, R, C, mode, rht_group, seed_rht, seed_sr, amax_in, out, slot, tbuf,
+                           (hipStream_t)stream);
+}
+
+qii_status qii_quantize_nvfp4_noalloc(const void *x, qii_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                                      int transpose, qii_mode mode, int rht_group, uint64_t seed_rht,
+                                      uint64_t seed_sr, const qii_nvfp4 *out, void *stream)
+{
+    qii::Source src;
+    int64_t R, C;
+    qii_status st = dense_source(x, dt, rows, cols, ld, transpose, rht_group, &src, &R, &C);
+    if (st != QII_OK) return st;
+    if (mode == QII_MS_EDEN_PH && R * (C / 16) > kScratchGroups)
+        return fail(QII_UNSUPPORTED, "qii_quantize_nvfp4_noalloc: the post hoc scheme needs one f32 per scale group and "
+                    "the library's scratch holds %lld; this tensor has %lld (use qii_quantize_nvfp4 with a workspace)",
+                    (long long)kScratchGroups, (long long)(R * (C / 16)));
+    void *base = nullptr;
+    st = scratch_address(&base);
+    if (st != QII_OK) return st;
+    // the slot is cleared by quantize_source (a fill kernel); the per-group buffer is written in
+    // full by the heavy pass before the scales pass reads it
+    float *slot = reinterpret_cast<float *>(base);
+    float *tbuf = mode == QII_MS_EDEN_PH ? reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(base) + kSlot) : nullptr;
+    return quantize_source(src, R, C, mode, rht_group, seed_rht, seed_sr, nullptr, out, slot, tbuf,
                            (hipStream_t)stream);
 }
 
