@@ -133,7 +133,7 @@ qii_status qii_quantize_nvfp4(const void *x, qii_dtype dt, int64_t rows, int64_t
 
 /* qii_quantize_nvfp4 for callers that cannot allocate device memory or bring a workspace (code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the abs-max
- * scalar and, for QII_MS_EDEN_PH, the per-group f32 buffer live in a buffer of 16 MiB + 256 bytes
+ * scalar and, for QII_MS_EDEN_PH, the per-group f32 buffer live in a buffer of 16 MiB + 16 KiB
  * that the library holds in each GPU's memory from load time to the end of the process.  The
  * tensor's maximum is always measured by the call (there is no amax_in).  Arguments, outputs and
  * errors as qii_quantize_nvfp4; in addition QII_UNSUPPORTED for QII_MS_EDEN_PH on a tensor of more

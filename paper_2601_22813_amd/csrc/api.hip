@@ -7,6 +7,7 @@
 
 #include "qii_device.h"
 #include "qii_internal.h"
+#include "quantize_core.h"
 
 namespace {
 
@@ -27,6 +28,7 @@ qii_status hip_fail(hipError_t e, const char *what)
 }
 
 constexpr size_t kSlot = 256;  // bytes reserved per device scalar in a workspace
+constexpr size_t kRegion = qii::kAmaxRegionBytes;   // the spread running maximum of the post hoc scheme (16 KiB)
 size_t align_up(size_t v) { return (v + kSlot - 1) / kSlot * kSlot; }
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
@@ -110,8 +112,8 @@ qii_status quantize_source(const qii::Source &src, int64_t R, int64_t C, qii_mod
     if (mode == QII_MS_EDEN_PH) {
         // Sec. 7: heavy pass (codes, corrected pseudo-scales, running maximum), then scales only
         if (!tbuf) return fail(QII_WORKSPACE_TOO_SMALL, "the post hoc scheme needs qii_quantize_posthoc_workspace_bytes of workspace");
-        if (!amax_in && !slot_zeroed) {
-            hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(amax_slot), 0u, 1, 1, s);
+        if (!amax_in && !slot_zeroed) {   // the running maximum is spread over 64 words of its region
+            hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(amax_slot), 0u, (int)qii::kAmaxSpread, (int)qii::kAmaxStrideWords, s);
             if (e != hipSuccess) return hip_fail(e, "fill");
         }
         qii::QuantizeArgs a;
@@ -121,8 +123,8 @@ qii_status quantize_source(const qii::Source &src, int64_t R, int64_t C, qii_mod
         a.tbuf = tbuf; a.amax_accum = amax_in ? nullptr : reinterpret_cast<uint32_t *>(amax_slot);
         hipError_t e = qii::launch_quantize(a, s);
         if (e != hipSuccess) return hip_fail(e, "quantize (heavy pass)");
-        e = qii::launch_posthoc_scales(tbuf, amax_in ? amax_in : amax_slot, R, C, seed_sr, out->scales,
-                                       out->tensor_scale, s);
+        e = qii::launch_posthoc_scales(tbuf, amax_in ? amax_in : amax_slot, amax_in ? 1 : (int)qii::kAmaxSpread, R, C, seed_sr,
+                                       out->scales, out->tensor_scale, s);
         if (e != hipSuccess) return hip_fail(e, "quantize (scales pass)");
         return QII_OK;
     }
@@ -153,11 +155,11 @@ qii_status carve_quantize_ws(qii_mode mode, const float *amax_in, int64_t R, int
     *slot = nullptr;
     *tbuf = nullptr;
     if (mode == QII_MS_EDEN_PH) {
-        const size_t need = kSlot + align_up((size_t)(R * (C / 16)) * 4);
+        const size_t need = kRegion + align_up((size_t)(R * (C / 16)) * 4);
         if (!ws || ws_bytes < need || !aligned(ws, kSlot))
             return fail(QII_WORKSPACE_TOO_SMALL, "the post hoc scheme needs %zu bytes of 256-byte aligned workspace", need);
         *slot = reinterpret_cast<float *>(ws);
-        *tbuf = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + kSlot);
+        *tbuf = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + kRegion);
         return QII_OK;
     }
     if (!amax_in) {
@@ -201,7 +203,7 @@ size_t posthoc_region_bytes(int64_t T, int64_t d_in, int64_t d_out, qii_mode mod
     int64_t groups = T * d_out / 16;
     if (d_in * d_out / 16 > groups) groups = d_in * d_out / 16;
     if (d_in * T / 16 > groups) groups = d_in * T / 16;
-    return 4 * kSlot + align_up((size_t)groups * 4);
+    return 4 * kRegion + align_up((size_t)groups * 4);
 }
 
 size_t nvfp4_bytes(int64_t rows, int64_t cols)
@@ -225,7 +227,7 @@ qii_nvfp4 carve_nvfp4(uint8_t *&p, int64_t rows, int64_t cols)
 // own address for the life of the process; in host code the array's name is only a handle for
 // hipGetSymbolAddress, never a device address.
 constexpr int64_t kScratchGroups = (int64_t)1 << 22;                       // 8192 x 8192 elements
-constexpr size_t kScratchBytes = kSlot + (size_t)kScratchGroups * 4;       // 16 MiB + 256 B
+constexpr size_t kScratchBytes = kRegion + (size_t)kScratchGroups * 4;     // 16 MiB + 16 KiB
 static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 constexpr int kMaxDevices = 64;
@@ -299,7 +301,7 @@ size_t qii_quantize_workspace_bytes(void) { return kSlot; }
 
 size_t qii_quantize_posthoc_workspace_bytes(int64_t rows, int64_t cols)
 {
-    return kSlot + align_up((size_t)(rows * (cols / 16)) * 4);
+    return kRegion + align_up((size_t)(rows * (cols / 16)) * 4);
 }
 
 size_t qii_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) { return align_up(qii::gemm_workspace_bytes(M, N, K)); }
@@ -390,7 +392,7 @@ qii_status qii_quantize_nvfp4_noalloc(const void *x, qii_dtype dt, int64_t rows,
     // the slot is cleared by quantize_source (a fill kernel); the per-group buffer is written in
     // full by the heavy pass before the scales pass reads it
     float *slot = reinterpret_cast<float *>(base);
-    float *tbuf = mode == QII_MS_EDEN_PH ? reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(base) + kSlot) : nullptr;
+    float *tbuf = mode == QII_MS_EDEN_PH ? reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(base) + kRegion) : nullptr;
     return quantize_source(src, R, C, mode, rht_group, seed_rht, seed_sr, nullptr, out, slot, tbuf,
                            (hipStream_t)stream);
 }
@@ -515,8 +517,9 @@ qii_status qii_linear_bwd_mode(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq
     // quantizers one after the other on the stream
     hipStream_t s = (hipStream_t)stream;
     float *slots = reinterpret_cast<float *>(p);
-    const int slot_words = (int)(kSlot / 4);
-    float *tbuf = mode == QII_MS_EDEN_PH ? reinterpret_cast<float *>(p + 4 * kSlot) : nullptr;
+    const bool ph = mode == QII_MS_EDEN_PH;
+    const int slot_words = (int)((ph ? kRegion : kSlot) / 4);   // distance between the four tensors' abs-max areas
+    float *tbuf = ph ? reinterpret_cast<float *>(p + 4 * kRegion) : nullptr;
     p += posthoc_region_bytes(T, d_in, d_out, mode);
     qii_nvfp4 Eq = carve_nvfp4(p, T, d_out);
     qii_nvfp4 WTq = carve_nvfp4(p, d_in, d_out);
@@ -526,7 +529,10 @@ qii_status qii_linear_bwd_mode(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq
     const size_t gws_bytes = reinterpret_cast<uint8_t *>(ws) + ws_bytes - p;
     uint64_t sd[6];
     for (uint32_t i = 0; i < 6; ++i) sd[i] = qii_derive_seed(seed, i);
-    hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(slots), 0u, 4, slot_words, s);
+    // (the post hoc scheme spreads each running maximum over 64 words, 256 bytes apart: the four
+    // regions are contiguous, so one launch clears all 256 words)
+    hipError_t e = ph ? qii::launch_fill_u32(reinterpret_cast<uint32_t *>(slots), 0u, 4 * (int)qii::kAmaxSpread, (int)qii::kAmaxStrideWords, s)
+                      : qii::launch_fill_u32(reinterpret_cast<uint32_t *>(slots), 0u, 4, slot_words, s);
     if (e != hipSuccess) return hip_fail(e, "fill");
     // dX = Q(E) Q(W^T)^T : rotation sd[0] on the inner dimension d_out
     st = quantize_dense(dY, dt, T, d_out, d_out, 0, mode, 128, sd[0], sd[2], nullptr, &Eq, slots, tbuf, s, true);

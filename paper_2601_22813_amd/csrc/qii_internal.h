@@ -34,8 +34,8 @@ struct QuantizeArgs {
     uint8_t *scales;
     float *tensor_scale;
     // post hoc range alignment only (mode QII_MS_EDEN_PH): the heavy pass writes one f32 per
-    // group into tbuf instead of scale bytes and folds the group maxima into amax_accum
-    // (nullable: the caller supplies the maximum itself); launch_posthoc_scales finishes
+    // group into tbuf instead of scale bytes and folds the group maxima into the 64 words (256
+    // bytes apart, a region of 16 KiB) at amax_accum (nullable: the caller supplies the maximum itself); launch_posthoc_scales finishes
     float *tbuf;
     uint32_t *amax_accum;
 };
@@ -48,12 +48,14 @@ hipError_t launch_absmax(const Source &src, int64_t R, int64_t C, int rht, uint6
 hipError_t launch_rht(const Source &src, int64_t R, int64_t C, uint64_t seed_rht, float *y,
                       float *amax /* nullable, must hold 0 */, hipStream_t s);
 hipError_t launch_quantize(const QuantizeArgs &a, hipStream_t s);
-hipError_t launch_posthoc_scales(const float *tbuf, const float *amax, int64_t R, int64_t C,
+// amax: n_amax words, 256 bytes apart (1: a maximum supplied by the caller; 64: the spread running
+// maximum of the heavy pass, whose maximum is taken)
+hipError_t launch_posthoc_scales(const float *tbuf, const float *amax, int n_amax, int64_t R, int64_t C,
                                  uint64_t seed_sr, uint8_t *scales, float *tensor_scale, hipStream_t s);
 hipError_t launch_dequantize(const uint8_t *codes, const uint8_t *scales, const float *ts,
                              int64_t rows, int64_t cols, float *y, hipStream_t s);
 // tuned kernels for dense sources quantized along their rows (quantize_rows.hip)
-bool rows_kernels_apply(const Source &src);
+bool rows_kernels_apply(const Source &src, int64_t R, int64_t C);
 hipError_t launch_absmax_rows(const Source &src, int64_t R, int64_t C, int rht, uint64_t seed_rht,
                               float *amax, hipStream_t s);
 hipError_t launch_quantize_rows(const QuantizeArgs &a, hipStream_t s);

@@ -285,9 +285,9 @@ __global__ __launch_bounds__(256) void quantize_kernel(Loader load, int64_t R, i
             scales[row * G + L.g] = (uint8_t)b;
         }
     }
-    if (kMode == QII_MS_EDEN_PH && amax_accum) {
+    if (kMode == QII_MS_EDEN_PH && amax_accum) {   // the running maximum is spread over the slot's words
         m = wave_max(m);
-        if ((threadIdx.x & 63) == 0) max_to_global(m, amax_accum);
+        if ((threadIdx.x & 63) == 0) max_to_global(m, amax_spread_word(amax_accum, blockIdx.x));
     }
 }
 
@@ -296,12 +296,20 @@ __global__ __launch_bounds__(256) void quantize_kernel(Loader load, int64_t R, i
 // Algorithm 1 uses.  One thread takes 4 rows x 4 groups: four Philox calls (a call serves the
 // four rows of one group) and, when whole, one 16-byte load and one 4-byte store per row.
 __global__ __launch_bounds__(256) void posthoc_scales_kernel(const float *__restrict__ tbuf,
-                                                             const float *__restrict__ amax_ptr,
+                                                             const float *__restrict__ amax_ptr, int n_amax,
                                                              int64_t R, int64_t G, uint64_t seed_sr,
                                                              uint8_t *__restrict__ scales,
                                                              float *__restrict__ tensor_scale)
 {
-    const float amax = *amax_ptr;
+    // the tensor maximum: one word supplied by the caller, or the maximum of the words the heavy
+    // pass spread its running maximum over
+    __shared__ float amax_s;
+    if (threadIdx.x < 64) {
+        const float m = wave_max((int)threadIdx.x < n_amax ? amax_ptr[threadIdx.x * kAmaxStrideWords] : 0.0f);
+        if (threadIdx.x == 0) amax_s = m;
+    }
+    __syncthreads();
+    const float amax = amax_s;
     const float s = (float)(96.0 / 17.0 / 0.93);
     const float x32 = amax > 0.0f ? amax / (s * 256.0f) : 1.0f;
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -383,7 +391,7 @@ hipError_t launch_absmax(const Source &src, int64_t R, int64_t C, int rht, uint6
                          float *amax, hipStream_t s)
 {
     if (R == 0 || C == 0) return hipSuccess;
-    if (rows_kernels_apply(src)) return launch_absmax_rows(src, R, C, rht, seed_rht, amax, s);
+    if (rows_kernels_apply(src, R, C)) return launch_absmax_rows(src, R, C, rht, seed_rht, amax, s);
     if (cols_kernels_apply(src, R, C)) return launch_absmax_cols(src, R, C, rht, seed_rht, amax, s);
     const dim3 grid((unsigned)grid_for(R, C, 256)), block(256);
     return with_loader(src, [&](auto load) {
@@ -409,7 +417,7 @@ hipError_t launch_rht(const Source &src, int64_t R, int64_t C, uint64_t seed_rht
 hipError_t launch_quantize(const QuantizeArgs &a, hipStream_t s)
 {
     if (a.R == 0 || a.C == 0) return hipSuccess;
-    if (rows_kernels_apply(a.src)) return launch_quantize_rows(a, s);
+    if (rows_kernels_apply(a.src, a.R, a.C)) return launch_quantize_rows(a, s);
     if (cols_kernels_apply(a.src, a.R, a.C)) return launch_quantize_cols(a, s);
     const dim3 grid((unsigned)grid_for(a.R, a.C, 256)), block(256);
     return with_loader(a.src, [&](auto load) {
@@ -428,13 +436,13 @@ hipError_t launch_quantize(const QuantizeArgs &a, hipStream_t s)
     });
 }
 
-hipError_t launch_posthoc_scales(const float *tbuf, const float *amax, int64_t R, int64_t C,
+hipError_t launch_posthoc_scales(const float *tbuf, const float *amax, int n_amax, int64_t R, int64_t C,
                                  uint64_t seed_sr, uint8_t *scales, float *tensor_scale, hipStream_t s)
 {
     const int64_t G = C / 16, threads = ((R + 3) / 4) * ((G + 3) / 4);
     if (threads == 0) return hipSuccess;
     hipLaunchKernelGGL(posthoc_scales_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, tbuf,
-                       amax, R, G, seed_sr, scales, tensor_scale);
+                       amax, n_amax, R, G, seed_sr, scales, tensor_scale);
     return hipGetLastError();
 }
 

@@ -40,7 +40,7 @@ struct ColsArgs {
     uint8_t *codes;
     uint8_t *scales;
     float *tensor_scale;
-    uint32_t *amax_out;  // abs-max kernel, and the heavy pass of the post hoc scheme (nullable there)
+    uint32_t *amax_out;  // abs-max kernel (one word), and the heavy pass of the post hoc scheme (kAmaxSpread words, nullable there)
     float *tbuf;         // post hoc scheme: corrected pseudo-scales [R][C/16]
 };
 
@@ -55,61 +55,78 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t chunk_rsrc(const void *base, i
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
 }
 
-// load this lane's 32 rows (rows 32q .. 32q+31 of the chunk) of columns j0 and j0+1 (j0 even),
-// widen to f32 and apply the rotation signs.  `chunk` is wave-uniform; j0 is clamped into the
-// tensor by the caller, so every lane loads from a valid address.
-template <int kSrc, bool kRht>
-__device__ __forceinline__ void load_quarter_chunk(float v[2][32], const ColsArgs &a, int64_t chunk, uint32_t j0, int q)
+// Raw words of this lane's 32 rows (rows 32q .. 32q+31 of the chunk) of columns j0 and j0+1
+// (j0 even): one word per row (two bf16, or two FP4 codes plus their scale byte), two for f32.
+template <int kSrc>
+struct RawCols {
+    uint32_t a[32];
+    uint32_t b[kSrc == kSrcBF16 ? 1 : 32];   // f32: second column; NVFP4: scale bytes
+};
+
+// issue the loads; `chunk` is wave-uniform, j0 is clamped into the tensor by the caller, so every
+// lane loads from a valid address
+template <int kSrc>
+__device__ __forceinline__ void load_quarter_chunk_raw(RawCols<kSrc> &r, const ColsArgs &a, int64_t chunk, uint32_t j0, int q)
 {
-    const uint32_t sw = q == 0 ? a.sign[0] : q == 1 ? a.sign[1] : q == 2 ? a.sign[2] : a.sign[3];
     if (kSrc == kSrcNVFP4) {
         // buffer loads: wave-uniform base and row offset in scalar registers, 32-bit lane offset
         const int64_t cstride = a.ld / 2, sstride = a.ld / 16;
         const __amdgpu_buffer_rsrc_t rc_rsrc = chunk_rsrc((const uint8_t *)a.x + chunk * 128 * cstride, 127 * cstride + a.R / 2);
         const __amdgpu_buffer_rsrc_t rs_rsrc = chunk_rsrc(a.in_scales + chunk * 128 * sstride, 127 * sstride + a.R / 16);
         const int oc = (int)(32 * q * cstride + j0 / 2), os = (int)(32 * q * sstride + j0 / 16);
-        const float x32 = *a.in_ts;
-        uint32_t rc[32], rs[32];
 #pragma unroll
         for (int i = 0; i < 32; ++i) {
-            rc[i] = __builtin_amdgcn_raw_buffer_load_b8(rc_rsrc, oc, (int)(i * cstride), 0);
-            rs[i] = __builtin_amdgcn_raw_buffer_load_b8(rs_rsrc, os, (int)(i * sstride), 0);
+            r.a[i] = __builtin_amdgcn_raw_buffer_load_b8(rc_rsrc, oc, (int)(i * cstride), 0);
+            r.b[i] = __builtin_amdgcn_raw_buffer_load_b8(rs_rsrc, os, (int)(i * sstride), 0);
         }
-#pragma unroll
-        for (int i = 0; i < 32; ++i) {
-            const float2_t c = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(rc[i], 1.0f, 0);
-            const float x8 = e4m3_decode(rs[i]);
-            const uint32_t flip = kRht ? (((sw >> i) & 1u) << 31) : 0u;
-            v[0][i] = u2f(f2u((c[0] * x8) * x32) ^ flip);   // first product exact
-            v[1][i] = u2f(f2u((c[1] * x8) * x32) ^ flip);
-        }
-        return;
-    }
-    if (kSrc == kSrcBF16) {
+    } else if (kSrc == kSrcBF16) {
         const __amdgpu_buffer_rsrc_t rsrc = chunk_rsrc((const char *)a.x + chunk * 128 * a.ld * 2, (127 * a.ld + a.R) * 2);
         const int off = (int)((32 * q * a.ld + j0) * 2);
-        uint32_t raw[32];
 #pragma unroll
-        for (int i = 0; i < 32; ++i) raw[i] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, off, (int)(i * a.ld * 2), 0);
-#pragma unroll
-        for (int i = 0; i < 32; ++i) {
-            const uint32_t flip = kRht ? (((sw >> i) & 1u) << 31) : 0u;
-            v[0][i] = u2f((raw[i] << 16) ^ flip);
-            v[1][i] = u2f((raw[i] & 0xFFFF0000u) ^ flip);
-        }
+        for (int i = 0; i < 32; ++i) r.a[i] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, off, (int)(i * a.ld * 2), 0);
     } else {
         const __amdgpu_buffer_rsrc_t rsrc = chunk_rsrc((const char *)a.x + chunk * 128 * a.ld * 4, (127 * a.ld + a.R) * 4);
         const int off = (int)((32 * q * a.ld + j0) * 4);
-        u32x2 raw[32];
-#pragma unroll
-        for (int i = 0; i < 32; ++i) raw[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off, (int)(i * a.ld * 4), 0);
 #pragma unroll
         for (int i = 0; i < 32; ++i) {
-            const uint32_t flip = kRht ? (((sw >> i) & 1u) << 31) : 0u;
-            v[0][i] = u2f(raw[i][0] ^ flip);
-            v[1][i] = u2f(raw[i][1] ^ flip);
+            const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off, (int)(i * a.ld * 4), 0);
+            r.a[i] = w[0];
+            r.b[i] = w[1];
         }
     }
+}
+
+// widen to f32 (an NVFP4 source is dequantized: (e2m1 * e4m3) * tensor scale, first product exact)
+// and apply the rotation signs
+template <int kSrc, bool kRht>
+__device__ __forceinline__ void unpack_quarter_chunk(float v[2][32], const RawCols<kSrc> &r, const ColsArgs &a, int q)
+{
+    const uint32_t sw = q == 0 ? a.sign[0] : q == 1 ? a.sign[1] : q == 2 ? a.sign[2] : a.sign[3];
+    const float x32 = kSrc == kSrcNVFP4 ? *a.in_ts : 0.0f;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+        const uint32_t flip = kRht ? (((sw >> i) & 1u) << 31) : 0u;
+        if (kSrc == kSrcNVFP4) {
+            const float2_t c = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(r.a[i], 1.0f, 0);
+            const float x8 = e4m3_decode(r.b[i]);
+            v[0][i] = u2f(f2u((c[0] * x8) * x32) ^ flip);
+            v[1][i] = u2f(f2u((c[1] * x8) * x32) ^ flip);
+        } else if (kSrc == kSrcBF16) {
+            v[0][i] = u2f((r.a[i] << 16) ^ flip);
+            v[1][i] = u2f((r.a[i] & 0xFFFF0000u) ^ flip);
+        } else {
+            v[0][i] = u2f(r.a[i] ^ flip);
+            v[1][i] = u2f(r.b[i] ^ flip);
+        }
+    }
+}
+
+template <int kSrc, bool kRht>
+__device__ __forceinline__ void load_quarter_chunk(float v[2][32], const ColsArgs &a, int64_t chunk, uint32_t j0, int q)
+{
+    RawCols<kSrc> r;
+    load_quarter_chunk_raw<kSrc>(r, a, chunk, j0, q);
+    unpack_quarter_chunk<kSrc, kRht>(v, r, a, q);
 }
 
 // one cross-lane butterfly stage on 16 registers: v[k] += partner(v[k]) * s
@@ -198,6 +215,31 @@ __device__ __forceinline__ uint2 gather_quad_scales(uint32_t two_bytes, int q)
     return make_uint2(t, other);
 }
 
+// the four scale groups of a lane (two per column), their stores
+template <int kMode, int kFast>
+__device__ __forceinline__ void quantize_tile_groups(const ColsArgs &a, float v[2][32], const TensorConsts &tc,
+                                                     const uint32_t draw[2][2], int64_t chunk, int64_t j0, int q,
+                                                     const float *inv_tab)
+{
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        uint32_t codes[4];
+        uint32_t sc = 0u;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t b = quantize_group16<kMode, kFast, true>(v[e] + 16 * h, tc, draw[e][h], a.seed_sr, j0 + e,
+                                                                    chunk * 8 + 2 * q + h, codes + 2 * h, inv_tab);
+            sc |= b << (8 * h);
+        }
+        const uint2 s8 = gather_quad_scales(sc, q);
+        if (j0 + e < a.R) {
+            *reinterpret_cast<uint4 *>(a.codes + (j0 + e) * (a.C / 2) + chunk * 64 + 16 * q) =
+                make_uint4(codes[0], codes[1], codes[2], codes[3]);
+            if (q == 0) *reinterpret_cast<uint2 *>(a.scales + (j0 + e) * (a.C / 16) + chunk * 8) = s8;
+        }
+    }
+}
+
 template <int kSrc, int kMode, bool kRht>
 __global__ __launch_bounds__(256) void quantize_cols_kernel(ColsArgs a)
 {
@@ -205,6 +247,13 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(ColsArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;   // wave-uniform
     const int64_t j0 = (int64_t)blockIdx.y * 32 + 2 * (lane >> 2);
+    // R is even whenever this kernel is chosen, so a pair of columns is in range or not as a whole
+    const bool live = chunk * 128 < a.C;   // wave-uniform
+    const int64_t jc = j0 < a.R ? j0 : a.R - 2;
+    // the tile's loads are issued before anything else: they do not depend on the tensor constants,
+    // whose set-up (a dependent load, divisions, the table and its barrier) then overlaps them
+    RawCols<kSrc> raw;
+    if (kMode != QII_MS_EDEN_PH && live) load_quarter_chunk_raw<kSrc>(raw, a, chunk, (uint32_t)jc, q);
     // (the heavy pass of the post hoc scheme knows no tensor maximum: tc stays unused there)
     const TensorConsts tc = kMode == QII_MS_EDEN_PH ? TensorConsts{} : tensor_consts(kMode, *a.amax);
     if (kMode != QII_MS_EDEN_PH && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *a.tensor_scale = tc.x32;
@@ -243,13 +292,14 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(ColsArgs a)
             if (lane == 0) wave_m[wave] = m;
             __syncthreads();
             if (threadIdx.x == 0)
-                max_to_global(fmaxf(fmaxf(wave_m[0], wave_m[1]), fmaxf(wave_m[2], wave_m[3])), a.amax_out);
+                max_to_global(fmaxf(fmaxf(wave_m[0], wave_m[1]), fmaxf(wave_m[2], wave_m[3])),
+                              amax_spread_word(a.amax_out, blockIdx.x + gridDim.x * blockIdx.y));
         }
         return;
     }
     __shared__ float inv_tab[128];
     fill_inv_table(inv_tab, tc);   // before any wave leaves: it ends in a block-wide barrier
-    if (chunk * 128 >= a.C) return;
+    if (!live) return;
     if (tc.zero) {  // uniform: an all-zero tensor is emitted as zero bytes
 #pragma unroll
         for (int e = 0; e < 2; ++e)
@@ -260,66 +310,50 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(ColsArgs a)
         return;
     }
     float v[2][32];
-    // R is even whenever this kernel is chosen, so a pair of columns is in range or not as a whole
-    const int64_t jc = j0 < a.R ? j0 : a.R - 2;
-    load_quarter_chunk<kSrc, kRht>(v, a, chunk, (uint32_t)jc, q);
+    unpack_quarter_chunk<kSrc, kRht>(v, raw, a, q);
     if (kRht) {
         fwht128_quad(v[0], q);
         fwht128_quad(v[1], q);
     }
     uint32_t draw[2][2] = {{0u, 0u}, {0u, 0u}};
     if (kMode == QII_MS_EDEN) octet_draws(draw, a.seed_sr, chunk, j0, q);
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-        uint32_t codes[4];
-        uint32_t sc = 0u;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const uint32_t b = quantize_group16<kMode>(v[e] + 16 * h, tc, draw[e][h], a.seed_sr, j0 + e,
-                                                       chunk * 8 + 2 * q + h, codes + 2 * h, inv_tab);
-            sc |= b << (8 * h);
-        }
-        const uint2 s8 = gather_quad_scales(sc, q);
-        if (j0 + e < a.R) {
-            *reinterpret_cast<uint4 *>(a.codes + (j0 + e) * (a.C / 2) + chunk * 64 + 16 * q) =
-                make_uint4(codes[0], codes[1], codes[2], codes[3]);
-            if (q == 0) *reinterpret_cast<uint2 *>(a.scales + (j0 + e) * (a.C / 16) + chunk * 8) = s8;
-        }
-    }
+    if (tc.fast) quantize_tile_groups<kMode, 1>(a, v, tc, draw, chunk, j0, q, inv_tab);   // uniform: one branch per tile
+    else quantize_tile_groups<kMode, 0>(a, v, tc, draw, chunk, j0, q, inv_tab);
 }
 
+// Abs-max pass: few long-lived blocks (two per compute unit) that stride over the tiles and fold
+// their maximum into the result with one atomic each at the very end (device-wide atomics on one
+// address are resolved one after the other, about 4 ns each).  Tiles are numbered with the four
+// chunks of a block fastest, then the groups of 32 columns.
 template <int kSrc, bool kRht>
-__global__ __launch_bounds__(256) void absmax_cols_kernel(ColsArgs a)
+__global__ __launch_bounds__(256) void absmax_cols_kernel(ColsArgs a, int64_t tiles_x, int64_t tiles)
 {
     __shared__ float wave_m[4];
     const int lane = threadIdx.x & 63, q = lane & 3;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;   // wave-uniform
-    const int64_t j0 = (int64_t)blockIdx.y * 32 + 2 * (lane >> 2);
     float m = 0.0f;
-    if (chunk * 128 < a.C) {
-        float v[2][32];
-        // a clamped duplicate of a real column pair cannot change the maximum
-        load_quarter_chunk<kSrc, kRht>(v, a, chunk, (uint32_t)(j0 < a.R ? j0 : a.R - 2), q);
-        if (kRht) {
-            fwht128_quad<false>(v[0], q);
-            fwht128_quad<false>(v[1], q);
+    for (int64_t t = blockIdx.x; t < tiles; t += gridDim.x) {
+        const int64_t chunk = (t % tiles_x) * 4 + wave;   // wave-uniform
+        const int64_t j0 = (t / tiles_x) * 32 + 2 * (lane >> 2);
+        if (chunk * 128 < a.C) {
+            float v[2][32];
+            // a clamped duplicate of a real column pair cannot change the maximum
+            load_quarter_chunk<kSrc, kRht>(v, a, chunk, (uint32_t)(j0 < a.R ? j0 : a.R - 2), q);
+            if (kRht) {
+                fwht128_quad<false>(v[0], q);
+                fwht128_quad<false>(v[1], q);
+            }
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) m = fmaxf(m, group_absmax(v[e] + 16 * h));
         }
-#pragma unroll
-        for (int e = 0; e < 2; ++e)
-#pragma unroll
-            for (int h = 0; h < 2; ++h) m = fmaxf(m, group_absmax(v[e] + 16 * h));
-        if (kRht) m = __builtin_fmaf(m, kInvSqrt128, 0.0f);   // the scaling the rotation left out
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    if (kRht) m = __builtin_fmaf(m, kInvSqrt128, 0.0f);   // the scaling the rotation left out
+    m = wave_max(m);
     if (lane == 0) wave_m[wave] = m;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        m = fmaxf(fmaxf(wave_m[0], wave_m[1]), fmaxf(wave_m[2], wave_m[3]));
-        // the running maximum only grows, so a stale read can only cause a redundant atomic
-        if (f2u(m) > __atomic_load_n(a.amax_out, __ATOMIC_RELAXED)) atomicMax(a.amax_out, f2u(m));
-    }
+    if (threadIdx.x == 0) max_to_global(fmaxf(fmaxf(wave_m[0], wave_m[1]), fmaxf(wave_m[2], wave_m[3])), a.amax_out);
 }
 
 ColsArgs make_args(const Source &src, int64_t R, int64_t C, uint64_t seed_rht, uint64_t seed_sr)
@@ -358,11 +392,13 @@ hipError_t launch_absmax_cols(const Source &src, int64_t R, int64_t C, int rht, 
 {
     ColsArgs a = make_args(src, R, C, seed_rht, 0);
     a.amax_out = reinterpret_cast<uint32_t *>(amax);
-    const dim3 grid = cols_grid(R, C), block(256);
+    const dim3 full = cols_grid(R, C), block(256);
+    const int64_t tiles_x = full.x, tiles = (int64_t)full.x * full.y;
+    const dim3 grid((unsigned)(tiles < 512 ? tiles : 512));   // two blocks per compute unit
 #define QII_AMAX(SRC)                                                                             \
     do {                                                                                          \
-        if (rht) hipLaunchKernelGGL((absmax_cols_kernel<SRC, true>), grid, block, 0, s, a);       \
-        else hipLaunchKernelGGL((absmax_cols_kernel<SRC, false>), grid, block, 0, s, a);          \
+        if (rht) hipLaunchKernelGGL((absmax_cols_kernel<SRC, true>), grid, block, 0, s, a, tiles_x, tiles);  \
+        else hipLaunchKernelGGL((absmax_cols_kernel<SRC, false>), grid, block, 0, s, a, tiles_x, tiles);     \
     } while (0)
     if (src.kind == kSrcBF16) QII_AMAX(kSrcBF16);
     else if (src.kind == kSrcF32) QII_AMAX(kSrcF32);

@@ -2,11 +2,11 @@
 // (the contiguous case: Q(E), and the forward-pass RTN of X and W).
 //
 // Layout of the work: a lane owns one 16-element scale group, 8 lanes one 128-chunk, a wave
-// 8 consecutive chunks of a row (1024 elements, 2 KiB of bf16), a block 4 waves: side by
-// side on wide tensors, or, when a row needs fewer than 4 waves, 2 or 4 row quads at once.
-// blockIdx.y selects the column range, blockIdx.x strides over row quads, so the
-// per-thread set-up (lane constants, sign masks) is paid once for many groups.  The four
-// rows of a quad are loaded together (32 B per lane and row) before any arithmetic.
+// 8 consecutive chunks of a row (1024 elements, 2 KiB of bf16) of one quad of 4 rows (one
+// scale-rounding draw call serves the 4 rows of a group), a block 4 waves: side by side on
+// wide tensors, or, when a row needs fewer than 4 waves, 2 or 4 row quads.  blockIdx.y selects
+// the column range, blockIdx.x the row quads.  The four rows of a quad are requested together
+// (32 B per lane and row) before anything else happens in the kernel.
 //
 // Rotation: butterfly stages over index bits 0..3 are plain in-lane add/sub; stages over
 // bits 4..6 pair lanes (xor 1, xor 2, xor 7 via DPP) with a single v_fmac_f32_dpp:
@@ -24,6 +24,9 @@ namespace {
 
 constexpr float kInvSqrt128 = 0x1.6a09e6p-4f;  // binary32 nearest to 2^-3.5
 
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 struct RowsArgs {
     const void *x;
     int64_t ld;          // elements
@@ -34,14 +37,16 @@ struct RowsArgs {
     uint8_t *codes;
     uint8_t *scales;
     float *tensor_scale;
-    uint32_t *amax_out;  // abs-max kernel, and the heavy pass of the post hoc scheme (nullable there)
+    uint32_t *amax_out;  // abs-max kernel (one word), and the heavy pass of the post hoc scheme
+                         // (kAmaxSpread words, nullable there)
     float *tbuf;         // post hoc scheme: corrected pseudo-scales [R][C/16]
     int wpr;             // waves of a block that sit side by side on a row: 1, 2 or 4
+    int gy;              // blocks side by side on a row; the grid is one-dimensional, columns fastest
 };
 
 struct LaneSetup {
     int blk;              // 16-block of the chunk owned by this lane
-    int64_t first, step;  // this wave's first row quad and its stride (quads)
+    int quad;             // this wave's row quad (rows 4 quad .. 4 quad + 3); wave-uniform
     int64_t g;            // scale group within the row
     bool col_ok;
     float s16, s32, s64;  // +-1 multipliers of the three cross-lane stages
@@ -49,17 +54,22 @@ struct LaneSetup {
     uint32_t sign16;      // rotation sign bits of this lane's 16 elements
 };
 
+// kQuadsPerWave: row quads a wave takes (the quantizers: 1; the abs-max pass: 2)
+template <int kQuadsPerWave>
 __device__ __forceinline__ LaneSetup lane_setup(const RowsArgs &a, int64_t G)
 {
     LaneSetup L;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept in a scalar register
     const int sub = lane & 7;
     L.blk = (sub & 4) ? (sub ^ 3) : sub;
-    // wpr waves side by side, 4 / wpr row quads per block
+    // wpr waves side by side, 4 / wpr waves below one another
     const int wcol = wave & (a.wpr - 1), wq = wave / a.wpr, qpb = 4 / a.wpr;
-    L.first = (int64_t)blockIdx.x * qpb + wq;
-    L.step = (int64_t)gridDim.x * qpb;
-    const int64_t chunk = ((int64_t)blockIdx.y * a.wpr + wcol) * 8 + (lane >> 3);
+    // consecutive blocks walk along a row first, then down the rows: blocks that run at the same
+    // time read one contiguous region of the tensor
+    const int bx = (int)blockIdx.x / a.gy, by = (int)blockIdx.x - bx * a.gy;
+    L.quad = (bx * qpb + wq) * kQuadsPerWave;
+    const int64_t chunk = ((int64_t)by * a.wpr + wcol) * 8 + (lane >> 3);
     L.g = chunk * 8 + L.blk;
     L.col_ok = L.g < G;
     L.s16 = (L.blk & 1) ? -1.0f : 1.0f;
@@ -138,30 +148,36 @@ __device__ __forceinline__ uint2 gather_scale_bytes(uint32_t b, int blk)
 // raw row data of one lane: 16 elements
 template <bool kBf16>
 struct Raw {
-    uint4 q[kBf16 ? 2 : 4];
+    u32x4 q[kBf16 ? 2 : 4];
 };
 
-// rows and groups are clamped into the tensor, so every lane always loads from a valid
-// address and no exec-masked branch is needed; out-of-range lanes simply do not store
-template <bool kBf16>
-__device__ __forceinline__ void load_raw(Raw<kBf16> &r, const RowsArgs &a, int64_t row, int64_t g)
+// All row addressing is wave-uniform (a wave works on whole rows): the row's base address sits
+// in scalar registers inside a buffer descriptor that covers exactly the row's C elements, and a
+// lane only contributes a 32-bit byte offset that never changes.  A row beyond the tensor gets an
+// empty descriptor, a lane beyond the last column an offset beyond the descriptor: such loads
+// return 0 and such stores are dropped by the hardware, so neither needs a branch or a mask.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t row_rsrc(const void *base, int64_t row_bytes_offset, bool row_ok, int bytes)
 {
-    constexpr int n = kBf16 ? 2 : 4;
-    const uint4 *p = kBf16 ? reinterpret_cast<const uint4 *>((const uint16_t *)a.x + row * a.ld + g * 16)
-                           : reinterpret_cast<const uint4 *>((const float *)a.x + row * a.ld + g * 16);
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(reinterpret_cast<const char *>(base) + row_bytes_offset), 0,
+                                             row_ok ? bytes : 0, 0x00020000);
+}
+
+constexpr uint32_t kNoStore = 0xFFFFFFF0u;   // a lane offset beyond every descriptor
+
+template <bool kBf16>
+__device__ __forceinline__ void load_raw(Raw<kBf16> &r, const RowsArgs &a, int row, uint32_t voff)
+{
+    constexpr int n = kBf16 ? 2 : 4, esz = kBf16 ? 2 : 4;
+    const __amdgpu_buffer_rsrc_t rs = row_rsrc(a.x, (int64_t)row * a.ld * esz, row < (int)a.R, (int)(a.C * esz));
 #pragma unroll
-    for (int i = 0; i < n; ++i) r.q[i] = p[i];
+    for (int i = 0; i < n; ++i) r.q[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + 16u * i, 0, 0);
 }
 
 template <bool kBf16>
-__device__ __forceinline__ void load_quad(Raw<kBf16> raw[4], const RowsArgs &a, int64_t quad, int64_t g)
+__device__ __forceinline__ void load_quad(Raw<kBf16> raw[4], const RowsArgs &a, int quad, uint32_t voff)
 {
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        int64_t row = quad * 4 + it;
-        row = row < a.R ? row : a.R - 1;
-        load_raw<kBf16>(raw[it], a, row, g);
-    }
+    for (int it = 0; it < 4; ++it) load_raw<kBf16>(raw[it], a, quad * 4 + it, voff);
 }
 
 // widen to f32 and apply the rotation signs (sign masks are lane constants)
@@ -169,7 +185,7 @@ template <bool kBf16, bool kRht>
 __device__ __forceinline__ void unpack_signed(const Raw<kBf16> &r, float v[16], const uint32_t mask[kBf16 ? 8 : 16])
 {
     if (kBf16) {
-        const uint32_t w[8] = {r.q[0].x, r.q[0].y, r.q[0].z, r.q[0].w, r.q[1].x, r.q[1].y, r.q[1].z, r.q[1].w};
+        const uint32_t w[8] = {r.q[0][0], r.q[0][1], r.q[0][2], r.q[0][3], r.q[1][0], r.q[1][1], r.q[1][2], r.q[1][3]};
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const uint32_t s = kRht ? (w[i] ^ mask[i]) : w[i];
@@ -178,11 +194,9 @@ __device__ __forceinline__ void unpack_signed(const Raw<kBf16> &r, float v[16], 
         }
     } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t w[4] = {r.q[i].x, r.q[i].y, r.q[i].z, r.q[i].w};
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[4 * i + j] = u2f(kRht ? (w[j] ^ mask[4 * i + j]) : w[j]);
-        }
+            for (int j = 0; j < 4; ++j) v[4 * i + j] = u2f(kRht ? (r.q[i][j] ^ mask[4 * i + j]) : r.q[i][j]);
     }
 }
 
@@ -199,135 +213,146 @@ __device__ __forceinline__ void make_masks(uint32_t sign16, uint32_t mask[kBf16 
     }
 }
 
-// One quad of rows for one lane.  Once a row's raw words are unpacked its slot is free, so with
-// kPrefetch the same row of the block's next quad (qn) is fetched right away, four rows of
-// arithmetic ahead of its use; the block's last quad runs the copy without the loads.
-template <bool kBf16, int kMode, bool kRht, bool kPrefetch>
+// per-lane store offsets (bytes within a row of the output)
+struct StoreOffsets {
+    uint32_t codes;    // 8 bytes of codes per group
+    uint32_t scale8;   // the gathered 8 scale bytes of a chunk: the lane holding block 0 stores them
+    uint32_t scale1;   // one scale byte per lane (rows whose group count is not a multiple of 8)
+    uint32_t t4;       // post hoc scheme: one f32 per group
+};
+
+// One quad of rows for one lane: the four rows' raw words are in registers (requested at the very
+// start of the kernel).
+template <bool kBf16, int kMode, bool kRht, int kFast>
 __device__ __forceinline__ void quantize_quad(const RowsArgs &a, const LaneSetup &L, const TensorConsts &tc,
-                                              const uint32_t *mask, Raw<kBf16> raw[4], int64_t quad,
-                                              int64_t qn, int64_t G, int64_t gc, float &m,
-                                              const float *inv_tab)
+                                              const uint32_t *mask, Raw<kBf16> raw[4], int64_t G,
+                                              const StoreOffsets &so, float &m, const float *inv_tab)
 {
     uint32_t draw[4] = {0u, 0u, 0u, 0u};
     if (kMode == QII_MS_EDEN) {
-        const U4 w = philox_seeded(a.seed_sr, (uint32_t)L.g, (uint32_t)quad, 0, kStreamScale);
+        const U4 w = philox_seeded(a.seed_sr, (uint32_t)L.g, (uint32_t)L.quad, 0, kStreamScale);
         draw[0] = w.x >> 12; draw[1] = w.y >> 12; draw[2] = w.z >> 12; draw[3] = w.w >> 12;
     }
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-        const int64_t row = quad * 4 + it;
+        const int row = L.quad * 4 + it;   // wave-uniform
         float v[16];
         unpack_signed<kBf16, kRht>(raw[it], v, mask);
-        if (kPrefetch) {
-            const int64_t rn = qn * 4 + it;
-            load_raw<kBf16>(raw[it], a, rn < a.R ? rn : a.R - 1, gc);
-        }
         if (kRht) rht128_lane(v, L);
+        const bool row_ok = row < (int)a.R;
+        const __amdgpu_buffer_rsrc_t rc = row_rsrc(a.codes, (int64_t)row * (a.C / 2), row_ok, (int)(a.C / 2));
         uint32_t packed[2];
         if (kMode == QII_MS_EDEN_PH) {
             // heavy pass of the post hoc scheme: codes, corrected pseudo-scale, running maximum
             float gmax;
             const float t = posthoc_group16(v, packed, gmax);
-            if (L.col_ok && row < a.R) {
-                *reinterpret_cast<uint2 *>(a.codes + row * (a.C / 2) + (uint32_t)L.g * 8u) = make_uint2(packed[0], packed[1]);
-                (a.tbuf + row * G)[(uint32_t)L.g] = t;
-                m = fmaxf(m, gmax);
-            }
+            __builtin_amdgcn_raw_buffer_store_b64(u32x2{packed[0], packed[1]}, rc, so.codes, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(f2u(t), row_rsrc(a.tbuf, (int64_t)row * G * 4, row_ok, (int)(G * 4)), so.t4, 0, 0);
+            if (L.col_ok && row_ok) m = fmaxf(m, gmax);
             continue;
         }
-        const uint32_t b = quantize_group16<kMode>(v, tc, draw[it], a.seed_sr, row, L.g, packed, inv_tab);
-        // row base pointers are wave-uniform (scalar registers); the lane adds a 32-bit offset
-        uint8_t *crow = a.codes + row * (a.C / 2), *srow = a.scales + row * G;
-        const uint32_t goff = (uint32_t)L.g;
-        if (L.col_ok && row < a.R)
-            *reinterpret_cast<uint2 *>(crow + goff * 8u) = make_uint2(packed[0], packed[1]);
-        if (G % 8 == 0) {   // whole octets: one 8-byte store per chunk
+        const uint32_t b = quantize_group16<kMode, kFast, true>(v, tc, draw[it], a.seed_sr, row, L.g, packed, inv_tab);
+        __builtin_amdgcn_raw_buffer_store_b64(u32x2{packed[0], packed[1]}, rc, so.codes, 0, 0);
+        const __amdgpu_buffer_rsrc_t rs = row_rsrc(a.scales, (int64_t)row * G, row_ok, (int)G);
+        if (kRht || G % 8 == 0) {   // whole octets (always so with rotation): one 8-byte store per chunk
             const uint2 sc = gather_scale_bytes(b, L.blk);
-            if (L.col_ok && row < a.R && L.blk == 0)
-                *reinterpret_cast<uint2 *>(srow + goff) = sc;
-        } else if (L.col_ok && row < a.R) {
-            srow[goff] = (uint8_t)b;
+            __builtin_amdgcn_raw_buffer_store_b64(u32x2{sc.x, sc.y}, rs, so.scale8, 0, 0);
+        } else {
+            __builtin_amdgcn_raw_buffer_store_b8((uint8_t)b, rs, so.scale1, 0, 0);
         }
     }
 }
 
+// One wave = one quad of rows x 1024 columns, one block = 4 such pieces; the grid covers the tensor.
+// Blocks are short-lived on purpose: many independent blocks that start and finish at different
+// times keep the memory traffic of the chip smooth, where long-lived waves marching in step (a
+// grid-stride loop with prefetch was measured) load and compute in bursts and ran 10 % slower.
 template <bool kBf16, int kMode, bool kRht>
 __global__ __launch_bounds__(256) void quantize_rows_kernel(RowsArgs a)
 {
+    constexpr int esz = kBf16 ? 2 : 4;
     const int64_t G = a.C / 16;
-    const LaneSetup L = lane_setup(a, G);
+    const LaneSetup L = lane_setup<1>(a, G);
+    // the rows are requested before anything else: the loads do not depend on the tensor
+    // constants, whose set-up (a dependent load, divisions, the table) then overlaps them
+    const uint32_t voff = (uint32_t)L.g * (16u * esz);   // (beyond the row for lanes beyond the last column)
+    Raw<kBf16> raw[4];
+    load_quad<kBf16>(raw, a, L.quad, voff);
     // (the heavy pass of the post hoc scheme knows no tensor maximum: tc stays unused there)
     const TensorConsts tc = kMode == QII_MS_EDEN_PH ? TensorConsts{} : tensor_consts(kMode, *a.amax);
-    if (kMode != QII_MS_EDEN_PH && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *a.tensor_scale = tc.x32;
-    const int64_t quads = (a.R + 3) / 4;
+    if (kMode != QII_MS_EDEN_PH && blockIdx.x == 0 && threadIdx.x == 0) *a.tensor_scale = tc.x32;
+    StoreOffsets so;
+    so.codes = L.col_ok ? (uint32_t)L.g * 8u : kNoStore;
+    so.scale8 = (L.col_ok && L.blk == 0) ? (uint32_t)L.g : kNoStore;
+    so.scale1 = L.col_ok ? (uint32_t)L.g : kNoStore;
+    so.t4 = L.col_ok ? (uint32_t)L.g * 4u : kNoStore;
     if (tc.zero) {  // uniform: an all-zero tensor is emitted as zero bytes
-        for (int64_t quad = L.first; quad < quads; quad += L.step)
-            for (int it = 0; it < 4; ++it) {
-                const int64_t row = quad * 4 + it;
-                if (L.col_ok && row < a.R) {
-                    *reinterpret_cast<uint2 *>(a.codes + (row * a.C + L.g * 16) / 2) = make_uint2(0u, 0u);
-                    a.scales[row * G + L.g] = 0;
-                }
+        for (int it = 0; it < 4; ++it) {
+            const int64_t row = (int64_t)L.quad * 4 + it;
+            if (L.col_ok && row < a.R) {
+                *reinterpret_cast<uint2 *>(a.codes + (row * a.C + L.g * 16) / 2) = make_uint2(0u, 0u);
+                a.scales[row * G + L.g] = 0;
             }
+        }
         return;
     }
     __shared__ float inv_tab[128];
+    __shared__ float wave_m[4];
     if (kMode != QII_MS_EDEN_PH) fill_inv_table(inv_tab, tc);
     uint32_t mask[kBf16 ? 8 : 16];
     make_masks<kBf16>(L.sign16, mask);
-    const int64_t gc = L.col_ok ? L.g : G - 1;
-    Raw<kBf16> raw[4];
-    int64_t quad = L.first;   // (a wave whose first quad lies beyond the tensor stores nothing)
-    load_quad<kBf16>(raw, a, quad, gc);
     float m = 0.0f;
-    for (; quad + L.step < quads; quad += L.step)
-        quantize_quad<kBf16, kMode, kRht, true>(a, L, tc, mask, raw, quad, quad + L.step, G, gc, m, inv_tab);
-    quantize_quad<kBf16, kMode, kRht, false>(a, L, tc, mask, raw, quad, quad, G, gc, m, inv_tab);
-    if (kMode == QII_MS_EDEN_PH && a.amax_out) {   // one atomic per wave at most; a wave covers many quads
+    if (kMode == QII_MS_EDEN_PH || tc.fast)   // uniform: one branch for the whole kernel
+        quantize_quad<kBf16, kMode, kRht, 1>(a, L, tc, mask, raw, G, so, m, inv_tab);
+    else
+        quantize_quad<kBf16, kMode, kRht, 0>(a, L, tc, mask, raw, G, so, m, inv_tab);
+    if (kMode == QII_MS_EDEN_PH && a.amax_out) {   // uniform: one update per block, spread over the slot's words
         m = wave_max(m);
-        if ((threadIdx.x & 63) == 0) max_to_global(m, a.amax_out);
+        if ((threadIdx.x & 63) == 0) wave_m[threadIdx.x >> 6] = m;
+        __syncthreads();
+        if (threadIdx.x == 0)
+            max_to_global(fmaxf(fmaxf(wave_m[0], wave_m[1]), fmaxf(wave_m[2], wave_m[3])),
+                          amax_spread_word(a.amax_out, blockIdx.x));
     }
 }
 
+// Abs-max pass.  Its result is one word that every block has to fold its maximum into, and such
+// device-wide atomics on one address are resolved one after the other (about 4 ns each), so this
+// kernel runs as few, long-lived blocks (two per compute unit) that stride over the row quads with
+// the next quad's loads in flight, and issue one atomic each at the very end.
 template <bool kBf16, bool kRht>
-__global__ __launch_bounds__(256, 4) void absmax_rows_kernel(RowsArgs a)
+__global__ __launch_bounds__(256) void absmax_rows_kernel(RowsArgs a)
 {
+    constexpr int esz = kBf16 ? 2 : 4;
     __shared__ float wave_m[4];
     const int64_t G = a.C / 16;
-    const LaneSetup L = lane_setup(a, G);
+    const LaneSetup L = lane_setup<1>(a, G);
+    const int quads = (int)((a.R + 3) / 4);
+    const int step = ((int)gridDim.x / a.gy) * (4 / a.wpr);
+    const uint32_t voff = (uint32_t)L.g * (16u * esz);
     uint32_t mask[kBf16 ? 8 : 16];
     make_masks<kBf16>(L.sign16, mask);
-    const int64_t quads = (a.R + 3) / 4;
-    const int64_t gc = L.col_ok ? L.g : G - 1;
     float m = 0.0f;
     Raw<kBf16> raw[4];
-    load_quad<kBf16>(raw, a, L.first, gc);
-    for (int64_t quad = L.first; quad < quads; quad += L.step) {
+    load_quad<kBf16>(raw, a, L.quad, voff);   // (rows and columns beyond the tensor read as 0 and cannot change the maximum)
+    for (int quad = L.quad; quad < quads; quad += step) {
         Raw<kBf16> nxt[4];
-        const int64_t qn = quad + L.step;
-        load_quad<kBf16>(nxt, a, qn < quads ? qn : quad, gc);
+        load_quad<kBf16>(nxt, a, quad + step, voff);
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             float v[16];
             unpack_signed<kBf16, kRht>(raw[it], v, mask);
             if (kRht) rht128_lane<false>(v, L);
-            // a clamped duplicate of a real row cannot change the maximum; lanes beyond the
-            // last column hold a made-up chunk and are left out
-            if (L.col_ok) m = fmaxf(m, group_absmax(v));
+            m = fmaxf(m, group_absmax(v));
         }
 #pragma unroll
         for (int it = 0; it < 4; ++it) raw[it] = nxt[it];
     }
     if (kRht) m = __builtin_fmaf(m, kInvSqrt128, 0.0f);   // the scaling the rotation left out
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    m = wave_max(m);
     if ((threadIdx.x & 63) == 0) wave_m[threadIdx.x >> 6] = m;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        m = fmaxf(fmaxf(wave_m[0], wave_m[1]), fmaxf(wave_m[2], wave_m[3]));
-        // the running maximum only grows, so a stale read can only cause a redundant atomic
-        if (f2u(m) > __atomic_load_n(a.amax_out, __ATOMIC_RELAXED)) atomicMax(a.amax_out, f2u(m));
-    }
+    if (threadIdx.x == 0) max_to_global(fmaxf(fmaxf(wave_m[0], wave_m[1]), fmaxf(wave_m[2], wave_m[3])), a.amax_out);
 }
 
 // waves of a block side by side on a row: as many as the row needs, at most 4
@@ -337,19 +362,20 @@ int rows_wpr(int64_t C)
     return nch <= 8 ? 1 : nch <= 16 ? 2 : 4;
 }
 
-// blocks: as many as stay resident at once (4 per CU), with the row quads split evenly
-dim3 rows_grid(int64_t R, int64_t C)
+// one wave per row quad x 1024 columns; max_block_rows > 0 caps the number of blocks below one
+// another (the abs-max pass then strides over the rest)
+dim3 rows_grid(int64_t R, int64_t C, int64_t max_block_rows)
 {
     const int64_t G = C / 16, nch = (G + 7) / 8;
     const int wpr = rows_wpr(C);
     const int64_t gy = (nch + 8 * wpr - 1) / (8 * wpr);
-    const int64_t quads = (R + 3) / 4, qpb = 4 / wpr, bquads = (quads + qpb - 1) / qpb;
-    int64_t cap = (256 * 4) / gy;                  // 256 CUs x 4 resident blocks
-    if (cap < 1) cap = 1;
-    const int64_t iters = (bquads + cap - 1) / cap; // iterations per block
-    int64_t gx = (bquads + iters - 1) / iters;      // even split
-    if (gx < 1) gx = 1;
-    return dim3((unsigned)gx, (unsigned)gy);
+    const int64_t quads = (R + 3) / 4, qpb = 4 / wpr;
+    int64_t gx = (quads + qpb - 1) / qpb;
+    if (max_block_rows > 0 && gx > max_block_rows) {
+        const int64_t iters = (gx + max_block_rows - 1) / max_block_rows;
+        gx = (gx + iters - 1) / iters;   // even split
+    }
+    return dim3((unsigned)((gx < 1 ? 1 : gx) * gy), 1u);
 }
 
 RowsArgs make_args(const Source &src, int64_t R, int64_t C, uint64_t seed_rht, uint64_t seed_sr)
@@ -362,14 +388,18 @@ RowsArgs make_args(const Source &src, int64_t R, int64_t C, uint64_t seed_rht, u
     a.amax = nullptr; a.codes = nullptr; a.scales = nullptr; a.tensor_scale = nullptr; a.amax_out = nullptr;
     a.tbuf = nullptr;
     a.wpr = rows_wpr(C);
+    const int64_t nch = (C / 16 + 7) / 8;
+    a.gy = (int)((nch + 8 * a.wpr - 1) / (8 * a.wpr));
     return a;
 }
 
 }  // namespace
 
-bool rows_kernels_apply(const Source &src)
+// (a row of the source and of every output is addressed through a 32-bit buffer descriptor)
+bool rows_kernels_apply(const Source &src, int64_t R, int64_t C)
 {
-    return !src.transpose && (src.kind == kSrcBF16 || src.kind == kSrcF32);
+    return !src.transpose && (src.kind == kSrcBF16 || src.kind == kSrcF32) && C <= ((int64_t)1 << 28) &&
+           R < ((int64_t)1 << 31) - 8;   // row indices are 32-bit in the kernels
 }
 
 hipError_t launch_absmax_rows(const Source &src, int64_t R, int64_t C, int rht, uint64_t seed_rht,
@@ -377,7 +407,8 @@ hipError_t launch_absmax_rows(const Source &src, int64_t R, int64_t C, int rht, 
 {
     RowsArgs a = make_args(src, R, C, seed_rht, 0);
     a.amax_out = reinterpret_cast<uint32_t *>(amax);
-    const dim3 grid = rows_grid(R, C), block(256);
+    const int64_t gy_ = a.gy;
+    const dim3 grid = rows_grid(R, C, 512 / gy_ > 0 ? 512 / gy_ : 1), block(256);   // two blocks per compute unit
     const bool bf = src.kind == kSrcBF16;
     if (bf) { if (rht) hipLaunchKernelGGL((absmax_rows_kernel<true, true>), grid, block, 0, s, a); else hipLaunchKernelGGL((absmax_rows_kernel<true, false>), grid, block, 0, s, a); }
     else { if (rht) hipLaunchKernelGGL((absmax_rows_kernel<false, true>), grid, block, 0, s, a); else hipLaunchKernelGGL((absmax_rows_kernel<false, false>), grid, block, 0, s, a); }
@@ -389,7 +420,7 @@ hipError_t launch_quantize_rows(const QuantizeArgs &q, hipStream_t s)
     RowsArgs a = make_args(q.src, q.R, q.C, q.seed_rht, q.seed_sr);
     a.amax = q.amax; a.codes = q.codes; a.scales = q.scales; a.tensor_scale = q.tensor_scale;
     a.tbuf = q.tbuf; a.amax_out = q.amax_accum;
-    const dim3 grid = rows_grid(q.R, q.C), block(256);
+    const dim3 grid = rows_grid(q.R, q.C, 0), block(256);
     const bool bf = q.src.kind == kSrcBF16;
 #define QII_ROWS(BF, MODE, RHT) hipLaunchKernelGGL((quantize_rows_kernel<BF, MODE, RHT>), grid, block, 0, s, a)
 #define QII_ROWS_MODE(BF, RHT)                                   \

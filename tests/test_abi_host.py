@@ -101,8 +101,8 @@ def test_new_modes_and_layer_variants_reject_bad_arguments(libqii):
     # post hoc scheme: needs its per-group buffer even when the abs-max is supplied
     assert L.qii_quantize_nvfp4(0x1000, 1, 4, 128, 128, 0, 4, 128, 0, 0, 0x2000, ctypes.byref(out), None, 0, None) == 4
     assert L.qii_quantize_nvfp4(0x1000, 1, 4, 128, 128, 0, 4, 128, 0, 0, 0x2000, ctypes.byref(out), 0x4000, 256, None) == 4
-    assert libqii.qii_quantize_posthoc_workspace_bytes(4, 128) == 256 + 256      # one slot + 32 floats, padded
-    assert libqii.qii_quantize_posthoc_workspace_bytes(8192, 8192) == 256 + 8192 * 512 * 4
+    assert libqii.qii_quantize_posthoc_workspace_bytes(4, 128) == 16384 + 256    # running-maximum region + 32 floats, padded
+    assert libqii.qii_quantize_posthoc_workspace_bytes(8192, 8192) == 16384 + 8192 * 512 * 4
     # the layer variants only take the modes that make sense for their pass
     xq = _NVFP4(0x1000, 0x1000, 0x1000, 256, 128)
     wq = _NVFP4(0x1000, 0x1000, 0x1000, 384, 128)
@@ -112,7 +112,7 @@ def test_new_modes_and_layer_variants_reject_bad_arguments(libqii):
     assert L.qii_linear_bwd_mode(0x1000, 1, ctypes.byref(xq), ctypes.byref(wq), 0, 4, 0x1000, 0x1000, 1, 0x1000, 16, None) == 4
     plain = libqii.qii_linear_bwd_mode_workspace_bytes(256, 128, 384, 2)
     assert plain == libqii.qii_linear_bwd_workspace_bytes(256, 128, 384)
-    assert libqii.qii_linear_bwd_mode_workspace_bytes(256, 128, 384, 4) == plain + 256 * 384 // 16 * 4
+    assert libqii.qii_linear_bwd_mode_workspace_bytes(256, 128, 384, 4) == plain + 4 * (16384 - 256) + 256 * 384 // 16 * 4
 
 
 def test_layer_passes_validate_everything_before_the_first_launch(libqii):
