@@ -165,6 +165,13 @@ qii_status qii_dequantize_nvfp4(const qii_nvfp4 *in, float *y, void *stream);
 qii_status qii_gemm_nvfp4(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_dtype c_dt,
                           int64_t ldc, void *ws, size_t ws_bytes, void *stream);
 
+/* The same GEMM that also emits max |C| (over the values as stored in C, i.e. after rounding to
+ * c_dt) into the device float amax_c: the abs-max the next quantizer of C needs (Sec. 3.1 / 3.3,
+ * numerator of x^FP32) comes out of the producing kernel, as App. D assumes, instead of costing
+ * one more read of C.  amax_c == NULL gives qii_gemm_nvfp4.  With M * N == 0 it receives 0.   */
+qii_status qii_gemm_nvfp4_amax(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_dtype c_dt,
+                               int64_t ldc, float *amax_c, void *ws, size_t ws_bytes, void *stream);
+
 /* Forward pass of one linear layer (Sec. 5): Xq = RTN(X) and Wq = RTN(W) with 1x16
  * scales along d_in and no rotation, Y = Xq * Wq^T.  X is T x d_in, W is d_out x d_in,
  * Y is T x d_out (contiguous, dtype y_dt).  Xq_saved (T x d_in) and Wq_saved
@@ -184,6 +191,14 @@ qii_status qii_linear_fwd(const void *X, const void *W, qii_dtype dt, int64_t T,
 qii_status qii_linear_fwd_mode(const void *X, const void *W, qii_dtype dt, int64_t T, int64_t d_in,
                                int64_t d_out, qii_mode mode, const float *amax_x, const float *amax_w,
                                void *Y, qii_dtype y_dt, const qii_nvfp4 *Xq_saved,
+                               const qii_nvfp4 *Wq_saved, void *ws, size_t ws_bytes, void *stream);
+
+/* qii_linear_fwd_mode that also emits max |Y| into the device float amax_y (nullable), from the
+ * GEMM's epilogue: a stack of layers passes it as amax_x of the layer that consumes Y, which then
+ * needs no abs-max pass over its input (App. D).                                          */
+qii_status qii_linear_fwd_amax(const void *X, const void *W, qii_dtype dt, int64_t T, int64_t d_in,
+                               int64_t d_out, qii_mode mode, const float *amax_x, const float *amax_w,
+                               void *Y, qii_dtype y_dt, float *amax_y, const qii_nvfp4 *Xq_saved,
                                const qii_nvfp4 *Wq_saved, void *ws, size_t ws_bytes, void *stream);
 
 /* Backward pass of one linear layer (Sec. 5): with six sub-seeds derived from `seed`

@@ -25,7 +25,7 @@ EXPORTS = [
     "qii_quantize_workspace_bytes", "qii_quantize_posthoc_workspace_bytes", "qii_linear_bwd_mode_workspace_bytes",
     "qii_gemm_workspace_bytes", "qii_linear_fwd_workspace_bytes", "qii_linear_bwd_workspace_bytes",
     "qii_derive_seed", "qii_status_string", "qii_last_error", "qii_version", "qii_selftest_conversions",
-    "qii_quantize_nvfp4_noalloc",
+    "qii_quantize_nvfp4_noalloc", "qii_gemm_nvfp4_amax", "qii_linear_fwd_amax",
 ]
 
 
@@ -60,6 +60,10 @@ def lib() -> ctypes.CDLL:
         L.qii_requantize_nvfp4.argtypes = [nv, c.c_int, c.c_int, c.c_int, u64, u64, vp, nv, vp, sz, vp]
         L.qii_dequantize_nvfp4.argtypes = [nv, vp, vp]
         L.qii_gemm_nvfp4.argtypes = [nv, nv, vp, c.c_int, i64, vp, sz, vp]
+        L.qii_gemm_nvfp4_amax.argtypes = [nv, nv, vp, c.c_int, i64, vp, vp, sz, vp]
+        L.qii_gemm_nvfp4_amax.restype = c.c_int
+        L.qii_linear_fwd_amax.argtypes = [vp, vp, c.c_int, i64, i64, i64, c.c_int, vp, vp, vp, c.c_int, vp, nv, nv, vp, sz, vp]
+        L.qii_linear_fwd_amax.restype = c.c_int
         L.qii_linear_fwd.argtypes = [vp, vp, c.c_int, i64, i64, i64, vp, c.c_int, nv, nv, vp, sz, vp]
         L.qii_linear_fwd_mode.argtypes = [vp, vp, c.c_int, i64, i64, i64, c.c_int, vp, vp, vp, c.c_int, nv, nv, vp, sz, vp]
         L.qii_linear_bwd.argtypes = [vp, c.c_int, nv, nv, u64, vp, vp, c.c_int, vp, sz, vp]
@@ -240,6 +244,27 @@ def qii_gemm_nvfp4(A: NVFP4Tensor, B: NVFP4Tensor, C: torch.Tensor, ws: torch.Te
     sa, sb = A.c_struct(), B.c_struct()
     _check(lib().qii_gemm_nvfp4(ctypes.byref(sa), ctypes.byref(sb), C.data_ptr(), _dt(C), C.stride(0),
                                 _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(), _stream()))
+
+
+def qii_gemm_nvfp4_amax(A: NVFP4Tensor, B: NVFP4Tensor, C: torch.Tensor, amax_c: torch.Tensor | None,
+                        ws: torch.Tensor | None = None):
+    _rows_contig(C)
+    sa, sb = A.c_struct(), B.c_struct()
+    _check(lib().qii_gemm_nvfp4_amax(ctypes.byref(sa), ctypes.byref(sb), C.data_ptr(), _dt(C), C.stride(0),
+                                     _ptr(amax_c), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                                     _stream()))
+
+
+def qii_linear_fwd_amax(X: torch.Tensor, W: torch.Tensor, mode: int, Y: torch.Tensor, amax_y: torch.Tensor | None,
+                        Xq: NVFP4Tensor, Wq: NVFP4Tensor, ws: torch.Tensor, amax_x: torch.Tensor | None = None,
+                        amax_w: torch.Tensor | None = None):
+    _contig(X, W, Y)
+    T, d_in = X.shape
+    d_out = W.shape[0]
+    sx, sw = Xq.c_struct(), Wq.c_struct()
+    _check(lib().qii_linear_fwd_amax(X.data_ptr(), W.data_ptr(), _dt(X), T, d_in, d_out, mode, _ptr(amax_x),
+                                     _ptr(amax_w), Y.data_ptr(), _dt(Y), _ptr(amax_y), ctypes.byref(sx),
+                                     ctypes.byref(sw), ws.data_ptr(), ws.numel() * ws.element_size(), _stream()))
 
 
 def qii_linear_fwd(X: torch.Tensor, W: torch.Tensor, Y: torch.Tensor, Xq: NVFP4Tensor,

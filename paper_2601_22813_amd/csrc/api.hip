@@ -424,23 +424,43 @@ qii_status qii_dequantize_nvfp4(const qii_nvfp4 *in, float *y, void *stream)
     return QII_OK;
 }
 
-qii_status qii_gemm_nvfp4(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_dtype c_dt,
-                          int64_t ldc, void *ws, size_t ws_bytes, void *stream)
+qii_status qii_gemm_nvfp4_amax(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_dtype c_dt,
+                               int64_t ldc, float *amax_c, void *ws, size_t ws_bytes, void *stream)
 {
     const qii_status st = check_gemm_args(A, B, C, c_dt, ldc);
     if (st != QII_OK) return st;
-    if (A->rows * B->rows == 0) return QII_OK;
-    hipError_t e = qii::launch_gemm(*A, *B, C, c_dt == QII_BF16, ldc, ws, ws_bytes, (hipStream_t)stream);
+    if (amax_c && !aligned(amax_c, 4)) return fail(QII_INVALID_ARG, "misaligned amax_c");
+    hipError_t e = qii::launch_gemm(*A, *B, C, c_dt == QII_BF16, ldc, amax_c, ws, ws_bytes, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, "gemm");
     return QII_OK;
 }
+
+qii_status qii_gemm_nvfp4(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_dtype c_dt,
+                          int64_t ldc, void *ws, size_t ws_bytes, void *stream)
+{
+    return qii_gemm_nvfp4_amax(A, B, C, c_dt, ldc, nullptr, ws, ws_bytes, stream);
+}
+
+qii_status qii_linear_fwd_amax(const void *X, const void *W, qii_dtype dt, int64_t T, int64_t d_in,
+                               int64_t d_out, qii_mode mode, const float *amax_x, const float *amax_w,
+                               void *Y, qii_dtype y_dt, float *amax_y, const qii_nvfp4 *Xq,
+                               const qii_nvfp4 *Wq, void *ws, size_t ws_bytes, void *stream);
 
 qii_status qii_linear_fwd_mode(const void *X, const void *W, qii_dtype dt, int64_t T, int64_t d_in,
                                int64_t d_out, qii_mode mode, const float *amax_x, const float *amax_w,
                                void *Y, qii_dtype y_dt, const qii_nvfp4 *Xq,
                                const qii_nvfp4 *Wq, void *ws, size_t ws_bytes, void *stream)
 {
+    return qii_linear_fwd_amax(X, W, dt, T, d_in, d_out, mode, amax_x, amax_w, Y, y_dt, nullptr, Xq, Wq, ws, ws_bytes, stream);
+}
+
+qii_status qii_linear_fwd_amax(const void *X, const void *W, qii_dtype dt, int64_t T, int64_t d_in,
+                               int64_t d_out, qii_mode mode, const float *amax_x, const float *amax_w,
+                               void *Y, qii_dtype y_dt, float *amax_y, const qii_nvfp4 *Xq,
+                               const qii_nvfp4 *Wq, void *ws, size_t ws_bytes, void *stream)
+{
     // every argument of the whole pass is checked before the first launch
+    if (amax_y && !aligned(amax_y, 4)) return fail(QII_INVALID_ARG, "misaligned amax_y");
     if (mode != QII_RTN && mode != QII_RTN_46)
         return fail(QII_INVALID_ARG, "the forward pass takes QII_RTN or QII_RTN_46, not mode %d", (int)mode);
     if (T < 0 || d_in < 0 || d_out < 0) return fail(QII_BAD_SHAPE, "negative dimension");
@@ -474,7 +494,7 @@ qii_status qii_linear_fwd_mode(const void *X, const void *W, qii_dtype dt, int64
     if (st != QII_OK) return st;
     st = quantize_source(sw, d_out, d_in, mode, 0, 0, 0, amax_w, Wq, slots + slot_words, nullptr, s, true);
     if (st != QII_OK) return st;
-    return qii_gemm_nvfp4(Xq, Wq, Y, y_dt, d_out, p + 2 * kSlot, ws_bytes - 2 * kSlot, stream);
+    return qii_gemm_nvfp4_amax(Xq, Wq, Y, y_dt, d_out, amax_y, p + 2 * kSlot, ws_bytes - 2 * kSlot, stream);
 }
 
 qii_status qii_linear_fwd(const void *X, const void *W, qii_dtype dt, int64_t T, int64_t d_in,

@@ -127,6 +127,18 @@ __device__ __forceinline__ uint32_t scale_pair(uint32_t two_bytes, int which)
     return (b << 7) | (b << 23);
 }
 
+// Optional by-product of the epilogue: max |C| over the stored values, for a consumer that
+// quantizes C next and would otherwise have to read it once more just for its abs-max (the
+// paper's layer timings assume the abs-max comes from the producing kernel, App. D).  One
+// atomic without return per wave; non-negative floats order like their bit patterns.
+__device__ __forceinline__ void emit_tile_max(float cmax, uint32_t *amax_out)
+{
+    if (!amax_out) return;   // uniform
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) cmax = fmaxf(cmax, __shfl_xor(cmax, off));
+    if ((threadIdx.x & 63) == 0) atomicMax(amax_out, f2u(cmax));
+}
+
 template <bool kBf16Out>
 __global__ __launch_bounds__(256, 1) void gemm_kernel(const uint8_t *__restrict__ a_codes,
                                                       const uint8_t *__restrict__ a_scales,
@@ -135,7 +147,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const uint8_t *__restrict_
                                                       const uint8_t *__restrict__ b_scales,
                                                       const float *__restrict__ b_ts, int64_t M,
                                                       int64_t N, int64_t K, void *__restrict__ Cout,
-                                                      int64_t ldc, int tiles_n)
+                                                      int64_t ldc, int tiles_n, uint32_t *amax_out)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     const int tile = blockIdx.x;
@@ -200,6 +212,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const uint8_t *__restrict_
     // epilogue: C = acc * (x32_A * x32_B).  acc[r] of a 32x32 tile is row
     // 8*(r/4) + 4*(lane/32) + r%4, column lane%32.
     const float ts = (*a_ts) * (*b_ts);
+    float cmax = 0.0f;   // max |C| as stored, over this lane's entries inside the matrix
 #pragma unroll
     for (int ti = 0; ti < 4; ++ti)
 #pragma unroll
@@ -210,11 +223,18 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const uint8_t *__restrict_
                 const int64_t row = m0 + wm * 128 + ti * 32 + 8 * (r >> 2) + 4 * kb + (r & 3);
                 if (row < M && col < N) {
                     const float v = acc[ti][tj][r] * ts;
-                    if (kBf16Out) reinterpret_cast<uint16_t *>(Cout)[row * ldc + col] = (uint16_t)f32_to_bf16_bits(v);
-                    else reinterpret_cast<float *>(Cout)[row * ldc + col] = v;
+                    if (kBf16Out) {
+                        const uint32_t bits = f32_to_bf16_bits(v);
+                        reinterpret_cast<uint16_t *>(Cout)[row * ldc + col] = (uint16_t)bits;
+                        cmax = fmaxf(cmax, fabsf(u2f(bits << 16)));
+                    } else {
+                        reinterpret_cast<float *>(Cout)[row * ldc + col] = v;
+                        cmax = fmaxf(cmax, fabsf(v));
+                    }
                 }
             }
         }
+    emit_tile_max(cmax, amax_out);
 }
 
 
@@ -292,8 +312,9 @@ template <bool kBf16Out>
 __device__ __forceinline__ void store_tile_through_lds(floatx16 (&acc)[4][4], uint8_t *smem, float ts,
                                                        void *Cout, int64_t ldc, int64_t M, int64_t N,
                                                        int64_t m0, int64_t n0, int wave, int wm, int wn,
-                                                       int lane, int li, int kb)
+                                                       int lane, int li, int kb, uint32_t *amax_out)
 {
+    float cmax = 0.0f;
     constexpr int esz = kBf16Out ? 2 : 4;
     constexpr int pitch = 128 * esz + 16;
     uint8_t *wtile = smem + wave * (32 * pitch);
@@ -318,6 +339,13 @@ __device__ __forceinline__ void store_tile_through_lds(floatx16 (&acc)[4][4], ui
             const int64_t grow = m0 + wm * 128 + ti * 32 + row;
             const int64_t gcol = n0 + wn * 128 + piece * (16 / esz);
             if (grow < M) {
+                if (amax_out) {   // uniform: max |C| over the entries of this piece that lie inside the matrix
+                    const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int e = 0; e < 16 / esz; ++e)
+                        if (gcol + e < N)
+                            cmax = fmaxf(cmax, fabsf(kBf16Out ? u2f((e & 1) ? (w4[e >> 1] & 0xFFFF0000u) : (w4[e >> 1] << 16)) : u2f(w4[e])));
+                }
                 uint8_t *dst = reinterpret_cast<uint8_t *>(Cout) + (grow * ldc + gcol) * esz;
                 if (gcol + 16 / esz <= N && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
                     // C is written once and not read again here: a streaming (non-temporal) store
@@ -335,6 +363,7 @@ __device__ __forceinline__ void store_tile_through_lds(floatx16 (&acc)[4][4], ui
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next band overwrites
     }
+    emit_tile_max(cmax, amax_out);
 }
 
 // 64 elements of K for the wave's 4 x 4 MFMA tiles: 4 steps of 16 MFMAs, each step
@@ -367,7 +396,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel_v2(const uint8_t *__restri
                                                          const uint8_t *__restrict__ b_scales,
                                                          const float *__restrict__ b_ts, int64_t M,
                                                          int64_t N, int64_t K, void *__restrict__ Cout,
-                                                         int64_t ldc, int tiles_m, int tiles_n)
+                                                         int64_t ldc, int tiles_m, int tiles_n, uint32_t *amax_out)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     // XCD-aware order: consecutive block ids land on different XCDs (8 of them, each with its
@@ -419,7 +448,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel_v2(const uint8_t *__restri
         st_cur = st_next;
     }
 
-    store_tile_through_lds<kBf16Out>(acc, smem, (*a_ts) * (*b_ts), Cout, ldc, M, N, m0, n0, wave, wm, wn, lane, li, kb);
+    store_tile_through_lds<kBf16Out>(acc, smem, (*a_ts) * (*b_ts), Cout, ldc, M, N, m0, n0, wave, wm, wn, lane, li, kb, amax_out);
 }
 
 
@@ -574,7 +603,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel_v4(const uint8_t *__restri
                                                          const uint8_t *__restrict__ b_tiled,
                                                          const float *__restrict__ b_ts, int64_t M,
                                                          int64_t N, int64_t K, void *__restrict__ Cout,
-                                                         int64_t ldc, int tiles_m, int tiles_n)
+                                                         int64_t ldc, int tiles_m, int tiles_n, uint32_t *amax_out)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     // XCD-aware order: consecutive block ids land on different XCDs (8 of them, each with its
@@ -678,7 +707,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel_v4(const uint8_t *__restri
     // the last read block is still in flight: its registers and the stages are reused below
     frag_read_wait(fo);
     __syncthreads();
-    store_tile_through_lds<kBf16Out>(acc, smem, (*a_ts) * (*b_ts), Cout, ldc, M, N, m0, n0, wave, wm, wn, lane, li, kb);
+    store_tile_through_lds<kBf16Out>(acc, smem, (*a_ts) * (*b_ts), Cout, ldc, M, N, m0, n0, wave, wm, wn, lane, li, kb, amax_out);
 }
 
 }  // namespace
@@ -707,9 +736,14 @@ hipError_t allow_dynamic_lds(Kern kern, int bytes)
 }
 
 hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is_bf16, int64_t ldc,
-                       void *ws, size_t ws_bytes, hipStream_t s)
+                       float *amax_c, void *ws, size_t ws_bytes, hipStream_t s)
 {
     const int64_t M = A.rows, N = B.rows, K = A.cols;
+    uint32_t *amax_out = reinterpret_cast<uint32_t *>(amax_c);
+    if (amax_out) {   // the running maximum starts at 0 (a kernel, not a memset node: graph capture)
+        const hipError_t e = launch_fill_u32(amax_out, 0u, 1, 1, s);
+        if (e != hipSuccess) return e;
+    }
     if (M == 0 || N == 0) return hipSuccess;
     const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
@@ -726,12 +760,12 @@ hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is
             e = allow_dynamic_lds(gemm_kernel_v4<true>, kSmem4);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(gemm_kernel_v4<true>, grid, block, kSmem4, s, A.codes, a_tiled, A.tensor_scale,
-                               B.codes, b_tiled, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n);
+                               B.codes, b_tiled, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n, amax_out);
         } else {
             e = allow_dynamic_lds(gemm_kernel_v4<false>, kSmem4);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(gemm_kernel_v4<false>, grid, block, kSmem4, s, A.codes, a_tiled, A.tensor_scale,
-                               B.codes, b_tiled, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n);
+                               B.codes, b_tiled, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n, amax_out);
         }
         return hipGetLastError();
     }
@@ -741,12 +775,12 @@ hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is
             e = allow_dynamic_lds(gemm_kernel_v2<true>, kSmem2);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(gemm_kernel_v2<true>, grid, block, kSmem2, s, A.codes, A.scales, A.tensor_scale,
-                               B.codes, B.scales, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n);
+                               B.codes, B.scales, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n, amax_out);
         } else {
             e = allow_dynamic_lds(gemm_kernel_v2<false>, kSmem2);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(gemm_kernel_v2<false>, grid, block, kSmem2, s, A.codes, A.scales, A.tensor_scale,
-                               B.codes, B.scales, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n);
+                               B.codes, B.scales, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n, amax_out);
         }
         return hipGetLastError();
     }
@@ -757,12 +791,12 @@ hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is
         e = allow_dynamic_lds(gemm_kernel<true>, smem);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(gemm_kernel<true>, grid, block, smem, s, A.codes, A.scales, A.tensor_scale, B.codes,
-                           B.scales, B.tensor_scale, M, N, K, C, ldc, (int)tiles_n);
+                           B.scales, B.tensor_scale, M, N, K, C, ldc, (int)tiles_n, amax_out);
     } else {
         e = allow_dynamic_lds(gemm_kernel<false>, smem);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(gemm_kernel<false>, grid, block, smem, s, A.codes, A.scales, A.tensor_scale, B.codes,
-                           B.scales, B.tensor_scale, M, N, K, C, ldc, (int)tiles_n);
+                           B.scales, B.tensor_scale, M, N, K, C, ldc, (int)tiles_n, amax_out);
     }
     return hipGetLastError();
 }

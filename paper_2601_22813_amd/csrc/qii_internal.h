@@ -67,8 +67,9 @@ hipError_t launch_quantize_cols(const QuantizeArgs &a, hipStream_t s);
 // ws (nullable): gemm_workspace_bytes(M, N, K) bytes, 16-byte aligned, for the re-tiled scale
 // bytes of the fast kernel; without it a slower kernel reads the row-major scales directly
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+// amax_c (nullable): device float that receives max |C| over the values as stored
 hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is_bf16, int64_t ldc,
-                       void *ws, size_t ws_bytes, hipStream_t s);
+                       float *amax_c, void *ws, size_t ws_bytes, hipStream_t s);
 
 // sweeps of the hardware conversions and short division sequences against their value-space
 // rules; counts[0..7] (device) receive the numbers of mismatches (selftest.hip)

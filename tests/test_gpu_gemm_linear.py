@@ -219,3 +219,55 @@ def test_layer_passes_replay_from_a_hip_graph(oracle):
         got = (Y, dX, dW, Xq.codes, Xq.scales, Wq.codes, Wq.scales)
         for k, (g, w_) in enumerate(zip(got, want)):
             assert torch.equal(g, w_), f"replay with seed {seed}: tensor {k} differs from the eager run"
+
+
+@pytest.mark.parametrize("M,N,K,use_ws", [(300, 200, 160, False), (513, 257, 384, False), (300, 520, 512, True),
+                                          (1024, 768, 2048, True), (64, 70, 48, False), (256, 256, 256, True)])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_gemm_emits_the_abs_max_of_what_it_stores(oracle, M, N, K, use_ws, dtype):
+    """max |C| out of the GEMM's epilogue (the abs-max the consumer's quantizer needs, App. D): it
+    must equal the maximum over the stored matrix bit for bit, in all three kernels, and entries of
+    the padded tile beyond M x N must not leak into it.  K = 48 also covers an inner dimension that
+    is a multiple of 16 but not of 32."""
+    rng = np.random.default_rng(M * 7 + N + K)
+    a = (rng.standard_t(3, size=(M, K)) * 0.1).astype(np.float32)
+    b = rng.standard_normal((N, K)).astype(np.float32)
+    qa = oracle.quantize(a, oracle.RTN, rht_group=0)
+    qb = oracle.quantize(b, oracle.RTN, rht_group=0)
+    C = torch.full((M, N + 5), float("nan"), dtype=dtype, device="cuda")[:, :N]
+    amax = torch.full((1,), -1.0, dtype=torch.float32, device="cuda")
+    w = ws(qii.qii_gemm_workspace_bytes(M, N, K)) if use_ws else None
+    if w is not None:
+        w.fill_(0x7E)     # stale scale bytes (448) for the padded rows of the re-tiled copy
+    qii.qii_gemm_nvfp4_amax(nv_to_dev(qa), nv_to_dev(qb), C, amax, w)
+    torch.cuda.synchronize()
+    ref, absum = oracle.gemm(qa, qb, with_abs=True)
+    check(C.float().cpu().numpy().astype(np.float64), ref, absum, dtype == torch.bfloat16)
+    assert amax.item() == C.float().abs().max().item()
+
+
+def test_forward_pass_hands_its_abs_max_to_the_next_layer(oracle):
+    """Two layers in a row: the first emits max|Y| from its GEMM, the second takes it as the abs-max
+    of its input and skips that pass.  Its saved tensors must equal the oracle's quantization of the
+    very bytes of Y."""
+    T, d0, d1, d2 = 384, 256, 512, 128
+    Xb, W1b, _ = synth.linear_layer_bf16(T, d0, d1, seed=5)
+    W2b = synth.normal_bf16((d2, d1), 0.02, seed=9)
+    X, W1, W2 = to_dev(Xb), to_dev(W1b), to_dev(W2b)
+    for mode in (qii.RTN, qii.RTN_46):
+        Y1 = torch.empty((T, d1), dtype=torch.bfloat16, device="cuda")
+        Y2 = torch.empty((T, d2), dtype=torch.bfloat16, device="cuda")
+        amax_y = torch.full((1,), -1.0, dtype=torch.float32, device="cuda")
+        Xq1, Wq1 = qii.NVFP4Tensor.empty(T, d0), qii.NVFP4Tensor.empty(d1, d0)
+        Xq2, Wq2 = qii.NVFP4Tensor.empty(T, d1), qii.NVFP4Tensor.empty(d2, d1)
+        qii.qii_linear_fwd_amax(X, W1, mode, Y1, amax_y, Xq1, Wq1, ws(qii.qii_linear_fwd_workspace_bytes(T, d0, d1)))
+        qii.qii_linear_fwd_amax(Y1, W2, mode, Y2, None, Xq2, Wq2, ws(qii.qii_linear_fwd_workspace_bytes(T, d1, d2)),
+                                amax_x=amax_y)
+        torch.cuda.synchronize()
+        assert amax_y.item() == Y1.float().abs().max().item()
+        y1_bits = Y1.view(torch.int16).cpu().numpy().view(np.uint16)
+        oXq2, oWq2 = oracle.linear_fwd(y1_bits, W2b, mode=mode)
+        assert_nv_equal(Xq2, oXq2, f"second layer's saved input, mode {mode}")
+        assert_nv_equal(Wq2, oWq2, f"second layer's saved weight, mode {mode}")
+        ref, absum = oracle.gemm(oXq2, oWq2, with_abs=True)
+        check(bf16_to_f64(Y2), ref, absum, True)
