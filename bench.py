@@ -189,11 +189,12 @@ def main() -> int:
         qii.qii_absmax(w_, False, 0, 0, aw_)
     ws_b = torch.empty(qii.qii_linear_bwd_mode_workspace_bytes(T, d_in, d_out, qii.MS_EDEN_PH), dtype=torch.uint8, device=dev)
     ws_ph = torch.empty(qii.qii_quantize_posthoc_workspace_bytes(max(R, C), max(R, C)), dtype=torch.uint8, device=dev)
+    ws_pair = torch.empty(qii.qii_quantize_pair_workspace_bytes(R, C, qii.MS_EDEN_PH), dtype=torch.uint8, device=dev)
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
     names = ["single_rows", "single_cols", "absmax_rows", "quant_rows", "absmax_cols", "quant_cols",
-             "posthoc_rows", "posthoc_cols", "linear_fwd", "linear_bwd", "linear_fwd_46", "linear_bwd_ph",
-             "linear_fwd_46_amax"]
+             "posthoc_rows", "posthoc_cols", "pair_ph", "pair_alg1", "linear_fwd", "linear_bwd", "linear_fwd_46",
+             "linear_bwd_ph", "linear_fwd_46_amax"]
     kernel_ms = {k: [] for k in names}
 
     do_v = args.parts in ("all", "value", "quantize")     # the two single-pass launches behind `value`
@@ -228,25 +229,33 @@ def main() -> int:
         if do_q:
             qii.qii_quantize_nvfp4(xs[b], True, qii.MS_EDEN_PH, 128, 0, i, None, out_cols, ws_ph)
         e[8].record()
+        # both orientations of one tensor from a single read (the backward pass's Q(E), Q(E^T)): the
+        # post hoc form (one heavy pass + two scales passes) and Algorithm 1 (two abs-max passes + one read)
+        if do_q:
+            qii.qii_quantize_pair_nvfp4(xs[c], qii.MS_EDEN_PH, 0, i, 1, i + 1, out_rows, out_cols, ws_pair)
+        e[9].record()
+        if do_q:
+            qii.qii_quantize_pair_nvfp4(xs[d], qii.MS_EDEN, 0, i, 1, i + 1, out_rows, out_cols, ws_pair)
+        e[10].record()
         j = i % 3
         if do_l:
             qii.qii_linear_fwd(Xs[j], Ws[j], Y, Xq, Wq, ws_f)
-        e[9].record()
+        e[11].record()
         if do_l:
             qii.qii_linear_bwd(Es[j], Xq, Wq, i, dX, dW, ws_b)
-        e[10].record()
+        e[12].record()
         # the layer as the paper runs it: 4/6 on the forward pass, post hoc range alignment on the backward pass
         k = (i + 1) % 3
         if do_l:
             qii.qii_linear_fwd_mode(Xs[k], Ws[k], qii.RTN_46, Y, Xq, Wq, ws_f)
-        e[11].record()
+        e[13].record()
         if do_l:
             qii.qii_linear_bwd_mode(Es[k], Xq, Wq, i, qii.MS_EDEN_PH, dX, dW, ws_b)
-        e[12].record()
+        e[14].record()
         # the same forward pass when the caller brings max|X| and max|W| (App. D assumes so)
         if do_l:
             qii.qii_linear_fwd_mode(Xs[k], Ws[k], qii.RTN_46, Y, Xq, Wq, ws_f, amax_x=amax_X[k], amax_w=amax_W[k])
-        e[13].record()
+        e[15].record()
         return e if record else None
 
     if args.copy_calibration:
@@ -327,6 +336,10 @@ def main() -> int:
                          "bytes_per_element": BYTES_PER_ELEM_POSTHOC,
                          "GBps": round(bytes_ph / (ms_ph * 1e-3) / 1e9, 1),
                          "speedup_over_two_pass": round(ms_a2 / ms_ph, 3)},
+            # Q(x) and Q(x^T) from one read of x (qii_quantize_pair_nvfp4), against the two separate calls above
+            "both_orientations_one_read": {
+                "post_hoc_ms": round(avg["pair_ph"], 4), "speedup_over_separate_post_hoc": round(ms_ph / avg["pair_ph"], 3),
+                "algorithm1_ms": round(avg["pair_alg1"], 4), "speedup_over_separate_two_pass": round(ms_a2 / avg["pair_alg1"], 3)},
         },
         "linear_fwd_bwd": {
             "value": round(tflops, 1), "unit": "TFLOP/s", "ms": round(lin_ms, 4),

@@ -131,6 +131,22 @@ qii_status qii_quantize_nvfp4(const void *x, qii_dtype dt, int64_t rows, int64_t
                               uint64_t seed_sr, const float *amax_in, const qii_nvfp4 *out,
                               void *ws, size_t ws_bytes, void *stream);
 
+/* Both orientations of one tensor from a single read (Sec. 5, backward pass: the output gradient
+ * E is needed as Q(E) with groups along d_out and as Q(E^T) with groups along the tokens; Sec. 7
+ * describes the backward quantizers as fused kernels around one load of their operand):
+ *   out_rows = Q(x)    rows x cols, rotation seed_rht_rows, rounding seed_sr_rows
+ *   out_cols = Q(x^T)  cols x rows, rotation seed_rht_cols, rounding seed_sr_cols
+ * with rotation groups of 128 on both (rows and cols must be multiples of 128), mode QII_MS_EDEN
+ * (Algorithm 1: two abs-max passes, then one read for both outputs) or QII_MS_EDEN_PH (one heavy
+ * pass that reads x once, then the two scales-only passes).  The bytes are those of the two
+ * qii_quantize_nvfp4 calls with the same seeds.  bf16 sources with 16-byte aligned rows take the
+ * single-read kernel; anything else falls back to the two separate quantizers.  ws:
+ * qii_quantize_pair_workspace_bytes(rows, cols, mode) bytes, 256-byte aligned.               */
+qii_status qii_quantize_pair_nvfp4(const void *x, qii_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                                   qii_mode mode, uint64_t seed_rht_rows, uint64_t seed_sr_rows,
+                                   uint64_t seed_rht_cols, uint64_t seed_sr_cols, const qii_nvfp4 *out_rows,
+                                   const qii_nvfp4 *out_cols, void *ws, size_t ws_bytes, void *stream);
+
 /* qii_quantize_nvfp4 for callers that cannot allocate device memory or bring a workspace (code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the abs-max
  * scalar and, for QII_MS_EDEN_PH, the per-group f32 buffer live in a buffer of 16 MiB + 16 KiB
@@ -225,6 +241,7 @@ qii_status qii_linear_bwd_mode(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq
 size_t qii_quantize_workspace_bytes(void);
 /* for mode QII_MS_EDEN_PH; rows x cols is the shape of the quantized output            */
 size_t qii_quantize_posthoc_workspace_bytes(int64_t rows, int64_t cols);
+size_t qii_quantize_pair_workspace_bytes(int64_t rows, int64_t cols, qii_mode mode);
 size_t qii_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 size_t qii_linear_fwd_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out);
 size_t qii_linear_bwd_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out);

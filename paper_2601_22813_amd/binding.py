@@ -26,6 +26,7 @@ EXPORTS = [
     "qii_gemm_workspace_bytes", "qii_linear_fwd_workspace_bytes", "qii_linear_bwd_workspace_bytes",
     "qii_derive_seed", "qii_status_string", "qii_last_error", "qii_version", "qii_selftest_conversions",
     "qii_quantize_nvfp4_noalloc", "qii_gemm_nvfp4_amax", "qii_linear_fwd_amax",
+    "qii_quantize_pair_nvfp4", "qii_quantize_pair_workspace_bytes",
 ]
 
 
@@ -57,6 +58,10 @@ def lib() -> ctypes.CDLL:
                                          u64, vp, nv, vp, sz, vp]
         L.qii_quantize_nvfp4_noalloc.argtypes = [vp, c.c_int, i64, i64, i64, c.c_int, c.c_int, c.c_int, u64, u64, nv, vp]
         L.qii_quantize_nvfp4_noalloc.restype = c.c_int
+        L.qii_quantize_pair_nvfp4.argtypes = [vp, c.c_int, i64, i64, i64, c.c_int, u64, u64, u64, u64, nv, nv, vp, sz, vp]
+        L.qii_quantize_pair_nvfp4.restype = c.c_int
+        L.qii_quantize_pair_workspace_bytes.argtypes = [i64, i64, c.c_int]
+        L.qii_quantize_pair_workspace_bytes.restype = sz
         L.qii_requantize_nvfp4.argtypes = [nv, c.c_int, c.c_int, c.c_int, u64, u64, vp, nv, vp, sz, vp]
         L.qii_dequantize_nvfp4.argtypes = [nv, vp, vp]
         L.qii_gemm_nvfp4.argtypes = [nv, nv, vp, c.c_int, i64, vp, sz, vp]
@@ -219,6 +224,20 @@ def qii_quantize_nvfp4_noalloc(x: torch.Tensor, transpose: bool, mode: int, rht_
     s = out.c_struct()
     _check(lib().qii_quantize_nvfp4_noalloc(x.data_ptr(), _dt(x), rows, cols, x.stride(0), int(transpose), mode,
                                             rht_group, seed_rht, seed_sr, ctypes.byref(s), _stream()))
+
+
+def qii_quantize_pair_workspace_bytes(rows: int, cols: int, mode: int) -> int:
+    return int(lib().qii_quantize_pair_workspace_bytes(rows, cols, mode))
+
+
+def qii_quantize_pair_nvfp4(x: torch.Tensor, mode: int, seed_rht_rows: int, seed_sr_rows: int, seed_rht_cols: int,
+                            seed_sr_cols: int, out_rows: NVFP4Tensor, out_cols: NVFP4Tensor, ws: torch.Tensor):
+    _rows_contig(x)
+    rows, cols = x.shape
+    sr, sc = out_rows.c_struct(), out_cols.c_struct()
+    _check(lib().qii_quantize_pair_nvfp4(x.data_ptr(), _dt(x), rows, cols, x.stride(0), mode, seed_rht_rows, seed_sr_rows,
+                                         seed_rht_cols, seed_sr_cols, ctypes.byref(sr), ctypes.byref(sc), ws.data_ptr(),
+                                         ws.numel() * ws.element_size(), _stream()))
 
 
 def qii_requantize_nvfp4(inp: NVFP4Tensor, transpose: bool, mode: int, rht_group: int, seed_rht: int,

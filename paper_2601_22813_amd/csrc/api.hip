@@ -195,15 +195,17 @@ qii_status requantize_saved(const qii_nvfp4 *in, int transpose, qii_mode mode, i
     return quantize_source(src, R, C, mode, rht_group, seed_rht, seed_sr, nullptr, out, slot, tbuf, s, slot_zeroed);
 }
 
-// quantizer workspace of a backward pass: four abs-max slots plus, for the post hoc scheme, one f32
-// per group of the largest of its four tensors (T x d_out and d_in x max(d_out, T))
+// quantizer workspace of a backward pass: four abs-max areas plus, for the post hoc scheme, the
+// per-group f32 buffers (two of T x d_out / 16, or one of d_in x max(d_out, T) / 16 if that is larger)
 size_t posthoc_region_bytes(int64_t T, int64_t d_in, int64_t d_out, qii_mode mode)
 {
     if (mode != QII_MS_EDEN_PH) return 4 * kSlot;
-    int64_t groups = T * d_out / 16;
-    if (d_in * d_out / 16 > groups) groups = d_in * d_out / 16;
+    // Q(E) and Q(E^T) are produced together and need a buffer each; the two re-quantizations reuse the first
+    const size_t e_bytes = 2 * align_up((size_t)(T * (d_out / 16)) * 4);
+    int64_t groups = d_in * d_out / 16;
     if (d_in * T / 16 > groups) groups = d_in * T / 16;
-    return 4 * kRegion + align_up((size_t)groups * 4);
+    const size_t r_bytes = align_up((size_t)groups * 4);
+    return 4 * kRegion + (e_bytes > r_bytes ? e_bytes : r_bytes);
 }
 
 size_t nvfp4_bytes(int64_t rows, int64_t cols)
@@ -251,6 +253,61 @@ qii_status scratch_address(void **out)
     }
     *out = g_scratch_ptr[dev];
     return QII_OK;
+}
+
+// Q(x) and Q(x^T) of one dense matrix (MS-EDEN or its post hoc form, rotation over 128).  slots:
+// two abs-max areas (256 bytes each, or two 16 KiB regions for the post hoc scheme), tbufs: two
+// per-group buffers (post hoc scheme).  Uses the single-read kernel where it applies, else the two
+// quantizers one after the other.  All arguments have been validated by the caller.
+qii_status quantize_pair(const qii::Source &src, int64_t rows, int64_t cols, qii_mode mode, uint64_t seed_rht_r,
+                         uint64_t seed_sr_r, uint64_t seed_rht_c, uint64_t seed_sr_c, const qii_nvfp4 *out_r,
+                         const qii_nvfp4 *out_c, float *slot_r, float *slot_c, float *tbuf_r, float *tbuf_c,
+                         hipStream_t s, bool slots_zeroed)
+{
+    qii::Source srct = src;
+    srct.transpose = 1;
+    if (rows * cols == 0 || !qii::pair_kernel_applies(src, rows, cols)) {
+        qii_status st = quantize_source(src, rows, cols, mode, 128, seed_rht_r, seed_sr_r, nullptr, out_r, slot_r, tbuf_r, s, slots_zeroed);
+        if (st != QII_OK) return st;
+        return quantize_source(srct, cols, rows, mode, 128, seed_rht_c, seed_sr_c, nullptr, out_c, slot_c, tbuf_c, s, slots_zeroed);
+    }
+    const bool ph = mode == QII_MS_EDEN_PH;
+    hipError_t e = hipSuccess;
+    if (!slots_zeroed) {
+        e = ph ? qii::launch_fill_u32(reinterpret_cast<uint32_t *>(slot_r), 0u, (int)qii::kAmaxSpread, (int)qii::kAmaxStrideWords, s)
+               : qii::launch_fill_u32(reinterpret_cast<uint32_t *>(slot_r), 0u, 1, 1, s);
+        if (e != hipSuccess) return hip_fail(e, "fill");
+        e = ph ? qii::launch_fill_u32(reinterpret_cast<uint32_t *>(slot_c), 0u, (int)qii::kAmaxSpread, (int)qii::kAmaxStrideWords, s)
+               : qii::launch_fill_u32(reinterpret_cast<uint32_t *>(slot_c), 0u, 1, 1, s);
+        if (e != hipSuccess) return hip_fail(e, "fill");
+    }
+    if (!ph) {   // Algorithm 1 needs both rotated maxima before any scale: two abs-max passes, then one read for both outputs
+        e = qii::launch_absmax(src, rows, cols, 1, seed_rht_r, slot_r, s);
+        if (e != hipSuccess) return hip_fail(e, "absmax");
+        e = qii::launch_absmax(srct, cols, rows, 1, seed_rht_c, slot_c, s);
+        if (e != hipSuccess) return hip_fail(e, "absmax");
+    }
+    qii::PairQuantizeArgs p;
+    p.src = src; p.rows = rows; p.cols = cols; p.mode = (int)mode;
+    p.r = {seed_rht_r, seed_sr_r, ph ? nullptr : slot_r, out_r->codes, out_r->scales, out_r->tensor_scale, tbuf_r,
+           ph ? reinterpret_cast<uint32_t *>(slot_r) : nullptr};
+    p.c = {seed_rht_c, seed_sr_c, ph ? nullptr : slot_c, out_c->codes, out_c->scales, out_c->tensor_scale, tbuf_c,
+           ph ? reinterpret_cast<uint32_t *>(slot_c) : nullptr};
+    e = qii::launch_quantize_pair(p, s);
+    if (e != hipSuccess) return hip_fail(e, "quantize (both orientations)");
+    if (ph) {
+        e = qii::launch_posthoc_scales(tbuf_r, slot_r, (int)qii::kAmaxSpread, rows, cols, seed_sr_r, out_r->scales, out_r->tensor_scale, s);
+        if (e != hipSuccess) return hip_fail(e, "quantize (scales pass)");
+        e = qii::launch_posthoc_scales(tbuf_c, slot_c, (int)qii::kAmaxSpread, cols, rows, seed_sr_c, out_c->scales, out_c->tensor_scale, s);
+        if (e != hipSuccess) return hip_fail(e, "quantize (scales pass)");
+    }
+    return QII_OK;
+}
+
+size_t pair_ws_bytes(int64_t rows, int64_t cols, qii_mode mode)
+{
+    if (mode != QII_MS_EDEN_PH) return 2 * kSlot;
+    return 2 * kRegion + 2 * align_up((size_t)(rows * (cols / 16)) * 4);
 }
 
 // every argument rule of the GEMM, checked before anything is launched
@@ -397,6 +454,42 @@ qii_status qii_quantize_nvfp4_noalloc(const void *x, qii_dtype dt, int64_t rows,
                            (hipStream_t)stream);
 }
 
+size_t qii_quantize_pair_workspace_bytes(int64_t rows, int64_t cols, qii_mode mode) { return pair_ws_bytes(rows, cols, mode); }
+
+qii_status qii_quantize_pair_nvfp4(const void *x, qii_dtype dt, int64_t rows, int64_t cols, int64_t ld, qii_mode mode,
+                                   uint64_t seed_rht_rows, uint64_t seed_sr_rows, uint64_t seed_rht_cols,
+                                   uint64_t seed_sr_cols, const qii_nvfp4 *out_rows, const qii_nvfp4 *out_cols,
+                                   void *ws, size_t ws_bytes, void *stream)
+{
+    if (mode != QII_MS_EDEN && mode != QII_MS_EDEN_PH)
+        return fail(QII_INVALID_ARG, "qii_quantize_pair_nvfp4 takes QII_MS_EDEN or QII_MS_EDEN_PH, not mode %d", (int)mode);
+    qii::Source src, srct;
+    int64_t R, C;
+    qii_status st = dense_source(x, dt, rows, cols, ld, 0, 128, &src, &R, &C);
+    if (st != QII_OK) return st;
+    st = dense_source(x, dt, rows, cols, ld, 1, 128, &srct, &R, &C);
+    if (st != QII_OK) return st;
+    st = check_nvfp4(out_rows, "out_rows");
+    if (st != QII_OK) return st;
+    st = check_nvfp4(out_cols, "out_cols");
+    if (st != QII_OK) return st;
+    if (out_rows->rows != rows || out_rows->cols != cols || out_cols->rows != cols || out_cols->cols != rows)
+        return fail(QII_BAD_SHAPE, "out_rows must be %lld x %lld and out_cols %lld x %lld", (long long)rows,
+                    (long long)cols, (long long)cols, (long long)rows);
+    const size_t need = pair_ws_bytes(rows, cols, mode);
+    if (!ws || ws_bytes < need || !aligned(ws, kSlot))
+        return fail(QII_WORKSPACE_TOO_SMALL, "qii_quantize_pair_nvfp4 needs %zu bytes of 256-byte aligned workspace", need);
+    if (rows * cols == 0) return QII_OK;
+    uint8_t *p = reinterpret_cast<uint8_t *>(ws);
+    const bool ph = mode == QII_MS_EDEN_PH;
+    const size_t area = ph ? kRegion : kSlot, tb = align_up((size_t)(rows * (cols / 16)) * 4);
+    float *slot_r = reinterpret_cast<float *>(p), *slot_c = reinterpret_cast<float *>(p + area);
+    float *tbuf_r = ph ? reinterpret_cast<float *>(p + 2 * area) : nullptr;
+    float *tbuf_c = ph ? reinterpret_cast<float *>(p + 2 * area + tb) : nullptr;
+    return quantize_pair(src, rows, cols, mode, seed_rht_rows, seed_sr_rows, seed_rht_cols, seed_sr_cols, out_rows,
+                         out_cols, slot_r, slot_c, tbuf_r, tbuf_c, (hipStream_t)stream, false);
+}
+
 qii_status qii_requantize_nvfp4(const qii_nvfp4 *in, int transpose, qii_mode mode, int rht_group,
                                 uint64_t seed_rht, uint64_t seed_sr, const float *amax_in,
                                 const qii_nvfp4 *out, void *ws, size_t ws_bytes, void *stream)
@@ -540,6 +633,7 @@ qii_status qii_linear_bwd_mode(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq
     const bool ph = mode == QII_MS_EDEN_PH;
     const int slot_words = (int)((ph ? kRegion : kSlot) / 4);   // distance between the four tensors' abs-max areas
     float *tbuf = ph ? reinterpret_cast<float *>(p + 4 * kRegion) : nullptr;
+    float *tbuf2 = ph ? tbuf + align_up((size_t)(T * (d_out / 16)) * 4) / 4 : nullptr;   // second buffer for Q(E^T)
     p += posthoc_region_bytes(T, d_in, d_out, mode);
     qii_nvfp4 Eq = carve_nvfp4(p, T, d_out);
     qii_nvfp4 WTq = carve_nvfp4(p, d_in, d_out);
@@ -554,16 +648,17 @@ qii_status qii_linear_bwd_mode(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq
     hipError_t e = ph ? qii::launch_fill_u32(reinterpret_cast<uint32_t *>(slots), 0u, 4 * (int)qii::kAmaxSpread, (int)qii::kAmaxStrideWords, s)
                       : qii::launch_fill_u32(reinterpret_cast<uint32_t *>(slots), 0u, 4, slot_words, s);
     if (e != hipSuccess) return hip_fail(e, "fill");
-    // dX = Q(E) Q(W^T)^T : rotation sd[0] on the inner dimension d_out
-    st = quantize_dense(dY, dt, T, d_out, d_out, 0, mode, 128, sd[0], sd[2], nullptr, &Eq, slots, tbuf, s, true);
+    // Q(E) and Q(E^T) from one read of dY: rotation sd[0] along d_out for the dX GEMM, sd[1] along
+    // the tokens for the dW GEMM (their abs-max areas are the first and third of the four)
+    st = quantize_pair(se, T, d_out, mode, sd[0], sd[2], sd[1], sd[4], &Eq, &ETq, slots, slots + 2 * slot_words, tbuf,
+                       tbuf2, s, true);
     if (st != QII_OK) return st;
+    // dX = Q(E) Q(W^T)^T : inner dimension d_out
     st = requantize_saved(Wq, 1, mode, 128, sd[0], sd[3], &WTq, slots + slot_words, tbuf, s, true);
     if (st != QII_OK) return st;
     st = qii_gemm_nvfp4(&Eq, &WTq, dX, g_dt, d_in, gws, gws_bytes, stream);
     if (st != QII_OK) return st;
-    // dW = Q(E^T) Q(X^T)^T : rotation sd[1] on the inner dimension T
-    st = quantize_dense(dY, dt, T, d_out, d_out, 1, mode, 128, sd[1], sd[4], nullptr, &ETq, slots + 2 * slot_words, tbuf, s, true);
-    if (st != QII_OK) return st;
+    // dW = Q(E^T) Q(X^T)^T : inner dimension T
     st = requantize_saved(Xq, 1, mode, 128, sd[1], sd[5], &XTq, slots + 3 * slot_words, tbuf, s, true);
     if (st != QII_OK) return st;
     return qii_gemm_nvfp4(&ETq, &XTq, dW, g_dt, d_in, gws, gws_bytes, stream);

@@ -40,6 +40,26 @@ struct QuantizeArgs {
     uint32_t *amax_accum;
 };
 
+// One read of a dense matrix producing Q(x) (side r: rows x cols) and Q(x^T) (side c: cols x rows),
+// mode QII_MS_EDEN (amax of each rotated tensor supplied) or QII_MS_EDEN_PH (heavy pass: tbuf and
+// amax_accum as in QuantizeArgs, per side); quantize_pair.hip
+struct PairQuantizeArgs {
+    Source src;
+    int64_t rows, cols;
+    int mode;
+    struct Side {
+        uint64_t seed_rht, seed_sr;
+        const float *amax;
+        uint8_t *codes;
+        uint8_t *scales;
+        float *tensor_scale;
+        float *tbuf;
+        uint32_t *amax_accum;
+    } r, c;
+};
+bool pair_kernel_applies(const Source &src, int64_t rows, int64_t cols);
+hipError_t launch_quantize_pair(const PairQuantizeArgs &p, hipStream_t s);
+
 // p[i * stride_words] = v for i < count (count <= 256); a kernel, not a memset node, so that the
 // calls can be captured in a HIP graph
 hipError_t launch_fill_u32(uint32_t *p, uint32_t v, int count, int stride_words, hipStream_t s);

@@ -22,11 +22,10 @@
 #include "qii_device.h"
 #include "qii_internal.h"
 #include "quantize_core.h"
+#include "quantize_lanes.h"
 
 namespace qii {
 namespace {
-
-constexpr float kInvSqrt128 = 0x1.6a09e6p-4f;  // binary32 nearest to 2^-3.5
 
 struct ColsArgs {
     const void *x;       // f32 / bf16 data, or the FP4 codes of an NVFP4 source
@@ -127,92 +126,6 @@ __device__ __forceinline__ void load_quarter_chunk(float v[2][32], const ColsArg
     RawCols<kSrc> r;
     load_quarter_chunk_raw<kSrc>(r, a, chunk, j0, q);
     unpack_quarter_chunk<kSrc, kRht>(v, r, a, q);
-}
-
-// one cross-lane butterfly stage on 16 registers: v[k] += partner(v[k]) * s
-#define QII_PAIR_STAGE(NAME, CTRL)                                                                \
-    __device__ __forceinline__ void NAME(float *v, float s)                                       \
-    {                                                                                             \
-        asm volatile("s_nop 1\n"                                                                  \
-                     "v_fmac_f32_dpp %0, %0, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
-                     "v_fmac_f32_dpp %1, %1, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
-                     "v_fmac_f32_dpp %2, %2, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
-                     "v_fmac_f32_dpp %3, %3, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
-                     "v_fmac_f32_dpp %4, %4, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
-                     "v_fmac_f32_dpp %5, %5, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
-                     "v_fmac_f32_dpp %6, %6, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
-                     "v_fmac_f32_dpp %7, %7, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
-                     "v_fmac_f32_dpp %8, %8, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
-                     "v_fmac_f32_dpp %9, %9, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"           \
-                     "v_fmac_f32_dpp %10, %10, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"         \
-                     "v_fmac_f32_dpp %11, %11, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"         \
-                     "v_fmac_f32_dpp %12, %12, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"         \
-                     "v_fmac_f32_dpp %13, %13, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"         \
-                     "v_fmac_f32_dpp %14, %14, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"         \
-                     "v_fmac_f32_dpp %15, %15, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"         \
-                     : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]),    \
-                       "+v"(v[6]), "+v"(v[7]), "+v"(v[8]), "+v"(v[9]), "+v"(v[10]), "+v"(v[11]),  \
-                       "+v"(v[12]), "+v"(v[13]), "+v"(v[14]), "+v"(v[15])                         \
-                     : "v"(s));                                                                   \
-    }
-QII_PAIR_STAGE(dpp_xor1_stage16, "quad_perm:[1,0,3,2]")
-QII_PAIR_STAGE(dpp_xor2_stage16, "quad_perm:[2,3,0,1]")
-#undef QII_PAIR_STAGE
-
-// y = H v / sqrt(128) over the 128 values of one column held by a lane quad: stages over
-// index bits 0..4 in-lane, bits 5 and 6 across the quad, then the scaling (kScale = false: left
-// to the caller; the abs-max pass scales its maximum once, which is the same number because
-// rounding is monotone and symmetric)
-template <bool kScale = true>
-__device__ __forceinline__ void fwht128_quad(float v[32], int q)
-{
-#pragma unroll
-    for (int len = 1; len < 32; len <<= 1)
-#pragma unroll
-        for (int i = 0; i < 32; ++i)
-            if ((i & len) == 0) {
-                const float x = v[i], y = v[i + len];
-                v[i] = x + y;
-                v[i + len] = x - y;
-            }
-    const float s5 = (q & 1) ? -1.0f : 1.0f, s6 = (q & 2) ? -1.0f : 1.0f;
-    dpp_xor1_stage16(v, s5);
-    dpp_xor1_stage16(v + 16, s5);
-    dpp_xor2_stage16(v, s6);
-    dpp_xor2_stage16(v + 16, s6);
-    const float c = (q == 1 || q == 2) ? -kInvSqrt128 : kInvSqrt128;
-    if (kScale)
-#pragma unroll
-        for (int i = 0; i < 32; ++i) v[i] = __builtin_fmaf(v[i], c, 0.0f);  // +0 for exact zeros
-}
-
-// draws of this lane's groups: draw[e][h] for column j0+e, column group 8*chunk + 2q + h.
-// Lane o of an octet (the 8 lanes that own columns 4j..4j+3) computes the call of column
-// group 8*chunk + o; a lane then takes the words of its two columns from its two calls.
-__device__ __forceinline__ void octet_draws(uint32_t draw[2][2], uint64_t seed_sr, int64_t chunk, int64_t j0, int q)
-{
-    const int lane = threadIdx.x & 63, o = lane & 7, upper = (lane >> 2) & 1;   // upper: columns 2,3 of the four
-    const U4 w = philox_seeded(seed_sr, (uint32_t)(chunk * 8 + o), (uint32_t)(j0 >> 2), 0, kStreamScale);
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int src = ((lane & ~7) | (2 * q + h)) * 4;
-        const uint32_t x = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)w.x);
-        const uint32_t y = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)w.y);
-        const uint32_t z = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)w.z);
-        const uint32_t t = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)w.w);
-        draw[0][h] = (upper ? z : x) >> 12;
-        draw[1][h] = (upper ? t : y) >> 12;
-    }
-}
-
-// the 8 scale bytes of a (column, chunk): lane q contributes bytes 2q, 2q+1; lane 0 of the quad
-// ends up with all of them
-__device__ __forceinline__ uint2 gather_quad_scales(uint32_t two_bytes, int q)
-{
-    uint32_t t = two_bytes << (16 * (q & 1));
-    t |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, kDppXor1, 0xF, 0xF, true);
-    const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, kDppXor2, 0xF, 0xF, true);
-    return make_uint2(t, other);
 }
 
 // the four scale groups of a lane (two per column), their stores

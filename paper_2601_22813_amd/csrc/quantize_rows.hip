@@ -7,22 +7,14 @@
 // wide tensors, or, when a row needs fewer than 4 waves, 2 or 4 row quads.  blockIdx.y selects
 // the column range, blockIdx.x the row quads.  The four rows of a quad are requested together
 // (32 B per lane and row) before anything else happens in the kernel.
-//
-// Rotation: butterfly stages over index bits 0..3 are plain in-lane add/sub; stages over
-// bits 4..6 pair lanes (xor 1, xor 2, xor 7 via DPP) with a single v_fmac_f32_dpp:
-// own += partner * (+1 | -1).  The lane whose block has the stage bit set thereby holds
-// -(a - b) instead of (a - b); the sign flip commutes with the later stages and is
-// undone exactly by the sign of the lane's final 2^-3.5 scaling constant.  Only the sign
-// of exactly-zero intermediates can differ from the plain butterfly, and the final
-// fma(v, c, +0) maps every zero result to +0, as the arithmetic contract states.
+// The octet register layout and its rotation are in quantize_lanes.h.
 #include "qii_device.h"
 #include "qii_internal.h"
 #include "quantize_core.h"
+#include "quantize_lanes.h"
 
 namespace qii {
 namespace {
-
-constexpr float kInvSqrt128 = 0x1.6a09e6p-4f;  // binary32 nearest to 2^-3.5
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -44,14 +36,10 @@ struct RowsArgs {
     int gy;              // blocks side by side on a row; the grid is one-dimensional, columns fastest
 };
 
-struct LaneSetup {
-    int blk;              // 16-block of the chunk owned by this lane
+struct LaneSetup : OctetLane {
     int quad;             // this wave's row quad (rows 4 quad .. 4 quad + 3); wave-uniform
     int64_t g;            // scale group within the row
     bool col_ok;
-    float s16, s32, s64;  // +-1 multipliers of the three cross-lane stages
-    float cfin;           // +-2^-3.5
-    uint32_t sign16;      // rotation sign bits of this lane's 16 elements
 };
 
 // kQuadsPerWave: row quads a wave takes (the quantizers: 1; the abs-max pass: 2)
@@ -61,8 +49,7 @@ __device__ __forceinline__ LaneSetup lane_setup(const RowsArgs &a, int64_t G)
     LaneSetup L;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept in a scalar register
-    const int sub = lane & 7;
-    L.blk = (sub & 4) ? (sub ^ 3) : sub;
+    static_cast<OctetLane &>(L) = octet_lane(lane, a.sign);
     // wpr waves side by side, 4 / wpr waves below one another
     const int wcol = wave & (a.wpr - 1), wq = wave / a.wpr, qpb = 4 / a.wpr;
     // consecutive blocks walk along a row first, then down the rows: blocks that run at the same
@@ -72,77 +59,7 @@ __device__ __forceinline__ LaneSetup lane_setup(const RowsArgs &a, int64_t G)
     const int64_t chunk = ((int64_t)by * a.wpr + wcol) * 8 + (lane >> 3);
     L.g = chunk * 8 + L.blk;
     L.col_ok = L.g < G;
-    L.s16 = (L.blk & 1) ? -1.0f : 1.0f;
-    L.s32 = (L.blk & 2) ? -1.0f : 1.0f;
-    L.s64 = (L.blk & 4) ? -1.0f : 1.0f;
-    L.cfin = (__builtin_popcount(L.blk) & 1) ? -kInvSqrt128 : kInvSqrt128;
-    const uint32_t w = (L.blk >> 1) == 0 ? a.sign[0] : (L.blk >> 1) == 1 ? a.sign[1] : (L.blk >> 1) == 2 ? a.sign[2] : a.sign[3];
-    L.sign16 = (w >> ((L.blk & 1) * 16)) & 0xFFFFu;
     return L;
-}
-
-// one cross-lane butterfly stage on all 16 registers: v[k] += partner(v[k]) * s
-#define QII_DPP_STAGE(CTRL)                                                                       \
-    asm volatile("s_nop 1\n"                                                                      \
-                 "v_fmac_f32_dpp %0, %0, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"               \
-                 "v_fmac_f32_dpp %1, %1, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"               \
-                 "v_fmac_f32_dpp %2, %2, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"               \
-                 "v_fmac_f32_dpp %3, %3, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"               \
-                 "v_fmac_f32_dpp %4, %4, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"               \
-                 "v_fmac_f32_dpp %5, %5, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"               \
-                 "v_fmac_f32_dpp %6, %6, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"               \
-                 "v_fmac_f32_dpp %7, %7, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"               \
-                 "v_fmac_f32_dpp %8, %8, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"               \
-                 "v_fmac_f32_dpp %9, %9, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"               \
-                 "v_fmac_f32_dpp %10, %10, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"             \
-                 "v_fmac_f32_dpp %11, %11, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"             \
-                 "v_fmac_f32_dpp %12, %12, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"             \
-                 "v_fmac_f32_dpp %13, %13, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"             \
-                 "v_fmac_f32_dpp %14, %14, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"             \
-                 "v_fmac_f32_dpp %15, %15, %16 " CTRL " row_mask:0xf bank_mask:0xf\n"             \
-                 : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]),        \
-                   "+v"(v[6]), "+v"(v[7]), "+v"(v[8]), "+v"(v[9]), "+v"(v[10]), "+v"(v[11]),      \
-                   "+v"(v[12]), "+v"(v[13]), "+v"(v[14]), "+v"(v[15])                             \
-                 : "v"(s))
-
-__device__ __forceinline__ void dpp_stage_xor1(float v[16], float s) { QII_DPP_STAGE("quad_perm:[1,0,3,2]"); }
-__device__ __forceinline__ void dpp_stage_xor2(float v[16], float s) { QII_DPP_STAGE("quad_perm:[2,3,0,1]"); }
-__device__ __forceinline__ void dpp_stage_xor7(float v[16], float s) { QII_DPP_STAGE("row_half_mirror"); }
-
-// stages over index bits 0..3 (in-lane) then 4..6 (cross-lane), then the scaling
-// kScale = false leaves out the final scaling: for the abs-max pass, where rounding is monotone
-// and symmetric, max |fma(v, c, 0)| = fma(max |v|, |c|, 0), so one scaling of the maximum does
-template <bool kScale = true>
-__device__ __forceinline__ void rht128_lane(float v[16], const LaneSetup &L)
-{
-#pragma unroll
-    for (int len = 1; len < 16; len <<= 1)
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-            if ((i & len) == 0) {
-                const float a = v[i], b = v[i + len];
-                v[i] = a + b;
-                v[i + len] = a - b;
-            }
-    dpp_stage_xor1(v, L.s16);
-    dpp_stage_xor2(v, L.s32);
-    dpp_stage_xor7(v, L.s64);
-    if (kScale)
-#pragma unroll
-        for (int k = 0; k < 16; ++k) v[k] = __builtin_fmaf(v[k], L.cfin, 0.0f);  // +0 for exact zeros
-}
-
-// The 8 scale bytes of an octet's chunk are consecutive in memory; single-byte stores are
-// slow, so they are gathered into the lane holding block 0, which stores them as one 8-byte
-// word: each lane shifts its byte to position (blk mod 4), two DPP ORs merge a quad, and the
-// half-mirror brings the upper quad's word (blocks 4..7 sit in lane 7 - blk) to the lower one.
-__device__ __forceinline__ uint2 gather_scale_bytes(uint32_t b, int blk)
-{
-    uint32_t t = b << (8 * (blk & 3));
-    t |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, kDppXor1, 0xF, 0xF, true);
-    t |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, kDppXor2, 0xF, 0xF, true);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)t, kDppHalfMirror, 0xF, 0xF, true);
-    return make_uint2(t, hi);
 }
 
 // raw row data of one lane: 16 elements
@@ -197,19 +114,6 @@ __device__ __forceinline__ void unpack_signed(const Raw<kBf16> &r, float v[16], 
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j) v[4 * i + j] = u2f(kRht ? (r.q[i][j] ^ mask[4 * i + j]) : r.q[i][j]);
-    }
-}
-
-template <bool kBf16>
-__device__ __forceinline__ void make_masks(uint32_t sign16, uint32_t mask[kBf16 ? 8 : 16])
-{
-    if (kBf16) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            mask[i] = (((sign16 >> (2 * i)) & 1u) << 15) | (((sign16 >> (2 * i + 1)) & 1u) << 31);
-    } else {
-#pragma unroll
-        for (int k = 0; k < 16; ++k) mask[k] = ((sign16 >> k) & 1u) << 31;
     }
 }
 

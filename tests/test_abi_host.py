@@ -112,7 +112,10 @@ def test_new_modes_and_layer_variants_reject_bad_arguments(libqii):
     assert L.qii_linear_bwd_mode(0x1000, 1, ctypes.byref(xq), ctypes.byref(wq), 0, 4, 0x1000, 0x1000, 1, 0x1000, 16, None) == 4
     plain = libqii.qii_linear_bwd_mode_workspace_bytes(256, 128, 384, 2)
     assert plain == libqii.qii_linear_bwd_workspace_bytes(256, 128, 384)
-    assert libqii.qii_linear_bwd_mode_workspace_bytes(256, 128, 384, 4) == plain + 4 * (16384 - 256) + 256 * 384 // 16 * 4
+    # four 16 KiB running-maximum regions instead of four slots, and one per-group f32 buffer for each of Q(E), Q(E^T)
+    assert libqii.qii_linear_bwd_mode_workspace_bytes(256, 128, 384, 4) == plain + 4 * (16384 - 256) + 2 * 256 * 384 // 16 * 4
+    assert libqii.qii_quantize_pair_workspace_bytes(256, 384, 2) == 512
+    assert libqii.qii_quantize_pair_workspace_bytes(256, 384, 4) == 2 * 16384 + 2 * 256 * 384 // 16 * 4
 
 
 def test_layer_passes_validate_everything_before_the_first_launch(libqii):

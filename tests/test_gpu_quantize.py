@@ -200,3 +200,32 @@ def test_leading_dimension_larger_than_the_row(oracle, mode, transpose):
                            ws(qii.qii_quantize_posthoc_workspace_bytes(R, C)))
     ref = oracle.quantize(sub, mode, transpose=transpose, rht_group=128, seed_rht=31, seed_sr=32)
     assert_nv_equal(out, ref, f"strided input, mode {mode}, transpose {transpose}")
+
+
+@pytest.mark.parametrize("mode", [qii.MS_EDEN, qii.MS_EDEN_PH])
+@pytest.mark.parametrize("kind,shape", [("grad_bf16", (256, 384)), ("t3_bf16", (128, 128)), ("t3_bf16", (640, 256)),
+                                        ("normal_f32", (128, 256)), ("grad_bf16", (384, 1152))])
+def test_both_orientations_from_one_read(oracle, mode, kind, shape):
+    """qii_quantize_pair_nvfp4: Q(x) and Q(x^T) of one tensor, each byte for byte what the oracle's
+    separate quantizations give (bf16 sources take the single-read kernel, f32 the fallback)."""
+    x = make(kind, shape, seed=19)
+    rows, cols = shape
+    out_r, out_c = qii.NVFP4Tensor.empty(rows, cols), qii.NVFP4Tensor.empty(cols, rows)
+    for t in (out_r, out_c):
+        t.codes.fill_(0xAB); t.scales.fill_(0xCD)
+    xfull = to_dev(np.concatenate([x, x[:, :128]], axis=1))   # a view with a leading dimension beyond the row
+    xd = xfull[:, :cols]
+    qii.qii_quantize_pair_nvfp4(xd, mode, 101, 102, 103, 104, out_r, out_c,
+                                ws(qii.qii_quantize_pair_workspace_bytes(rows, cols, mode)))
+    assert_nv_equal(out_r, oracle.quantize(x, mode, seed_rht=101, seed_sr=102), f"Q(x), mode {mode} {kind} {shape}")
+    assert_nv_equal(out_c, oracle.quantize(x, mode, transpose=True, seed_rht=103, seed_sr=104), f"Q(x^T), mode {mode} {kind} {shape}")
+
+
+def test_both_orientations_of_a_zero_tensor(oracle):
+    z = np.zeros((128, 256), dtype=np.uint16)
+    for mode in (qii.MS_EDEN, qii.MS_EDEN_PH):
+        out_r, out_c = qii.NVFP4Tensor.empty(128, 256), qii.NVFP4Tensor.empty(256, 128)
+        out_r.codes.fill_(0xAB); out_c.scales.fill_(0xCD)
+        qii.qii_quantize_pair_nvfp4(to_dev(z), mode, 1, 2, 3, 4, out_r, out_c, ws(qii.qii_quantize_pair_workspace_bytes(128, 256, mode)))
+        assert_nv_equal(out_r, oracle.quantize(z, mode, seed_rht=1, seed_sr=2), "zeros, rows")
+        assert_nv_equal(out_c, oracle.quantize(z, mode, transpose=True, seed_rht=3, seed_sr=4), "zeros, columns")
