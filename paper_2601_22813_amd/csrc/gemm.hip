@@ -555,13 +555,30 @@ __device__ __forceinline__ void frag_read_wait(RawFrag4 &f)
                    "+v"(f.sb[0]), "+v"(f.sb[1]), "+v"(f.sb[2]), "+v"(f.sb[3]));
 }
 
-// half of one fragment (4 of its 8 values): two conversions and two packed multiplies
-template <int H>
-__device__ __forceinline__ void dequant_half(half8_t &dst, uint32_t codes, uint32_t scale16x2)
+// The two scale bytes of a lane's 32 elements of K, as two f16 numbers in one register: byte b in
+// f16 position (b << 7) is e4m3 * 2^-8, subnormals included.  v_perm_b32 spreads the bytes to the
+// two halves, one shift moves them to f16 position.
+__device__ __forceinline__ uint32_t scale_halves(uint32_t two_bytes)
 {
-    const half2_t s2 = __builtin_bit_cast(half2_t, scale16x2);
-    const half2_t h0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, 256.0f, 2 * H) * s2;
-    const half2_t h1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, 256.0f, 2 * H + 1) * s2;
+    return __builtin_amdgcn_perm(0u, two_bytes, 0x0C010C00u) << 7;
+}
+
+// half of one fragment (4 of its 8 values): two conversions and two packed multiplies by the f16
+// scale in the low (kHi = 0) or high half of `scales`, taken for both lanes of the packed multiply
+// through the instruction's operand selectors
+template <int H, int kHi>
+__device__ __forceinline__ void dequant_half(half8_t &dst, uint32_t codes, uint32_t scales)
+{
+    const half2_t c0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, 256.0f, 2 * H);
+    const half2_t c1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, 256.0f, 2 * H + 1);
+    half2_t h0, h1;
+    if (kHi) {
+        asm("v_pk_mul_f16 %0, %1, %2 op_sel:[0,1] op_sel_hi:[1,1]" : "=v"(h0) : "v"(c0), "v"(scales));
+        asm("v_pk_mul_f16 %0, %1, %2 op_sel:[0,1] op_sel_hi:[1,1]" : "=v"(h1) : "v"(c1), "v"(scales));
+    } else {
+        asm("v_pk_mul_f16 %0, %1, %2 op_sel_hi:[1,0]" : "=v"(h0) : "v"(c0), "v"(scales));
+        asm("v_pk_mul_f16 %0, %1, %2 op_sel_hi:[1,0]" : "=v"(h1) : "v"(c1), "v"(scales));
+    }
     dst[4 * H] = h0[0]; dst[4 * H + 1] = h0[1]; dst[4 * H + 2] = h1[0]; dst[4 * H + 3] = h1[1];
 }
 
@@ -569,21 +586,27 @@ struct Frags {
     half8_t a[4], b[4];
 };
 
-// chunk I (0..15) of the dequantization of dword D of raw fragments f into nx:
-// fragment I/2 (0..3 = A, 4..7 = B), half I%2
+// chunk I (0..15) of the dequantization of dword D of raw fragments f into nx: fragment I/2
+// (0..3 = A, 4..7 = B), half I%2.  The first chunk that touches a fragment of a freshly read
+// slice (dword 0, half 0) first turns its two scale bytes into the two-f16 form, in place.
 template <int I, int D>
-__device__ __forceinline__ void dequant_chunk(Frags &nx, const RawFrag4 &f)
+__device__ __forceinline__ void dequant_chunk(Frags &nx, RawFrag4 &f)
 {
     constexpr int t = (I >> 1) & 3, h = I & 1;
-    if (I < 8) dequant_half<h>(nx.a[t], f.a[t][D], scale_pair(f.sa[t], D >> 1));
-    else dequant_half<h>(nx.b[t], f.b[t][D], scale_pair(f.sb[t], D >> 1));
+    if (I < 8) {
+        if (D == 0 && h == 0) f.sa[t] = scale_halves(f.sa[t]);
+        dequant_half<h, (D >> 1)>(nx.a[t], f.a[t][D], f.sa[t]);
+    } else {
+        if (D == 0 && h == 0) f.sb[t] = scale_halves(f.sb[t]);
+        dequant_half<h, (D >> 1)>(nx.b[t], f.b[t][D], f.sb[t]);
+    }
 }
 
 // One step = 16 matrix instructions on the fragments in cu, with the fragments of the next
 // step (dword D of f) dequantized into nx in between, one chunk per matrix instruction; the
 // scheduling barriers keep that order, so the conversions run in the shadow of the matrix pipe.
 template <int D>
-__device__ __forceinline__ void mma_step(floatx16 (&acc)[4][4], const Frags &cu, Frags &nx, const RawFrag4 &f)
+__device__ __forceinline__ void mma_step(floatx16 (&acc)[4][4], const Frags &cu, Frags &nx, RawFrag4 &f)
 {
 #define QII_MMA(I)                                                                                          \
     acc[(I) >> 2][(I) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(cu.a[(I) >> 2], cu.b[(I) & 3],          \
@@ -663,10 +686,12 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel_v4(const uint8_t *__restri
     frag_read_wait(fe);   // (waits for both)
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-        dequant_half<0>(x.a[t], fe.a[t][0], scale_pair(fe.sa[t], 0));
-        dequant_half<1>(x.a[t], fe.a[t][0], scale_pair(fe.sa[t], 0));
-        dequant_half<0>(x.b[t], fe.b[t][0], scale_pair(fe.sb[t], 0));
-        dequant_half<1>(x.b[t], fe.b[t][0], scale_pair(fe.sb[t], 0));
+        fe.sa[t] = scale_halves(fe.sa[t]);
+        fe.sb[t] = scale_halves(fe.sb[t]);
+        dequant_half<0, 0>(x.a[t], fe.a[t][0], fe.sa[t]);
+        dequant_half<1, 0>(x.a[t], fe.a[t][0], fe.sa[t]);
+        dequant_half<0, 0>(x.b[t], fe.b[t][0], fe.sb[t]);
+        dequant_half<1, 0>(x.b[t], fe.b[t][0], fe.sb[t]);
     }
     for (int kt = 0; kt < ktiles; ++kt) {
         const uint32_t cur_off = (kt & 1) * kStage4Bytes, nxt_off = ((kt + 1) & 1) * kStage4Bytes;
