@@ -28,6 +28,8 @@ namespace {
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 256, BN = 256, BK = 128;
@@ -325,11 +327,19 @@ __device__ __forceinline__ void store_tile_through_lds(floatx16 (&acc)[4][4], ui
 #pragma unroll
         for (int tj = 0; tj < 4; ++tj)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
+            for (int r = 0; r < 16; r += 2) {
+                // two consecutive rows of one column: one packed conversion (round to nearest even)
                 const int row = 8 * (r >> 2) + 4 * kb + (r & 3), col = tj * 32 + li;
-                const float v = acc[ti][tj][r] * ts;
-                if (kBf16Out) *reinterpret_cast<uint16_t *>(wtile + row * pitch + col * 2) = (uint16_t)f32_to_bf16_bits(v);
-                else *reinterpret_cast<float *>(wtile + row * pitch + col * 4) = v;
+                const float v0 = acc[ti][tj][r] * ts, v1 = acc[ti][tj][r + 1] * ts;
+                if (kBf16Out) {
+                    const bf16x2_t pk = __builtin_convertvector(float2_t{v0, v1}, bf16x2_t);
+                    const uint32_t bits = __builtin_bit_cast(uint32_t, pk);
+                    *reinterpret_cast<uint16_t *>(wtile + row * pitch + col * 2) = (uint16_t)bits;
+                    *reinterpret_cast<uint16_t *>(wtile + (row + 1) * pitch + col * 2) = (uint16_t)(bits >> 16);
+                } else {
+                    *reinterpret_cast<float *>(wtile + row * pitch + col * 4) = v0;
+                    *reinterpret_cast<float *>(wtile + (row + 1) * pitch + col * 4) = v1;
+                }
             }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // wave-local: same wave reads below
 #pragma unroll
