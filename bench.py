@@ -8,11 +8,17 @@ One step = one pass of the whole path over synthetic inputs already resident in 
       input from buffers that are cold in the 256 MiB Infinity Cache;
   A2. the same two quantizations as the literal two kernels of Algorithm 1 (rotated abs-max
       pass, then the quantize pass re-reading the tensor);
+  A3. the same without a supplied abs-max in the two-kernel form of Sec. 7 (post hoc range
+      alignment: heavy pass + scales-only pass), and both orientations from one read;
   B.  one linear layer forward + backward (tokens 16384, d_in 2048 -> d_out 8192, bf16):
-      qii_linear_fwd + qii_linear_bwd = six quantizations and three block-scaled GEMMs.
-`value` is the quantizer's algorithmic GB/s over part A1 (the benchmark's first metric, on
-configs[1]); A2 and the layer's TFLOP/s over part B are reported beside it.  Inputs rotate
-over 768 MiB of distinct buffers so that the Infinity Cache does not serve them.
+      six quantizations and three block-scaled GEMMs, as RTN + Algorithm 1 and as the paper's
+      recipe (4/6 forward, post hoc backward).
+`value` is the quantizer's GB/s over part A3 (the benchmark's first metric on configs[1], run
+the way the paper's layer runs it: nothing supplied, all kernels of the scheme counted); the
+abs-max-supplied and two-pass figures and the layer's TFLOP/s are reported beside it.  Inputs
+rotate over 768 MiB of distinct buffers so that the Infinity Cache does not serve them.
+After the timed steps the larger configurations (T = 32768 decoder linears, the two stress
+shapes, the paper's table of layer shapes) are timed once each and added to the same JSON line.
 Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -32,7 +38,9 @@ ALU_FLOPS_PER_ELEM = 16.5                    # arithmetic the contract asks of M
 VALU_F32_PEAK_TFLOPS = 157.3
 # post hoc scheme: bf16 in, FP4 + one f32 per group out; then that f32 in, E4M3 scale out
 BYTES_PER_ELEM_POSTHOC = 2 + 0.5 + 0.25 + 0.25 + 0.0625
-TRAFFIC_QUANT_ROWS_BYTES = 172_278_000       # measured, see the roofline entry below
+# HBM bytes of one launch of the roofline kernel at 8192 x 8192, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by
+# the same counters' reading of a 512 MiB device copy: the row of that kernel in profiles/value_workload_hbm_traffic.txt
+TRAFFIC_QUANT_ROWS_BYTES = 172_278_000
 
 
 # Weight shapes [d_in, d_out] of Llama-like models (App. D, table of linear shapes), 8 x 2048 tokens.
@@ -42,6 +50,66 @@ PAPER_SHAPES = {
     "7B": {"QKV": (4096, 12288), "Out": (4096, 4096), "UpGate": (4096, 22016), "Down": (11008, 4096)},
     "22B": {"QKV": (6144, 18432), "Out": (6144, 6144), "UpGate": (6144, 32768), "Down": (16384, 6144)},
 }
+
+
+# Larger configurations: per-layer linears of a ~1.9B decoder at 32768 tokens per step, and the two stress shapes.
+LARGE_CONFIGS = {
+    "C4_decoder_1.9B_T32768": {"tokens": 32768, "layers": {"QKV": (2048, 6144), "O": (2048, 2048), "GateUp": (2048, 16384), "Down": (8192, 2048)}},
+    "C5_stress": {"tokens": 16384, "layers": {"square_16384": (16384, 16384), "rect_8192_to_28672": (8192, 28672)}},
+}
+
+
+def time_layer(torch, qii, dev, T, d_in, d_out, reps=3):
+    """ms of one layer forward + backward in the paper's recipe (4/6 forward with max|X|, max|W| supplied, post hoc
+    MS-EDEN backward, all quantizers included), mean over `reps` runs after one warm-up."""
+    g = torch.Generator(device=dev).manual_seed(1)
+    X = torch.randn((T, d_in), device=dev, dtype=torch.float32, generator=g).to(torch.bfloat16)
+    W = (0.02 * torch.randn((d_out, d_in), device=dev, dtype=torch.float32, generator=g)).to(torch.bfloat16)
+    E = (1e-3 * torch.randn((T, d_out), device=dev, dtype=torch.float32, generator=g)).to(torch.bfloat16)
+    Xq, Wq = qii.NVFP4Tensor.empty(T, d_in), qii.NVFP4Tensor.empty(d_out, d_in)
+    Y = torch.empty((T, d_out), dtype=torch.bfloat16, device=dev)
+    dX = torch.empty((T, d_in), dtype=torch.bfloat16, device=dev)
+    dW = torch.empty((d_out, d_in), dtype=torch.bfloat16, device=dev)
+    ws_f = torch.empty(qii.qii_linear_fwd_workspace_bytes(T, d_in, d_out), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(qii.qii_linear_bwd_mode_workspace_bytes(T, d_in, d_out, qii.MS_EDEN_PH), dtype=torch.uint8, device=dev)
+    ax = torch.zeros(1, dtype=torch.float32, device=dev)
+    aw = torch.zeros(1, dtype=torch.float32, device=dev)
+    qii.qii_absmax(X, False, 0, 0, ax)
+    qii.qii_absmax(W, False, 0, 0, aw)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    out = []
+    for i in range(reps + 1):
+        e0, e1, e2 = ev(), ev(), ev()
+        e0.record()
+        qii.qii_linear_fwd_mode(X, W, qii.RTN_46, Y, Xq, Wq, ws_f, amax_x=ax, amax_w=aw)
+        e1.record()
+        qii.qii_linear_bwd_mode(E, Xq, Wq, i, qii.MS_EDEN_PH, dX, dW, ws_b)
+        e2.record()
+        torch.cuda.synchronize()
+        if i:
+            out.append((e0.elapsed_time(e1), e1.elapsed_time(e2)))
+    fwd = float(np.mean([o[0] for o in out]))
+    bwd = float(np.mean([o[1] for o in out]))
+    return fwd, bwd
+
+
+def large_configs(torch, qii, dev):
+    res = {}
+    for name, cfg in LARGE_CONFIGS.items():
+        T = cfg["tokens"]
+        layers, tot, flop = {}, 0.0, 0.0
+        for lname, (d_in, d_out) in cfg["layers"].items():
+            fwd, bwd = time_layer(torch, qii, dev, T, d_in, d_out)
+            f = 6.0 * T * d_in * d_out
+            layers[lname] = {"d_in": d_in, "d_out": d_out, "fwd_ms": round(fwd, 4), "bwd_ms": round(bwd, 4),
+                             "TFLOPs": round(f / ((fwd + bwd) * 1e-3) / 1e12, 1)}
+            tot += fwd + bwd
+            flop += f
+        res[name] = {"tokens": T, "ms": round(tot, 4), "TFLOPs": round(flop / (tot * 1e-3) / 1e12, 1),
+                     "frac_of_mfma_peak": round(flop / (tot * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4), "layers": layers}
+    res["note"] = ("forward + backward per layer, 4/6 forward (max|X|, max|W| supplied) + post hoc MS-EDEN backward, all "
+                   "quantizers included; TFLOP/s = 6 T d_in d_out / time")
+    return res
 
 
 def paper_shapes(torch, qii, synth, dev):
@@ -126,12 +194,12 @@ def main() -> int:
                     help="run only the two launches behind `value`, only the quantize-only parts or only the layer parts of a step (for profiles in "
                          "which every launch of a kernel has the same tensor size); the JSON line then reports "
                          "the skipped parts as null timings")
-    ap.add_argument("--paper-shapes", action="store_true",
-                    help="after the timed steps, also time one layer forward + backward (4/6 forward, "
-                         "post hoc backward) for every weight shape of the paper's table of Llama-like "
-                         "layers (App. D) at 8 x 2048 tokens, next to a plain bf16 matmul of the same "
-                         "shapes (torch.matmul, i.e. the vendor GEMM library) as the 'speedup over BF16' "
-                         "denominator; adds a paper_shapes object to the JSON line")
+    ap.add_argument("--no-extra-configs", action="store_true",
+                    help="skip what runs after the timed steps: the larger configurations (the decoder's linears at "
+                         "32768 tokens, the two stress shapes) and the paper's table of Llama-like layer shapes (App. D) "
+                         "at 8 x 2048 tokens next to plain bf16 matmuls of the same shapes (torch.matmul, i.e. the vendor "
+                         "GEMM library, the 'speedup over BF16' denominator)")
+    ap.add_argument("--paper-shapes", action="store_true", help="(kept for compatibility: the table is part of the default run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives, no sharding); "
@@ -294,7 +362,7 @@ def main() -> int:
 
     n = R * C
     bytes_a1 = 2 * n * BYTES_PER_ELEM_QUANT
-    value = bytes_a1 / ((avg["single_rows"] + avg["single_cols"]) * 1e-3) / 1e9
+    value_supplied = bytes_a1 / ((avg["single_rows"] + avg["single_cols"]) * 1e-3) / 1e9
     bytes_a2 = 2 * n * (BYTES_PER_ELEM_ABSMAX + BYTES_PER_ELEM_QUANT)
     ms_a2 = avg["absmax_rows"] + avg["quant_rows"] + avg["absmax_cols"] + avg["quant_cols"]
     quant_kernel_gbps = n * BYTES_PER_ELEM_QUANT / (avg["single_rows"] * 1e-3) / 1e9
@@ -307,6 +375,8 @@ def main() -> int:
     tflops3 = flops / (lin3_ms * 1e-3) / 1e12
     bytes_ph = 2 * n * BYTES_PER_ELEM_POSTHOC
     ms_ph = avg["posthoc_rows"] + avg["posthoc_cols"]
+    value = bytes_ph / (ms_ph * 1e-3) / 1e9 if do_q else value_supplied
+    quant_cols_gbps = n * BYTES_PER_ELEM_QUANT / (avg["single_cols"] * 1e-3) / 1e9
 
     result = {
         "metric": "MS-EDEN quantize HBM GB/s; NVFP4 linear fwd+bwd TFLOP/s (% of MFMA peak)",
@@ -318,13 +388,17 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {
             "workload": f"MS-EDEN quantize of {R}x{C} bf16 0.1*Student-t(3), RHT-128, blocks along "
-                        f"rows then columns, abs-max supplied, cold inputs (value); the same as "
-                        f"abs-max pass + quantize pass (quantize.two_pass); plus linear fwd+bwd "
-                        f"T={T} d_in={d_in} d_out={d_out} bf16 (linear_fwd_bwd)",
-            "quantize_bytes_per_element": {"absmax_pass": BYTES_PER_ELEM_ABSMAX, "quantize_pass": BYTES_PER_ELEM_QUANT},
+                        f"rows then columns, cold inputs, no abs-max supplied, in the two-kernel form of Sec. 7 "
+                        f"(heavy pass + scales pass; all launches counted) (value); the same with the abs-max "
+                        f"supplied (quantize.single_pass_*) and as abs-max pass + quantize pass (quantize.two_pass); "
+                        f"plus linear fwd+bwd T={T} d_in={d_in} d_out={d_out} bf16 (linear_fwd_bwd)",
+            "quantize_bytes_per_element": {"absmax_pass": BYTES_PER_ELEM_ABSMAX, "quantize_pass": BYTES_PER_ELEM_QUANT,
+                                           "post_hoc_both_passes": BYTES_PER_ELEM_POSTHOC},
             "rotating_input_buffers": n_rot,
         },
         "quantize": {
+            # abs-max supplied by the caller (App. D): one launch per tensor, 2.5625 B per element
+            "abs_max_supplied_GBps": round(value_supplied, 1),
             "single_pass_rows_ms": round(avg["single_rows"], 4), "single_pass_cols_ms": round(avg["single_cols"], 4),
             "single_pass_rows_GBps": round(quant_kernel_gbps, 1),
             "single_pass_cols_GBps": round(n * BYTES_PER_ELEM_QUANT / (avg["single_cols"] * 1e-3) / 1e9, 1),
@@ -365,7 +439,13 @@ def main() -> int:
             # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by what the same
             # counters read for a 512 MiB device copy (x2.0 and x1.0): profiles/bench_hbm_traffic.txt
             "traffic": {"bytes": TRAFFIC_QUANT_ROWS_BYTES, "algorithmic_bytes": int(n * BYTES_PER_ELEM_QUANT),
-                        "valid_for": "8192x8192 bf16"} if (R, C) == (8192, 8192) else None,
+                        "valid_for": "8192x8192 bf16", "source": "profiles/value_workload_hbm_traffic.txt"} if (R, C) == (8192, 8192) else None,
+        },
+        # the same for the columns kernel (transposed source), the slower of the two
+        "roofline_cols": {
+            "kernel": "quantize_cols_kernel<bf16, MS_EDEN, RHT> (abs-max supplied, cold input)", "bound": "hbm",
+            "achieved": round(quant_cols_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(quant_cols_gbps / HBM_PEAK_GBPS, 4),
         },
         # the same launch against the vector-ALU peak: what the arithmetic contract asks per element
         # (7 butterfly add/sub, scaling fma 2, abs/max 1, quotient 1, FP4 rounding 1, two EDEN fma 4,
@@ -390,33 +470,39 @@ def main() -> int:
 
     if args.parts != "all":   # partial runs are for profiles: no figures for what did not run
         result["config"]["parts"] = args.parts
-        if not do_v:
+        if not do_q:
             result["value"] = None
+        if not do_v:
             result["roofline"] = None
+            result["roofline_cols"] = None
             result["roofline_alu"] = None
         if not do_q:
             result["quantize"] = None
         if not do_l:
             result["linear_fwd_bwd"] = None
             result["roofline_gemm"] = None
-    if args.paper_shapes:
+    if not args.no_extra_configs and args.parts == "all":
+        # free the step buffers first: the stress shapes need several GiB
+        del xs, Xs, Ws, Es, Y, dX, dW, ws_b, ws_ph, ws_pair, out_rows, out_cols
+        torch.cuda.empty_cache()
+        result["configs"] = large_configs(torch, qii, dev)
         result["paper_shapes"] = paper_shapes(torch, qii, synth, dev)
 
-    if not args.no_cpu_baseline and do_v:
+    if not args.no_cpu_baseline and do_q:
         import oracle
         oracle.build()
         reps = 0
         t0 = time.perf_counter()
         while reps < 3 or time.perf_counter() - t0 < 12.0:   # a bounded sample: 12 s or more of oracle time
             for transpose in (False, True):
-                oracle.quantize(x_np, oracle.MS_EDEN, transpose=transpose, seed_rht=0, seed_sr=reps)
+                oracle.quantize(x_np, oracle.MS_EDEN_PH, transpose=transpose, seed_rht=0, seed_sr=reps)
             reps += 1
         dt = (time.perf_counter() - t0) / reps
         result["cpu_baseline"] = {
-            "value": round(bytes_a1 / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.max_threads(),
+            "value": round(bytes_ph / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.max_threads(),
             "kind": "oracle",
-            "sample": f"the whole part-A1 workload ({R}x{C} MS-EDEN, rows then columns; the oracle "
-                      f"measures the abs-max itself) {reps} times, {dt:.2f} s of wall time each",
+            "sample": f"the whole `value` workload ({R}x{C} MS-EDEN with post hoc range alignment, rows then "
+                      f"columns, same byte count as the GPU figure) {reps} times, {dt:.2f} s of wall time each",
         }
     print(json.dumps(result))
     return 0
