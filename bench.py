@@ -176,6 +176,81 @@ def paper_shapes(torch, qii, synth, dev):
     return out
 
 
+def microbench(torch, qii, dev):
+    """Machine limits behind the roofline arguments, each one launch of qii_microbench timed with events (mean of 5
+    after 2 warm-ups): streaming rates, the quantizer's traffic pattern without arithmetic, issue rates, atomics."""
+    MiB = 2 ** 20
+    a = torch.empty(512 * MiB, dtype=torch.uint8, device=dev).random_(0, 255)
+    b = torch.empty(512 * MiB, dtype=torch.uint8, device=dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def t_ms(fn, reps=6, warm=2):
+        # launches back to back with an event between them, one synchronization at the end: the way the benchmark's
+        # steps are timed, so that the figures compare
+        e = [ev() for _ in range(reps + 1)]
+        for i in range(warm):
+            fn(i)
+        e[0].record()
+        for i in range(reps):
+            fn(warm + i)
+            e[i + 1].record()
+        torch.cuda.synchronize()
+        return float(np.mean([e[i].elapsed_time(e[i + 1]) for i in range(reps)]))
+
+    res = {"note": "512 MiB buffers (twice the Infinity Cache); GB/s counts bytes read plus bytes written; clock taken as 2.4 GHz"}
+    n = 512 * MiB
+    for name, kind, nbytes in (("copy", qii.MB_COPY, 2 * n), ("read", qii.MB_READ, n), ("write", qii.MB_WRITE, n)):
+        res[name] = {}
+        for blocks in (1024, 2048, 4096, 32768):
+            ms = t_ms(lambda i: qii.qii_microbench(kind, a, b, n, blocks, 0))
+            res[name][f"blocks_{blocks}"] = {"ms": round(ms, 4), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1)}
+    # the rows quantizer's loads and stores on 8192 x 8192 bf16, a different (cold) 128 MiB input per launch
+    nq = 128 * MiB
+    ms = t_ms(lambda i: qii.qii_microbench(qii.MB_QUANT_TRAFFIC, a[(i % 4) * nq:], b, nq, 1, 0), reps=8)
+    res["quantizer_rows_traffic_8192x8192_bf16"] = {"ms": round(ms, 4), "bytes": int(nq * (1 + 0.25 + 1 / 32)),
+                                               "GBps": round(nq * (1 + 0.25 + 1 / 32) / (ms * 1e-3) / 1e9, 1)}
+    ms = t_ms(lambda i: qii.qii_microbench(qii.MB_QUANT_TRAFFIC, a, b, nq, 1, 0), reps=8)
+    res["quantizer_rows_traffic_8192x8192_bf16_same_input"] = {"ms": round(ms, 4), "GBps": round(nq * (1 + 0.25 + 1 / 32) / (ms * 1e-3) / 1e9, 1)}
+    for order, oname in ((0, "row_blocks_fastest"), (1, "die_stripes"), (2, "column_blocks_fastest"),
+                         (3, "lines_of_128B_waves_stacked"), (4, "lines_of_128B_waves_side_by_side"),
+                         (5, "lines_of_128B_but_contiguous_stores"), (6, "lines_of_128B_but_contiguous_loads")):
+        ms = t_ms(lambda i: qii.qii_microbench(qii.MB_QUANT_TRAFFIC_COLS, a[(i % 4) * nq:], b, nq, 1, order), reps=8)
+        res.setdefault("quantizer_cols_traffic_8192x8192_bf16", {})[oname] = {
+            "ms": round(ms, 4), "GBps": round(nq * (1 + 0.25 + 1 / 32) / (ms * 1e-3) / 1e9, 1)}
+    # streaming at the quantizer's size: 128 MiB read (cold), and 128 MiB read + 32 MiB written by the copy kernel's
+    # access pattern cannot be had from one kernel, so the two are given separately
+    ms = t_ms(lambda i: qii.qii_microbench(qii.MB_READ, a[(i % 4) * nq:], b, nq, 8192, 0), reps=8)
+    res["read_128MiB_cold"] = {"ms": round(ms, 4), "GBps": round(nq / (ms * 1e-3) / 1e9, 1)}
+    ms = t_ms(lambda i: qii.qii_microbench(qii.MB_WRITE, None, b[(i % 4) * nq:], 36 * MiB, 2304, 0), reps=8)
+    res["write_36MiB"] = {"ms": round(ms, 4), "GBps": round(36 * MiB / (ms * 1e-3) / 1e9, 1)}
+    # issue rates: 2048 blocks of 4 waves (8 waves per SIMD)
+    blocks, iters = 2048, 4096
+    waves = blocks * 4
+    cu_clk = 256 * 2.4e9
+    for name, kind, per_trip in (("v_fma_f32", qii.MB_VALU_FMA, 16), ("rht128_slice", qii.MB_VALU_RHT, 128),
+                                 ("v_cvt_scalef32_pk_fp4_f32", qii.MB_VALU_CVT_FP4, 8)):
+        ms = t_ms(lambda i: qii.qii_microbench(kind, None, b, 0, blocks, iters))
+        wave_instr = waves * iters * per_trip
+        res[name] = {"ms": round(ms, 4), "wave_instructions_per_CU_per_clock": round(wave_instr / (ms * 1e-3) / cu_clk, 3)}
+    res["v_fma_f32"]["TFLOPs"] = round(waves * iters * 16 * 64 * 2 / (res["v_fma_f32"]["ms"] * 1e-3) / 1e12, 1)
+    # what the rotation alone costs on the value workload: one slice per 16 elements
+    r = res["rht128_slice"]
+    r["us_for_8192x8192"] = round(r["ms"] * 1e3 * (8192 * 8192 / 16 / 64) / (waves * iters), 2)
+    ms = t_ms(lambda i: qii.qii_microbench(qii.MB_MFMA_F16, None, b, 0, blocks, iters))
+    res["v_mfma_f32_32x32x16_f16"] = {"ms": round(ms, 4), "TFLOPs": round(waves * iters * 4 * 2 * 32 * 32 * 16 / (ms * 1e-3) / 1e12, 1)}
+    # launch floor and atomics: the extra time per block over an empty kernel of the same grid
+    res["atomics"] = {}
+    for blocks in (4096, 16384, 65536):
+        e = t_ms(lambda i: qii.qii_microbench(qii.MB_EMPTY, None, None, 0, blocks, 0))
+        one = t_ms(lambda i: qii.qii_microbench(qii.MB_ATOMIC_ONE_WORD, b, None, 0, blocks, 0))
+        spread = t_ms(lambda i: qii.qii_microbench(qii.MB_ATOMIC_SPREAD, b, None, 0, blocks, 0))
+        res["atomics"][f"blocks_{blocks}"] = {"empty_kernel_us": round(e * 1e3, 2), "one_word_us": round(one * 1e3, 2),
+                                              "spread_64_words_us": round(spread * 1e3, 2),
+                                              "ns_per_atomic_one_word": round((one - e) * 1e6 / blocks, 2),
+                                              "ns_per_atomic_spread": round((spread - e) * 1e6 / blocks, 2)}
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -199,6 +274,10 @@ def main() -> int:
                          "32768 tokens, the two stress shapes) and the paper's table of Llama-like layer shapes (App. D) "
                          "at 8 x 2048 tokens next to plain bf16 matmuls of the same shapes (torch.matmul, i.e. the vendor "
                          "GEMM library, the 'speedup over BF16' denominator)")
+    ap.add_argument("--microbench", action="store_true",
+                    help="instead of the benchmark, measure the machine limits the rooflines are argued from (streaming "
+                         "rates, the quantizer's traffic pattern without arithmetic, instruction issue rates, atomics) "
+                         "and print them as one JSON line")
     ap.add_argument("--paper-shapes", action="store_true", help="(kept for compatibility: the table is part of the default run)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -216,6 +295,10 @@ def main() -> int:
     qii.lib()  # fail loudly if the HIP library is not built
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.microbench:
+        print(json.dumps({"microbench": microbench(torch, qii, dev)}))
+        return 0
 
     def to_dev(bits: np.ndarray) -> torch.Tensor:
         return torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)

@@ -260,6 +260,26 @@ size_t qii_linear_bwd_mode_workspace_bytes(int64_t T, int64_t d_in, int64_t d_ou
  * All eight must read 0.  Takes a few hundred milliseconds.                              */
 qii_status qii_selftest_conversions(uint64_t *counts, void *stream);
 
+/* Microbenchmarks of the machine limits the kernels are measured against (a measurement aid,
+ * not an operation of the paper): one launch per call, timed by the caller with events.
+ *   a, b   device buffers (see the kinds); n bytes, a multiple of 16
+ *   blocks grid size in blocks of 256 threads (1..2^20); iters loop trips of the issue-rate kinds
+ * Kinds: EMPTY no work (launch floor); COPY a -> b, READ a, WRITE b: n bytes in 16-byte words,
+ * grid-stride; QUANT_TRAFFIC the loads and stores of the rows quantizer on an [n/16384][8192] bf16
+ * matrix at a without its arithmetic (n a multiple of 262144; b holds n/4 + n/32 bytes; the grid
+ * is derived from n); QUANT_TRAFFIC_COLS the same for the columns quantizer on an 8192 x 8192 bf16
+ * matrix (n must be 134217728); VALU_FMA 16 independent v_fma_f32 per trip; VALU_RHT one 16-element slice
+ * of the 128-point rotation per lane and trip (128 vector instructions); VALU_CVT_FP4 8 FP4
+ * conversions per trip; MFMA_F16 4 v_mfma_f32_32x32x16_f16 per wave and trip; ATOMIC_ONE_WORD one
+ * atomic maximum per block on a[0]; ATOMIC_SPREAD the same over 64 words 256 bytes apart (a holds
+ * 16 KiB).  Buffers a kind does not name may be NULL.                                    */
+typedef enum {
+    QII_MB_EMPTY = 0, QII_MB_COPY = 1, QII_MB_READ = 2, QII_MB_WRITE = 3, QII_MB_QUANT_TRAFFIC = 4,
+    QII_MB_VALU_FMA = 5, QII_MB_VALU_RHT = 6, QII_MB_VALU_CVT_FP4 = 7, QII_MB_MFMA_F16 = 8,
+    QII_MB_ATOMIC_ONE_WORD = 9, QII_MB_ATOMIC_SPREAD = 10, QII_MB_QUANT_TRAFFIC_COLS = 11
+} qii_microbench_kind;
+qii_status qii_microbench(int kind, void *a, void *b, uint64_t n, int blocks, int iters, void *stream);
+
 /* Host helpers.                                                                        */
 uint64_t qii_derive_seed(uint64_t seed, uint32_t i); /* backward sub-seed i (0..5)      */
 const char *qii_status_string(qii_status s);

@@ -24,7 +24,7 @@ EXPORTS = [
     "qii_gemm_nvfp4", "qii_linear_fwd", "qii_linear_fwd_mode", "qii_linear_bwd", "qii_linear_bwd_mode",
     "qii_quantize_workspace_bytes", "qii_quantize_posthoc_workspace_bytes", "qii_linear_bwd_mode_workspace_bytes",
     "qii_gemm_workspace_bytes", "qii_linear_fwd_workspace_bytes", "qii_linear_bwd_workspace_bytes",
-    "qii_derive_seed", "qii_status_string", "qii_last_error", "qii_version", "qii_selftest_conversions",
+    "qii_derive_seed", "qii_status_string", "qii_last_error", "qii_version", "qii_selftest_conversions", "qii_microbench",
     "qii_quantize_nvfp4_noalloc", "qii_gemm_nvfp4_amax", "qii_linear_fwd_amax",
     "qii_quantize_pair_nvfp4", "qii_quantize_pair_workspace_bytes",
 ]
@@ -90,6 +90,8 @@ def lib() -> ctypes.CDLL:
             getattr(L, name).restype = sz
         L.qii_selftest_conversions.argtypes = [vp, vp]
         L.qii_selftest_conversions.restype = c.c_int
+        L.qii_microbench.argtypes = [c.c_int, vp, vp, c.c_uint64, c.c_int, c.c_int, vp]
+        L.qii_microbench.restype = c.c_int
         L.qii_derive_seed.argtypes = [u64, c.c_uint32]
         L.qii_derive_seed.restype = u64
         L.qii_status_string.argtypes = [c.c_int]
@@ -188,6 +190,16 @@ def qii_linear_bwd_workspace_bytes(T: int, d_in: int, d_out: int) -> int:
 def qii_selftest_conversions(counts: torch.Tensor):
     """counts: 8 x int64 on the device; receives the mismatch counts (see include/qii.h)."""
     _check(lib().qii_selftest_conversions(counts.data_ptr(), _stream()))
+
+
+MB_EMPTY, MB_COPY, MB_READ, MB_WRITE, MB_QUANT_TRAFFIC, MB_VALU_FMA, MB_VALU_RHT, MB_VALU_CVT_FP4, MB_MFMA_F16, \
+    MB_ATOMIC_ONE_WORD, MB_ATOMIC_SPREAD, MB_QUANT_TRAFFIC_COLS = range(12)
+
+
+def qii_microbench(kind: int, a: torch.Tensor | None, b: torch.Tensor | None, n: int, blocks: int, iters: int):
+    """One launch of a machine-limit microbenchmark (see include/qii.h); a, b: device byte buffers or None."""
+    _check(lib().qii_microbench(kind, a.data_ptr() if a is not None else None, b.data_ptr() if b is not None else None,
+                                n, blocks, iters, _stream()))
 
 
 def qii_rht(x: torch.Tensor, transpose: bool, seed_rht: int, y: torch.Tensor, amax: torch.Tensor | None):

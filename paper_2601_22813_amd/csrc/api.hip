@@ -672,6 +672,24 @@ qii_status qii_selftest_conversions(uint64_t *counts, void *stream)
     return QII_OK;
 }
 
+qii_status qii_microbench(int kind, void *a, void *b, uint64_t n, int blocks, int iters, void *stream)
+{
+    if (kind < QII_MB_EMPTY || kind > QII_MB_QUANT_TRAFFIC_COLS) return fail(QII_INVALID_ARG, "microbench: unknown kind");
+    if (blocks < 1 || blocks > (1 << 20) || iters < 0) return fail(QII_INVALID_ARG, "microbench: blocks in 1..2^20, iters >= 0");
+    const bool quant = kind == QII_MB_QUANT_TRAFFIC || kind == QII_MB_QUANT_TRAFFIC_COLS;
+    const bool atomic = kind == QII_MB_ATOMIC_ONE_WORD || kind == QII_MB_ATOMIC_SPREAD;
+    const bool needs_a = kind == QII_MB_COPY || kind == QII_MB_READ || quant || atomic;
+    const bool needs_b = kind == QII_MB_COPY || kind == QII_MB_WRITE || quant;
+    if ((needs_a && (!a || !aligned(a, 16))) || (needs_b && (!b || !aligned(b, 16))))
+        return fail(QII_INVALID_ARG, "microbench: a buffer this kind uses is NULL or not 16-byte aligned");
+    if ((needs_a || needs_b) && !atomic && (n == 0 || n % 16)) return fail(QII_BAD_SHAPE, "microbench: n must be a positive multiple of 16");
+    if (kind == QII_MB_QUANT_TRAFFIC && (n % 262144 || n / 262144 > (1u << 20))) return fail(QII_BAD_SHAPE, "microbench: n must be a multiple of 262144 (16 rows of 8192 bf16)");
+    if (kind == QII_MB_QUANT_TRAFFIC_COLS && n != 134217728u) return fail(QII_BAD_SHAPE, "microbench: n must be 134217728 (8192 x 8192 bf16)");
+    hipError_t e = qii::launch_microbench(kind, a, b, n, blocks, iters, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, "microbench");
+    return QII_OK;
+}
+
 qii_status qii_linear_bwd(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq, const qii_nvfp4 *Wq,
                           uint64_t seed, void *dX, void *dW, qii_dtype g_dt, void *ws,
                           size_t ws_bytes, void *stream)

@@ -94,5 +94,6 @@ hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is
 // sweeps of the hardware conversions and short division sequences against their value-space
 // rules; counts[0..7] (device) receive the numbers of mismatches (selftest.hip)
 hipError_t launch_selftest_conversions(unsigned long long *counts, hipStream_t s);
+hipError_t launch_microbench(int kind, void *a, void *b, uint64_t n, int blocks, int iters, hipStream_t s);
 
 }  // namespace qii

@@ -158,8 +158,19 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(ColsArgs a)
 {
     const int lane = threadIdx.x & 63, q = lane & 3;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;   // wave-uniform
-    const int64_t j0 = (int64_t)blockIdx.y * 32 + 2 * (lane >> 2);
+    // Blocks are dispatched x fastest and go to the 8 dies round robin.  Where the grid allows it, die k
+    // takes stripes of 32 column blocks (2 KiB of a source row) and walks each stripe column blocks
+    // fastest, so that the pieces of one source row inside a stripe are fetched at about the same
+    // time and through one L2.
+    uint32_t bx = blockIdx.x, by = blockIdx.y;
+    if ((gridDim.y & 255u) == 0u) {
+        const uint32_t id = by * gridDim.x + bx, xcd = id & 7u, slot = id >> 3, per = 32u * gridDim.x;
+        const uint32_t stripe = (slot / per) * 8u + xcd, r = slot % per;
+        by = 32u * stripe + (r & 31u);
+        bx = r >> 5;
+    }
+    const int64_t chunk = (int64_t)bx * 4 + wave;   // wave-uniform
+    const int64_t j0 = (int64_t)by * 32 + 2 * (lane >> 2);
     // R is even whenever this kernel is chosen, so a pair of columns is in range or not as a whole
     const bool live = chunk * 128 < a.C;   // wave-uniform
     const int64_t jc = j0 < a.R ? j0 : a.R - 2;
@@ -169,7 +180,7 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(ColsArgs a)
     if (kMode != QII_MS_EDEN_PH && live) load_quarter_chunk_raw<kSrc>(raw, a, chunk, (uint32_t)jc, q);
     // (the heavy pass of the post hoc scheme knows no tensor maximum: tc stays unused there)
     const TensorConsts tc = kMode == QII_MS_EDEN_PH ? TensorConsts{} : tensor_consts(kMode, *a.amax);
-    if (kMode != QII_MS_EDEN_PH && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *a.tensor_scale = tc.x32;
+    if (kMode != QII_MS_EDEN_PH && bx == 0 && by == 0 && threadIdx.x == 0) *a.tensor_scale = tc.x32;
     if (kMode == QII_MS_EDEN_PH) {
         // heavy pass of the post hoc scheme: codes, corrected pseudo-scales, and the block's
         // maximum into the running maximum (a wave does one tile only, so the four waves of a
