@@ -228,7 +228,9 @@ def microbench(torch, qii, dev):
     waves = blocks * 4
     cu_clk = 256 * 2.4e9
     for name, kind, per_trip in (("v_fma_f32", qii.MB_VALU_FMA, 16), ("rht128_slice", qii.MB_VALU_RHT, 128),
-                                 ("v_cvt_scalef32_pk_fp4_f32", qii.MB_VALU_CVT_FP4, 8)):
+                                 ("v_cvt_scalef32_pk_fp4_f32", qii.MB_VALU_CVT_FP4, 8),
+                                 ("v_cvt_scalef32_pk_f16_fp4", qii.MB_VALU_CVT_F16_FP4, 8), ("v_pk_mul_f16", qii.MB_VALU_PK_MUL_F16, 16),
+                                 ("v_cvt_scalef32_pk32_f16_fp6", qii.MB_VALU_CVT_PK32_F16_FP6, 2)):
         ms = t_ms(lambda i: qii.qii_microbench(kind, None, b, 0, blocks, iters))
         wave_instr = waves * iters * per_trip
         res[name] = {"ms": round(ms, 4), "wave_instructions_per_CU_per_clock": round(wave_instr / (ms * 1e-3) / cu_clk, 3)}
@@ -238,6 +240,12 @@ def microbench(torch, qii, dev):
     r["us_for_8192x8192"] = round(r["ms"] * 1e3 * (8192 * 8192 / 16 / 64) / (waves * iters), 2)
     ms = t_ms(lambda i: qii.qii_microbench(qii.MB_MFMA_F16, None, b, 0, blocks, iters))
     res["v_mfma_f32_32x32x16_f16"] = {"ms": round(ms, 4), "TFLOPs": round(waves * iters * 4 * 2 * 32 * 32 * 16 / (ms * 1e-3) / 1e12, 1)}
+    # the GEMM's inner loop without its memory side: one block per compute unit, one wave per SIMD
+    res["gemm_inner_loop_no_memory"] = {}
+    for chunks, cname in ((0, "matrix_instructions_only"), (1, "with_dequantization_as_in_the_gemm"),
+                          (2, "with_one_operand_dequantized"), (3, "with_dequantization_from_packed_e2m3")):
+        ms = t_ms(lambda i: qii.qii_microbench(qii.MB_MFMA_DEQUANT, None, b, chunks, 256, 4096))
+        res["gemm_inner_loop_no_memory"][cname] = {"ms": round(ms, 4), "TFLOPs": round(256 * 4 * 4096 * 16 * 2 * 32 * 32 * 16 / (ms * 1e-3) / 1e12, 1)}
     # launch floor and atomics: the extra time per block over an empty kernel of the same grid
     res["atomics"] = {}
     for blocks in (4096, 16384, 65536):

@@ -270,13 +270,20 @@ qii_status qii_selftest_conversions(uint64_t *counts, void *stream);
  * is derived from n); QUANT_TRAFFIC_COLS the same for the columns quantizer on an 8192 x 8192 bf16
  * matrix (n must be 134217728); VALU_FMA 16 independent v_fma_f32 per trip; VALU_RHT one 16-element slice
  * of the 128-point rotation per lane and trip (128 vector instructions); VALU_CVT_FP4 8 FP4
- * conversions per trip; MFMA_F16 4 v_mfma_f32_32x32x16_f16 per wave and trip; ATOMIC_ONE_WORD one
+ * conversions per trip; VALU_CVT_F16_FP4 8 FP4 -> f16 conversions, VALU_PK_MUL_F16 16 packed f16
+ * products per trip; MFMA_DEQUANT the GEMM's inner loop without its memory side, one wave per SIMD
+ * (16 matrix instructions per trip, each followed by a dequantization chunk of 2 conversions
+ * and 2 packed products: n = 1 all 16 as in the GEMM, n = 2 the first 8 only, n = 0 none, n = 3 the work that
+ * codes packed as E2M3 would need instead, 2 conversions of 32 values and 32 packed products per
+ * trip; iters even); VALU_CVT_PK32_F16_FP6 2 conversions of 32 E2M3 values per trip; MFMA_F16 4 v_mfma_f32_32x32x16_f16 per wave and trip; ATOMIC_ONE_WORD one
  * atomic maximum per block on a[0]; ATOMIC_SPREAD the same over 64 words 256 bytes apart (a holds
  * 16 KiB).  Buffers a kind does not name may be NULL.                                    */
 typedef enum {
     QII_MB_EMPTY = 0, QII_MB_COPY = 1, QII_MB_READ = 2, QII_MB_WRITE = 3, QII_MB_QUANT_TRAFFIC = 4,
     QII_MB_VALU_FMA = 5, QII_MB_VALU_RHT = 6, QII_MB_VALU_CVT_FP4 = 7, QII_MB_MFMA_F16 = 8,
-    QII_MB_ATOMIC_ONE_WORD = 9, QII_MB_ATOMIC_SPREAD = 10, QII_MB_QUANT_TRAFFIC_COLS = 11
+    QII_MB_ATOMIC_ONE_WORD = 9, QII_MB_ATOMIC_SPREAD = 10, QII_MB_QUANT_TRAFFIC_COLS = 11,
+    QII_MB_VALU_CVT_F16_FP4 = 12, QII_MB_VALU_PK_MUL_F16 = 13, QII_MB_MFMA_DEQUANT = 14,
+    QII_MB_VALU_CVT_PK32_F16_FP6 = 15
 } qii_microbench_kind;
 qii_status qii_microbench(int kind, void *a, void *b, uint64_t n, int blocks, int iters, void *stream);
 

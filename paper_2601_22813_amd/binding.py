@@ -193,7 +193,8 @@ def qii_selftest_conversions(counts: torch.Tensor):
 
 
 MB_EMPTY, MB_COPY, MB_READ, MB_WRITE, MB_QUANT_TRAFFIC, MB_VALU_FMA, MB_VALU_RHT, MB_VALU_CVT_FP4, MB_MFMA_F16, \
-    MB_ATOMIC_ONE_WORD, MB_ATOMIC_SPREAD, MB_QUANT_TRAFFIC_COLS = range(12)
+    MB_ATOMIC_ONE_WORD, MB_ATOMIC_SPREAD, MB_QUANT_TRAFFIC_COLS, MB_VALU_CVT_F16_FP4, \
+    MB_VALU_PK_MUL_F16, MB_MFMA_DEQUANT, MB_VALU_CVT_PK32_F16_FP6 = range(16)
 
 
 def qii_microbench(kind: int, a: torch.Tensor | None, b: torch.Tensor | None, n: int, blocks: int, iters: int):

@@ -12,6 +12,7 @@ namespace {
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
 __global__ void mb_empty(uint32_t *) {}
 
@@ -246,6 +247,205 @@ __global__ __launch_bounds__(256) void mb_mfma_f16(float *out, int iters)
     if (s == 123456.789f) out[0] = s;
 }
 
+// v_cvt_scalef32_pk_f16_fp4: 8 conversions per trip, chained through the source word
+__global__ __launch_bounds__(256) void mb_valu_cvt_f16_fp4(float *out, int iters)
+{
+    uint32_t w = threadIdx.x * 0x01010101u + blockIdx.x;
+    uint32_t acc = 0;
+    for (int it = 0; it < iters; ++it) {
+        half2_t h[8];
+#define QII_MB_CVT(K) h[K] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w + K, 256.0f, K & 3)
+        QII_MB_CVT(0); QII_MB_CVT(1); QII_MB_CVT(2); QII_MB_CVT(3); QII_MB_CVT(4); QII_MB_CVT(5); QII_MB_CVT(6); QII_MB_CVT(7);
+#undef QII_MB_CVT
+        uint32_t x = 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) x ^= __builtin_bit_cast(uint32_t, h[k]);
+        acc ^= x;
+        w += acc & 1u;
+    }
+    if (acc == 0x9E3779B9u) out[0] = u2f(acc);
+}
+
+// v_pk_mul_f16: 16 independent products per trip
+__global__ __launch_bounds__(256) void mb_valu_pk_mul_f16(float *out, int iters)
+{
+    half2_t v[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = half2_t{(_Float16)(1.0f + 0.001f * (float)(threadIdx.x + k)), (_Float16)1.0f};
+    const half2_t c = half2_t{(_Float16)1.0f, (_Float16)(blockIdx.x ? 1.0f : 1.0009765625f)};
+    for (int it = 0; it < iters; ++it)
+#pragma unroll
+        for (int k = 0; k < 16; ++k) asm volatile("v_pk_mul_f16 %0, %0, %1" : "+v"(v[k]) : "v"(c));
+    uint32_t x = 0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) x ^= __builtin_bit_cast(uint32_t, v[k]);
+    if (x == 0x9E3779B9u) out[0] = u2f(x);
+}
+
+// The inner loop of the GEMM without its memory side, one wave per SIMD (the block holds more than
+// half of the LDS, as the GEMM's does): 16 matrix instructions on 16 accumulators per trip, each
+// followed (chunks = 1) by the GEMM's dequantization chunk, 2 FP4 -> f16 conversions and 2 packed
+// multiplies, which produce the operands of the next trip, by that chunk after the first 8 only (chunks = 2:
+// one operand dequantized, the other taken as it is), or (chunks = 0) by nothing.
+template <int chunks>
+__global__ __launch_bounds__(256, 1) void mb_mfma_dequant(float *out, int iters)
+{
+    __shared__ uint32_t hold[24576];   // 96 KiB
+    if (iters < 0) hold[threadIdx.x] = 1u;
+    half8_t a[2][4], b[2][4];
+    uint32_t raw[8], sc = 0x3C003C00u;   // 1.0, 1.0
+#pragma unroll
+    for (int t = 0; t < 8; ++t) raw[t] = (threadIdx.x + t) * 0x00010203u;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            a[0][t][k] = a[1][t][k] = (_Float16)0.5f;
+            b[0][t][k] = b[1][t][k] = (_Float16)0.25f;
+        }
+    float16_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int k = 0; k < 16; ++k) acc[i][j][k] = 0.0f;
+#define QII_MB_DQ(DST, SRC, H)                                                                            \
+    do {                                                                                                  \
+        const half2_t c0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(SRC, 256.0f, 2 * H);                  \
+        const half2_t c1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(SRC, 256.0f, 2 * H + 1);              \
+        half2_t h0, h1;                                                                                   \
+        asm("v_pk_mul_f16 %0, %1, %2 op_sel_hi:[1,0]" : "=v"(h0) : "v"(c0), "v"(sc));                     \
+        asm("v_pk_mul_f16 %0, %1, %2 op_sel_hi:[1,0]" : "=v"(h1) : "v"(c1), "v"(sc));                     \
+        DST[4 * H] = h0[0]; DST[4 * H + 1] = h0[1]; DST[4 * H + 2] = h1[0]; DST[4 * H + 3] = h1[1];       \
+    } while (0)
+#define QII_MB_MMA(CU, NX, I)                                                                             \
+    acc[(I) >> 2][(I) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[CU][(I) >> 2], b[CU][(I) & 3],      \
+                                                                    acc[(I) >> 2][(I) & 3], 0, 0, 0);     \
+    if (chunks >= 1) {                                                                                    \
+        if ((I) < 8) QII_MB_DQ(a[NX][((I) >> 1) & 3], raw[(I) >> 1], ((I) & 1));                          \
+        else if (chunks == 1) QII_MB_DQ(b[NX][((I) >> 1) & 3], raw[(I) >> 1], ((I) & 1));                 \
+    }                                                                                                     \
+    __builtin_amdgcn_sched_barrier(0)
+#define QII_MB_STEP(CU, NX)                                                                               \
+    QII_MB_MMA(CU, NX, 0); QII_MB_MMA(CU, NX, 1); QII_MB_MMA(CU, NX, 2); QII_MB_MMA(CU, NX, 3);           \
+    QII_MB_MMA(CU, NX, 4); QII_MB_MMA(CU, NX, 5); QII_MB_MMA(CU, NX, 6); QII_MB_MMA(CU, NX, 7);           \
+    QII_MB_MMA(CU, NX, 8); QII_MB_MMA(CU, NX, 9); QII_MB_MMA(CU, NX, 10); QII_MB_MMA(CU, NX, 11);         \
+    QII_MB_MMA(CU, NX, 12); QII_MB_MMA(CU, NX, 13); QII_MB_MMA(CU, NX, 14); QII_MB_MMA(CU, NX, 15)
+    for (int it = 0; it < iters; it += 2) {
+        QII_MB_STEP(0, 1);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) raw[t] += 0x11111111u;
+        QII_MB_STEP(1, 0);
+    }
+#undef QII_MB_STEP
+#undef QII_MB_MMA
+#undef QII_MB_DQ
+    float s = (float)hold[threadIdx.x & 1];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int k = 0; k < 16; ++k) s += acc[i][j][k];
+    if (s == 123456.789f) out[0] = s;
+}
+
+typedef uint32_t u32x6 __attribute__((ext_vector_type(6)));
+typedef _Float16 half32_t __attribute__((ext_vector_type(32)));
+
+// v_cvt_scalef32_pk32_f16_fp6: 2 conversions of 32 values per trip
+__global__ __launch_bounds__(256) void mb_valu_cvt_pk32_f16_fp6(float *out, int iters)
+{
+    u32x6 w0, w1;
+#pragma unroll
+    for (int k = 0; k < 6; ++k) {
+        w0[k] = (threadIdx.x + k) * 0x01020304u;
+        w1[k] = (threadIdx.x + 7 * k) * 0x04030201u;
+    }
+    uint32_t acc = 0;
+    for (int it = 0; it < iters; ++it) {
+        const half32_t h0 = __builtin_amdgcn_cvt_scalef32_pk32_f16_fp6(w0, 1.0f);
+        const half32_t h1 = __builtin_amdgcn_cvt_scalef32_pk32_f16_fp6(w1, 1.0f);
+        const uint32_t x = __builtin_bit_cast(uint32_t, half2_t{h0[0], h0[31]}) ^ __builtin_bit_cast(uint32_t, half2_t{h1[1], h1[30]});
+        acc ^= x;
+        w0[0] += acc & 1u;
+        w1[5] += acc & 2u;
+    }
+    if (acc == 0x9E3779B9u) out[0] = u2f(acc);
+}
+
+// The GEMM's inner loop without its memory side if the codes came as packed E2M3 (6 bits each):
+// per trip of 16 matrix instructions, 2 conversions of 32 values and 32 packed multiplies by the
+// group scales produce the 8 operand fragments of the next trip.
+__global__ __launch_bounds__(256, 1) void mb_mfma_dequant_fp6(float *out, int iters)
+{
+    __shared__ uint32_t hold[24576];   // 96 KiB
+    if (iters < 0) hold[threadIdx.x] = 1u;
+    half8_t a[2][4], b[2][4];
+    u32x6 ra, rb;
+    const uint32_t sc = 0x3C003C00u;
+#pragma unroll
+    for (int k = 0; k < 6; ++k) {
+        ra[k] = (threadIdx.x + k) * 0x00010203u;
+        rb[k] = (threadIdx.x + 5 * k) * 0x00030201u;
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            a[0][t][k] = a[1][t][k] = (_Float16)0.5f;
+            b[0][t][k] = b[1][t][k] = (_Float16)0.25f;
+        }
+    float16_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int k = 0; k < 16; ++k) acc[i][j][k] = 0.0f;
+    half32_t ha, hb;
+#define QII_MB_MUL2(DST, SRC, P)                                                                          \
+    do {                                                                                                  \
+        half2_t h0, h1;                                                                                   \
+        const half2_t c0 = half2_t{SRC[4 * (P)], SRC[4 * (P) + 1]}, c1 = half2_t{SRC[4 * (P) + 2], SRC[4 * (P) + 3]}; \
+        asm("v_pk_mul_f16 %0, %1, %2 op_sel_hi:[1,0]" : "=v"(h0) : "v"(c0), "v"(sc));                     \
+        asm("v_pk_mul_f16 %0, %1, %2 op_sel_hi:[1,0]" : "=v"(h1) : "v"(c1), "v"(sc));                     \
+        DST[((P) >> 1) & 3][4 * ((P) & 1)] = h0[0]; DST[((P) >> 1) & 3][4 * ((P) & 1) + 1] = h0[1];       \
+        DST[((P) >> 1) & 3][4 * ((P) & 1) + 2] = h1[0]; DST[((P) >> 1) & 3][4 * ((P) & 1) + 3] = h1[1];   \
+    } while (0)
+#define QII_MB_MMA(CU, NX, I)                                                                             \
+    acc[(I) >> 2][(I) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[CU][(I) >> 2], b[CU][(I) & 3],      \
+                                                                    acc[(I) >> 2][(I) & 3], 0, 0, 0);     \
+    if ((I) == 0) ha = __builtin_amdgcn_cvt_scalef32_pk32_f16_fp6(ra, 256.0f);                            \
+    if ((I) == 7) hb = __builtin_amdgcn_cvt_scalef32_pk32_f16_fp6(rb, 256.0f);                            \
+    if ((I) >= 1 && (I) < 9) QII_MB_MUL2(a[NX], ha, (I) - 1);                                             \
+    if ((I) >= 8) QII_MB_MUL2(b[NX], hb, (I) - 8);                                                        \
+    __builtin_amdgcn_sched_barrier(0)
+#define QII_MB_STEP(CU, NX)                                                                               \
+    QII_MB_MMA(CU, NX, 0); QII_MB_MMA(CU, NX, 1); QII_MB_MMA(CU, NX, 2); QII_MB_MMA(CU, NX, 3);           \
+    QII_MB_MMA(CU, NX, 4); QII_MB_MMA(CU, NX, 5); QII_MB_MMA(CU, NX, 6); QII_MB_MMA(CU, NX, 7);           \
+    QII_MB_MMA(CU, NX, 8); QII_MB_MMA(CU, NX, 9); QII_MB_MMA(CU, NX, 10); QII_MB_MMA(CU, NX, 11);         \
+    QII_MB_MMA(CU, NX, 12); QII_MB_MMA(CU, NX, 13); QII_MB_MMA(CU, NX, 14); QII_MB_MMA(CU, NX, 15)
+    for (int it = 0; it < iters; it += 2) {
+        QII_MB_STEP(0, 1);
+#pragma unroll
+        for (int t = 0; t < 6; ++t) { ra[t] += 0x11111111u; rb[t] += 0x01010101u; }
+        QII_MB_STEP(1, 0);
+    }
+#undef QII_MB_STEP
+#undef QII_MB_MMA
+#undef QII_MB_MUL2
+    float s = (float)hold[threadIdx.x & 1];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int k = 0; k < 16; ++k) s += acc[i][j][k];
+    if (s == 123456.789f) out[0] = s;
+}
+
 // one atomic maximum per block: all to one word, or to 64 words 256 bytes apart
 __global__ __launch_bounds__(256) void mb_atomic(uint32_t *a, int spread)
 {
@@ -278,6 +478,15 @@ hipError_t launch_microbench(int kind, void *a, void *b, uint64_t n, int blocks,
     case QII_MB_VALU_RHT: hipLaunchKernelGGL(mb_valu_rht, grid, block, 0, s, (float *)b, iters); break;
     case QII_MB_VALU_CVT_FP4: hipLaunchKernelGGL(mb_valu_cvt_fp4, grid, block, 0, s, (float *)b, iters); break;
     case QII_MB_MFMA_F16: hipLaunchKernelGGL(mb_mfma_f16, grid, block, 0, s, (float *)b, iters); break;
+    case QII_MB_VALU_CVT_F16_FP4: hipLaunchKernelGGL(mb_valu_cvt_f16_fp4, grid, block, 0, s, (float *)b, iters); break;
+    case QII_MB_VALU_CVT_PK32_F16_FP6: hipLaunchKernelGGL(mb_valu_cvt_pk32_f16_fp6, grid, block, 0, s, (float *)b, iters); break;
+    case QII_MB_VALU_PK_MUL_F16: hipLaunchKernelGGL(mb_valu_pk_mul_f16, grid, block, 0, s, (float *)b, iters); break;
+    case QII_MB_MFMA_DEQUANT:
+        if (n == 0) hipLaunchKernelGGL(mb_mfma_dequant<0>, grid, block, 0, s, (float *)b, iters);
+        else if (n == 1) hipLaunchKernelGGL(mb_mfma_dequant<1>, grid, block, 0, s, (float *)b, iters);
+        else if (n == 2) hipLaunchKernelGGL(mb_mfma_dequant<2>, grid, block, 0, s, (float *)b, iters);
+        else hipLaunchKernelGGL(mb_mfma_dequant_fp6, grid, block, 0, s, (float *)b, iters);
+        break;
     case QII_MB_ATOMIC_ONE_WORD: hipLaunchKernelGGL(mb_atomic, grid, block, 0, s, (uint32_t *)a, 0); break;
     case QII_MB_ATOMIC_SPREAD: hipLaunchKernelGGL(mb_atomic, grid, block, 0, s, (uint32_t *)a, 1); break;
     default: return hipErrorInvalidValue;
