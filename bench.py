@@ -40,7 +40,7 @@ VALU_F32_PEAK_TFLOPS = 157.3
 BYTES_PER_ELEM_POSTHOC = 2 + 0.5 + 0.25 + 0.25 + 0.0625
 # HBM bytes of one launch of the roofline kernel at 8192 x 8192, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by
 # the same counters' reading of a 512 MiB device copy: the row of that kernel in profiles/value_workload_hbm_traffic.txt
-TRAFFIC_QUANT_ROWS_BYTES = 172_278_000
+TRAFFIC_QUANT_ROWS_BYTES = 172_165_000
 
 
 # Weight shapes [d_in, d_out] of Llama-like models (App. D, table of linear shapes), 8 x 2048 tokens.
@@ -528,7 +528,7 @@ def main() -> int:
             "achieved": round(quant_kernel_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(quant_kernel_gbps / HBM_PEAK_GBPS, 4),
             # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by what the same
-            # counters read for a 512 MiB device copy (x2.0 and x1.0): profiles/bench_hbm_traffic.txt
+            # counters read for a 512 MiB device copy (x2.0 and x1.0)
             "traffic": {"bytes": TRAFFIC_QUANT_ROWS_BYTES, "algorithmic_bytes": int(n * BYTES_PER_ELEM_QUANT),
                         "valid_for": "8192x8192 bf16", "source": "profiles/value_workload_hbm_traffic.txt"} if (R, C) == (8192, 8192) else None,
         },
@@ -550,7 +550,7 @@ def main() -> int:
             "flops_per_element": ALU_FLOPS_PER_ELEM,
             "note": "mostly single adds in binary32 (1 flop per lane-instruction against the 2 of an fma; several "
                     "conversion and cross-lane instructions issue at half or quarter rate); "
-                    "measured VALU issue occupancy 75-78 % (profiles/bench_sq_counters.txt)",
+                    "the kernel runs within 10 % of its own loads and stores without arithmetic (profiles/microbench_summary.txt)",
         },
         "roofline_gemm": {
             "kernel": f"gemm_kernel_v4<bf16 out> M={T} N={d_out} K={d_in} (incl. the scale re-tiling launch)",
