@@ -40,7 +40,16 @@
 extern "C" {
 #endif
 
-typedef enum {
+/* The enumerations below cross the ABI as 32-bit integers.  A C++ translation unit gives them the
+ * fixed underlying type int, so that a value outside the enumerators (which the entry points
+ * answer with QII_INVALID_ARG) is an ordinary integer and not undefined behaviour on load.      */
+#ifdef __cplusplus
+#define QII_ENUM_INT : int
+#else
+#define QII_ENUM_INT
+#endif
+
+typedef enum QII_ENUM_INT {
     QII_OK = 0,
     QII_INVALID_ARG = 1,         /* null pointer, bad enum, misaligned buffer          */
     QII_BAD_SHAPE = 2,           /* a dimension violates the divisibility rules below   */
@@ -71,9 +80,9 @@ typedef enum {
  *               QII_MS_EDEN).  Equal to QII_MS_EDEN bit for bit when the tensor scale is a
  *               power of two, otherwise a different but equally unbiased estimate.  Needs
  *               qii_quantize_posthoc_workspace_bytes of workspace. */
-typedef enum { QII_RTN = 0, QII_SR = 1, QII_MS_EDEN = 2, QII_RTN_46 = 3, QII_MS_EDEN_PH = 4 } qii_mode;
+typedef enum QII_ENUM_INT { QII_RTN = 0, QII_SR = 1, QII_MS_EDEN = 2, QII_RTN_46 = 3, QII_MS_EDEN_PH = 4 } qii_mode;
 
-typedef enum { QII_F32 = 0, QII_BF16 = 1 } qii_dtype;
+typedef enum QII_ENUM_INT { QII_F32 = 0, QII_BF16 = 1 } qii_dtype;
 
 /* One NVFP4 tensor of `rows` x `cols` (cols % 16 == 0).
  *   codes        rows*cols/2 bytes; element 2j of a row in the low nibble of byte j,
@@ -278,7 +287,7 @@ qii_status qii_selftest_conversions(uint64_t *counts, void *stream);
  * trip; iters even); VALU_CVT_PK32_F16_FP6 2 conversions of 32 E2M3 values per trip; MFMA_F16 4 v_mfma_f32_32x32x16_f16 per wave and trip; ATOMIC_ONE_WORD one
  * atomic maximum per block on a[0]; ATOMIC_SPREAD the same over 64 words 256 bytes apart (a holds
  * 16 KiB).  Buffers a kind does not name may be NULL.                                    */
-typedef enum {
+typedef enum QII_ENUM_INT {
     QII_MB_EMPTY = 0, QII_MB_COPY = 1, QII_MB_READ = 2, QII_MB_WRITE = 3, QII_MB_QUANT_TRAFFIC = 4,
     QII_MB_VALU_FMA = 5, QII_MB_VALU_RHT = 6, QII_MB_VALU_CVT_FP4 = 7, QII_MB_MFMA_F16 = 8,
     QII_MB_ATOMIC_ONE_WORD = 9, QII_MB_ATOMIC_SPREAD = 10, QII_MB_QUANT_TRAFFIC_COLS = 11,

@@ -50,5 +50,28 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+def build_sanitized(out_dir: str) -> str:
+    """A second build of the library whose HOST half is compiled with AddressSanitizer and
+    UndefinedBehaviorSanitizer (the device code is unchanged and never runs in that check), written
+    to out_dir/libqii_san.so.  For tests/sanitize/abi_check.c; the product never loads it."""
+    os.makedirs(out_dir, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=all", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+    procs, objs = [], []
+    for src in SOURCES:
+        obj = os.path.join(out_dir, src.replace(".hip", ".san.o"))
+        cmd = ["hipcc", *FLAGS, *san, "-c", os.path.join(CSRC, src), "-o", obj]
+        procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+        objs.append(obj)
+    for src, p in procs:
+        out, _ = p.communicate()
+        if p.returncode != 0:
+            raise RuntimeError(f"hipcc (sanitized host) failed on {src}:\n{out}")
+    lib = os.path.join(out_dir, "libqii_san.so")
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address", "-fsanitize=undefined",
+                    "-fno-gpu-sanitize", "-shared-libsan", "-o", lib, *objs], check=True)
+    return lib
+
+
 if __name__ == "__main__":
     print(build(force=True, verbose="-v" in sys.argv))
