@@ -243,7 +243,8 @@ def microbench(torch, qii, dev):
     # the GEMM's inner loop without its memory side: one block per compute unit, one wave per SIMD
     res["gemm_inner_loop_no_memory"] = {}
     for chunks, cname in ((0, "matrix_instructions_only"), (1, "with_dequantization_as_in_the_gemm"),
-                          (2, "with_one_operand_dequantized"), (3, "with_dequantization_from_packed_e2m3")):
+                          (2, "with_one_operand_dequantized"), (3, "with_dequantization_from_packed_e2m3"),
+                          (4, "matrix_instructions_only_changing_operands")):
         ms = t_ms(lambda i: qii.qii_microbench(qii.MB_MFMA_DEQUANT, None, b, chunks, 256, 4096))
         res["gemm_inner_loop_no_memory"][cname] = {"ms": round(ms, 4), "TFLOPs": round(256 * 4 * 4096 * 16 * 2 * 32 * 32 * 16 / (ms * 1e-3) / 1e12, 1)}
     # launch floor and atomics: the extra time per block over an empty kernel of the same grid

@@ -284,7 +284,8 @@ qii_status qii_selftest_conversions(uint64_t *counts, void *stream);
  * (16 matrix instructions per trip, each followed by a dequantization chunk of 2 conversions
  * and 2 packed products: n = 1 all 16 as in the GEMM, n = 2 the first 8 only, n = 0 none, n = 3 the work that
  * codes packed as E2M3 would need instead, 2 conversions of 32 values and 32 packed products per
- * trip; iters even); VALU_CVT_PK32_F16_FP6 2 conversions of 32 E2M3 values per trip; MFMA_F16 4 v_mfma_f32_32x32x16_f16 per wave and trip; ATOMIC_ONE_WORD one
+ * trip, n = 4 none again but with operands that change from one matrix instruction to the next, as
+ * real data does; iters even); VALU_CVT_PK32_F16_FP6 2 conversions of 32 E2M3 values per trip; MFMA_F16 4 v_mfma_f32_32x32x16_f16 per wave and trip; ATOMIC_ONE_WORD one
  * atomic maximum per block on a[0]; ATOMIC_SPREAD the same over 64 words 256 bytes apart (a holds
  * 16 KiB).  Buffers a kind does not name may be NULL.                                    */
 typedef enum QII_ENUM_INT {

@@ -684,7 +684,7 @@ qii_status qii_microbench(int kind, void *a, void *b, uint64_t n, int blocks, in
         return fail(QII_INVALID_ARG, "microbench: a buffer this kind uses is NULL or not 16-byte aligned");
     if ((needs_a || needs_b) && !atomic && (n == 0 || n % 16)) return fail(QII_BAD_SHAPE, "microbench: n must be a positive multiple of 16");
     if (kind == QII_MB_QUANT_TRAFFIC && (n % 262144 || n / 262144 > (1u << 20))) return fail(QII_BAD_SHAPE, "microbench: n must be a multiple of 262144 (16 rows of 8192 bf16)");
-    if (kind == QII_MB_MFMA_DEQUANT && (n > 3 || (iters & 1))) return fail(QII_INVALID_ARG, "microbench: n must be 0..3 and iters even");
+    if (kind == QII_MB_MFMA_DEQUANT && (n > 4 || (iters & 1))) return fail(QII_INVALID_ARG, "microbench: n must be 0..4 and iters even");
     if (kind == QII_MB_QUANT_TRAFFIC_COLS && n != 134217728u) return fail(QII_BAD_SHAPE, "microbench: n must be 134217728 (8192 x 8192 bf16)");
     hipError_t e = qii::launch_microbench(kind, a, b, n, blocks, iters, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, "microbench");

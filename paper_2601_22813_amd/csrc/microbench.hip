@@ -286,7 +286,14 @@ __global__ __launch_bounds__(256) void mb_valu_pk_mul_f16(float *out, int iters)
 // half of the LDS, as the GEMM's does): 16 matrix instructions on 16 accumulators per trip, each
 // followed (chunks = 1) by the GEMM's dequantization chunk, 2 FP4 -> f16 conversions and 2 packed
 // multiplies, which produce the operands of the next trip, by that chunk after the first 8 only (chunks = 2:
-// one operand dequantized, the other taken as it is), or (chunks = 0) by nothing.
+// one operand dequantized, the other taken as it is), or by nothing: with constant operands
+// (chunks = 0) or with operands that differ between consecutive matrix instructions (chunks = 3).
+__device__ __forceinline__ uint32_t mix(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7FEB352Du; x ^= x >> 15; x *= 0x846CA68Bu; x ^= x >> 16;
+    return x;
+}
+
 template <int chunks>
 __global__ __launch_bounds__(256, 1) void mb_mfma_dequant(float *out, int iters)
 {
@@ -300,8 +307,18 @@ __global__ __launch_bounds__(256, 1) void mb_mfma_dequant(float *out, int iters)
     for (int t = 0; t < 4; ++t)
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-            a[0][t][k] = a[1][t][k] = (_Float16)0.5f;
-            b[0][t][k] = b[1][t][k] = (_Float16)0.25f;
+            if (chunks == 3) {
+                // no dequantization, but operands that differ from one matrix instruction to the next and
+                // between the two alternating sets, as real data does (values +-{0.5 .. 6} * 2^{-3..4})
+                const uint32_t h0 = mix(threadIdx.x * 64u + t * 8u + k), h1 = mix(h0 + 0x9E3779B9u);
+                a[0][t][k] = (_Float16)(((float)(h0 & 15u) - 7.5f) * (float)(1u << ((h0 >> 4) & 7u)) * 0.125f);
+                a[1][t][k] = (_Float16)(((float)(h1 & 15u) - 7.5f) * (float)(1u << ((h1 >> 4) & 7u)) * 0.125f);
+                b[0][t][k] = (_Float16)(((float)((h0 >> 8) & 15u) - 7.5f) * (float)(1u << ((h0 >> 12) & 7u)) * 0.125f);
+                b[1][t][k] = (_Float16)(((float)((h1 >> 8) & 15u) - 7.5f) * (float)(1u << ((h1 >> 12) & 7u)) * 0.125f);
+            } else {
+                a[0][t][k] = a[1][t][k] = (_Float16)0.5f;
+                b[0][t][k] = b[1][t][k] = (_Float16)0.25f;
+            }
         }
     float16_t acc[4][4];
 #pragma unroll
@@ -322,7 +339,7 @@ __global__ __launch_bounds__(256, 1) void mb_mfma_dequant(float *out, int iters)
 #define QII_MB_MMA(CU, NX, I)                                                                             \
     acc[(I) >> 2][(I) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[CU][(I) >> 2], b[CU][(I) & 3],      \
                                                                     acc[(I) >> 2][(I) & 3], 0, 0, 0);     \
-    if (chunks >= 1) {                                                                                    \
+    if (chunks == 1 || chunks == 2) {                                                                     \
         if ((I) < 8) QII_MB_DQ(a[NX][((I) >> 1) & 3], raw[(I) >> 1], ((I) & 1));                          \
         else if (chunks == 1) QII_MB_DQ(b[NX][((I) >> 1) & 3], raw[(I) >> 1], ((I) & 1));                 \
     }                                                                                                     \
@@ -485,7 +502,8 @@ hipError_t launch_microbench(int kind, void *a, void *b, uint64_t n, int blocks,
         if (n == 0) hipLaunchKernelGGL(mb_mfma_dequant<0>, grid, block, 0, s, (float *)b, iters);
         else if (n == 1) hipLaunchKernelGGL(mb_mfma_dequant<1>, grid, block, 0, s, (float *)b, iters);
         else if (n == 2) hipLaunchKernelGGL(mb_mfma_dequant<2>, grid, block, 0, s, (float *)b, iters);
-        else hipLaunchKernelGGL(mb_mfma_dequant_fp6, grid, block, 0, s, (float *)b, iters);
+        else if (n == 3) hipLaunchKernelGGL(mb_mfma_dequant_fp6, grid, block, 0, s, (float *)b, iters);
+        else hipLaunchKernelGGL(mb_mfma_dequant<3>, grid, block, 0, s, (float *)b, iters);
         break;
     case QII_MB_ATOMIC_ONE_WORD: hipLaunchKernelGGL(mb_atomic, grid, block, 0, s, (uint32_t *)a, 0); break;
     case QII_MB_ATOMIC_SPREAD: hipLaunchKernelGGL(mb_atomic, grid, block, 0, s, (uint32_t *)a, 1); break;
