@@ -247,22 +247,53 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(ColsArgs a)
 
 // Abs-max pass: few long-lived blocks (two per compute unit) that stride over the tiles and fold
 // their maximum into the result with one atomic each at the very end (device-wide atomics on one
-// address are resolved one after the other, about 4 ns each).  Tiles are numbered with the four
-// chunks of a block fastest, then the groups of 32 columns.
+// address are resolved one after the other, about 10 ns each).  A block requests its next tile
+// before it works on the current one.  Tile order as in the quantizer where the shape allows it:
+// the blocks of one die walk that die's stripes of 32 column blocks, column blocks fastest.
 template <int kSrc, bool kRht>
 __global__ __launch_bounds__(256) void absmax_cols_kernel(ColsArgs a, int64_t tiles_x, int64_t tiles)
 {
     __shared__ float wave_m[4];
     const int lane = threadIdx.x & 63, q = lane & 3;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t tiles_y = tiles / tiles_x;
+    const bool striped = (tiles_y & 255) == 0 && (gridDim.x & 7u) == 0u;   // uniform
+    // the k-th tile of this block: (row block bx, column block by), or none
+    auto tile_of = [&](int64_t k, int64_t &bx, int64_t &by) -> bool {
+        if (striped) {
+            const int64_t slot = (int64_t)(blockIdx.x >> 3) + k * (gridDim.x >> 3), per = 32 * tiles_x;
+            if (slot >= tiles / 8) return false;
+            const int64_t stripe = (slot / per) * 8 + (blockIdx.x & 7u), r = slot % per;
+            by = 32 * stripe + (r & 31);
+            bx = r >> 5;
+        } else {
+            const int64_t t = (int64_t)blockIdx.x + k * gridDim.x;
+            if (t >= tiles) return false;
+            bx = t % tiles_x;
+            by = t / tiles_x;
+        }
+        return true;
+    };
     float m = 0.0f;
-    for (int64_t t = blockIdx.x; t < tiles; t += gridDim.x) {
-        const int64_t chunk = (t % tiles_x) * 4 + wave;   // wave-uniform
-        const int64_t j0 = (t / tiles_x) * 32 + 2 * (lane >> 2);
-        if (chunk * 128 < a.C) {
+    RawCols<kSrc> cur, nxt;
+    int64_t bx, by;
+    bool have = tile_of(0, bx, by);
+    bool live = have && (bx * 4 + wave) * 128 < a.C;   // wave-uniform
+    // (a clamped duplicate of a real column pair cannot change the maximum)
+    if (live) {
+        const int64_t j0 = by * 32 + 2 * (lane >> 2);
+        load_quarter_chunk_raw<kSrc>(cur, a, bx * 4 + wave, (uint32_t)(j0 < a.R ? j0 : a.R - 2), q);
+    }
+    for (int64_t k = 1; have; ++k) {
+        const bool have_n = tile_of(k, bx, by);
+        const bool live_n = have_n && (bx * 4 + wave) * 128 < a.C;
+        if (live_n) {
+            const int64_t j0 = by * 32 + 2 * (lane >> 2);
+            load_quarter_chunk_raw<kSrc>(nxt, a, bx * 4 + wave, (uint32_t)(j0 < a.R ? j0 : a.R - 2), q);
+        }
+        if (live) {
             float v[2][32];
-            // a clamped duplicate of a real column pair cannot change the maximum
-            load_quarter_chunk<kSrc, kRht>(v, a, chunk, (uint32_t)(j0 < a.R ? j0 : a.R - 2), q);
+            unpack_quarter_chunk<kSrc, kRht>(v, cur, a, q);
             if (kRht) {
                 fwht128_quad<false>(v[0], q);
                 fwht128_quad<false>(v[1], q);
@@ -272,6 +303,9 @@ __global__ __launch_bounds__(256) void absmax_cols_kernel(ColsArgs a, int64_t ti
 #pragma unroll
                 for (int h = 0; h < 2; ++h) m = fmaxf(m, group_absmax(v[e] + 16 * h));
         }
+        cur = nxt;
+        have = have_n;
+        live = live_n;
     }
     if (kRht) m = __builtin_fmaf(m, kInvSqrt128, 0.0f);   // the scaling the rotation left out
     m = wave_max(m);
