@@ -176,6 +176,58 @@ def paper_shapes(torch, qii, synth, dev):
     return out
 
 
+def inexact_gemm(torch, qii, synth, dev, T, d_in, d_out):
+    """The exploratory non-exact GEMM variants on the forward GEMM of the benchmark's layer: time including their
+    operand re-encoding pre-pass, and distance from the exact kernel's f32 result (which the GPU tests hold to 1e-5
+    of the oracle's definition).  Context for what the native block-scaled matrix instruction would give if NVFP4's
+    numerics were given up; never part of `value` or of the layer figures."""
+    X_np, W_np, _ = synth.linear_layer_bf16(T, d_in, d_out, seed=2)
+    to_dev = lambda b: torch.from_numpy(b.view(np.int16)).to(dev).view(torch.bfloat16)
+    X, W = to_dev(X_np), to_dev(W_np)
+    Xq, Wq = qii.NVFP4Tensor.empty(T, d_in), qii.NVFP4Tensor.empty(d_out, d_in)
+    ws = torch.empty(256, dtype=torch.uint8, device=dev)
+    qii.qii_quantize_nvfp4(X, False, qii.RTN, 0, 0, 0, None, Xq, ws)
+    qii.qii_quantize_nvfp4(W, False, qii.RTN, 0, 0, 0, None, Wq, ws)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps=5):
+        out = []
+        for i in range(reps + 1):
+            e0, e1 = ev(), ev()
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            if i:
+                out.append(e0.elapsed_time(e1))
+        return float(np.mean(out))
+
+    flops = 2.0 * T * d_in * d_out
+    C_ex = torch.empty((T, d_out), dtype=torch.float32, device=dev)
+    C16 = torch.empty((T, d_out), dtype=torch.bfloat16, device=dev)
+    gws = torch.empty(max(256, qii.qii_gemm_workspace_bytes(T, d_out, d_in)), dtype=torch.uint8, device=dev)
+    qii.qii_gemm_nvfp4(Xq, Wq, C_ex, gws)
+    ms = timed(lambda: qii.qii_gemm_nvfp4(Xq, Wq, C16, gws))
+    res = {"shape": {"M": T, "N": d_out, "K": d_in},
+           "exact": {"ms": round(ms, 4), "TFLOPs": round(flops / (ms * 1e-3) / 1e12, 1)},
+           "note": "non-exact variants, measurement only (qii_gemm_nvfp4_inexact; a plain kernel of 8 waves per tile without "
+                   "software pipelining): times are for bf16 output and include the pre-pass that re-encodes both operands; "
+                   "errors are of the f32 output against the exact kernel's, relative to the root mean square of its entries"}
+    rms = float(C_ex.double().pow(2).mean().sqrt())
+    C = torch.empty_like(C_ex)
+    for name, variant in (("fp8_e4m3_pow2_scale_per_32", qii.INEXACT_FP8), ("fp4_zero_padded_pow2_scales", qii.INEXACT_FP4_POW2)):
+        w = torch.empty(max(256, qii.qii_gemm_inexact_workspace_bytes(T, d_out, d_in, variant)), dtype=torch.uint8, device=dev)
+        ms = timed(lambda: qii.qii_gemm_nvfp4_inexact(Xq, Wq, C16, variant, w))
+        qii.qii_gemm_nvfp4_inexact(Xq, Wq, C, variant, w)
+        torch.cuda.synchronize()
+        d = (C - C_ex).double()
+        res[name] = {"ms": round(ms, 4), "TFLOPs": round(flops / (ms * 1e-3) / 1e12, 1),
+                     "rms_error_over_rms": round(float(d.pow(2).mean().sqrt()) / rms, 5),
+                     "max_error_over_rms": round(float(d.abs().max()) / rms, 4)}
+        del w, d
+    return res
+
+
 def microbench(torch, qii, dev):
     """Machine limits behind the roofline arguments, each one launch of qii_microbench timed with events (mean of 5
     after 2 warm-ups): streaming rates, the quantizer's traffic pattern without arithmetic, issue rates, atomics."""
@@ -590,6 +642,7 @@ def main() -> int:
         torch.cuda.empty_cache()
         result["configs"] = large_configs(torch, qii, dev)
         result["paper_shapes"] = paper_shapes(torch, qii, synth, dev)
+        result["inexact_gemm"] = inexact_gemm(torch, qii, synth, dev, T, d_in, d_out)
 
     if not args.no_cpu_baseline and do_q:
         import oracle

@@ -269,6 +269,24 @@ size_t qii_linear_bwd_mode_workspace_bytes(int64_t T, int64_t d_in, int64_t d_ou
  * All eight must read 0.  Takes a few hundred milliseconds.                              */
 qii_status qii_selftest_conversions(uint64_t *counts, void *stream);
 
+/* Exploratory NON-EXACT variants of qii_gemm_nvfp4 (measurement only; no other entry point of the
+ * library reaches them, and their results do not meet the tolerance of the exact GEMM).  They show
+ * what gfx950's native block-scaled matrix instruction (one power-of-two scale per 32 elements of
+ * K) delivers when NVFP4's numerics (Sec. 5: products of the dequantized operands) are given up:
+ *   QII_INEXACT_FP8       operand elements rounded to FP8 E4M3 relative to a power-of-two scale per
+ *                         32 elements of K
+ *   QII_INEXACT_FP4_POW2  FP4 codes as they are, each group's E4M3 scale rounded to the nearest
+ *                         power of two, groups zero-padded to the instruction's 32-element scale
+ *                         blocks
+ * K must be a multiple of 64.
+ * Arguments as qii_gemm_nvfp4; ws: qii_gemm_inexact_workspace_bytes(M, N, K, variant) bytes, 256-byte
+ * aligned, required (it receives both operands re-encoded).  Errors as qii_gemm_nvfp4, plus
+ * QII_BAD_SHAPE for a K the variant does not take.                                         */
+typedef enum QII_ENUM_INT { QII_INEXACT_FP8 = 0, QII_INEXACT_FP4_POW2 = 1 } qii_inexact_variant;
+qii_status qii_gemm_nvfp4_inexact(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_dtype c_dt, int64_t ldc,
+                                  qii_inexact_variant variant, void *ws, size_t ws_bytes, void *stream);
+size_t qii_gemm_inexact_workspace_bytes(int64_t M, int64_t N, int64_t K, qii_inexact_variant variant);
+
 /* Microbenchmarks of the machine limits the kernels are measured against (a measurement aid,
  * not an operation of the paper): one launch per call, timed by the caller with events.
  *   a, b   device buffers (see the kinds); n bytes, a multiple of 16

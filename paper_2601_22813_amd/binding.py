@@ -24,7 +24,7 @@ EXPORTS = [
     "qii_gemm_nvfp4", "qii_linear_fwd", "qii_linear_fwd_mode", "qii_linear_bwd", "qii_linear_bwd_mode",
     "qii_quantize_workspace_bytes", "qii_quantize_posthoc_workspace_bytes", "qii_linear_bwd_mode_workspace_bytes",
     "qii_gemm_workspace_bytes", "qii_linear_fwd_workspace_bytes", "qii_linear_bwd_workspace_bytes",
-    "qii_derive_seed", "qii_status_string", "qii_last_error", "qii_version", "qii_selftest_conversions", "qii_microbench",
+    "qii_derive_seed", "qii_status_string", "qii_last_error", "qii_version", "qii_selftest_conversions", "qii_microbench", "qii_gemm_nvfp4_inexact", "qii_gemm_inexact_workspace_bytes",
     "qii_quantize_nvfp4_noalloc", "qii_gemm_nvfp4_amax", "qii_linear_fwd_amax",
     "qii_quantize_pair_nvfp4", "qii_quantize_pair_workspace_bytes",
 ]
@@ -66,6 +66,10 @@ def lib() -> ctypes.CDLL:
         L.qii_dequantize_nvfp4.argtypes = [nv, vp, vp]
         L.qii_gemm_nvfp4.argtypes = [nv, nv, vp, c.c_int, i64, vp, sz, vp]
         L.qii_gemm_nvfp4_amax.argtypes = [nv, nv, vp, c.c_int, i64, vp, vp, sz, vp]
+        L.qii_gemm_nvfp4_inexact.argtypes = [nv, nv, vp, c.c_int, i64, c.c_int, vp, sz, vp]
+        L.qii_gemm_nvfp4_inexact.restype = c.c_int
+        L.qii_gemm_inexact_workspace_bytes.argtypes = [i64, i64, i64, c.c_int]
+        L.qii_gemm_inexact_workspace_bytes.restype = sz
         L.qii_gemm_nvfp4_amax.restype = c.c_int
         L.qii_linear_fwd_amax.argtypes = [vp, vp, c.c_int, i64, i64, i64, c.c_int, vp, vp, vp, c.c_int, vp, nv, nv, vp, sz, vp]
         L.qii_linear_fwd_amax.restype = c.c_int
@@ -276,6 +280,21 @@ def qii_gemm_nvfp4(A: NVFP4Tensor, B: NVFP4Tensor, C: torch.Tensor, ws: torch.Te
     sa, sb = A.c_struct(), B.c_struct()
     _check(lib().qii_gemm_nvfp4(ctypes.byref(sa), ctypes.byref(sb), C.data_ptr(), _dt(C), C.stride(0),
                                 _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(), _stream()))
+
+
+INEXACT_FP8, INEXACT_FP4_POW2 = 0, 1
+
+
+def qii_gemm_inexact_workspace_bytes(M: int, N: int, K: int, variant: int) -> int:
+    return int(lib().qii_gemm_inexact_workspace_bytes(M, N, K, variant))
+
+
+def qii_gemm_nvfp4_inexact(A: NVFP4Tensor, B: NVFP4Tensor, C: torch.Tensor, variant: int, ws: torch.Tensor):
+    """Exploratory non-exact variants of the GEMM (measurement only; see include/qii.h)."""
+    _rows_contig(C)
+    sa, sb = A.c_struct(), B.c_struct()
+    _check(lib().qii_gemm_nvfp4_inexact(ctypes.byref(sa), ctypes.byref(sb), C.data_ptr(), _dt(C), C.stride(0), variant,
+                                        _ptr(ws), ws.numel() * ws.element_size(), _stream()))
 
 
 def qii_gemm_nvfp4_amax(A: NVFP4Tensor, B: NVFP4Tensor, C: torch.Tensor, amax_c: torch.Tensor | None,

@@ -672,6 +672,30 @@ qii_status qii_selftest_conversions(uint64_t *counts, void *stream)
     return QII_OK;
 }
 
+size_t qii_gemm_inexact_workspace_bytes(int64_t M, int64_t N, int64_t K, qii_inexact_variant variant)
+{
+    if (variant != QII_INEXACT_FP8 && variant != QII_INEXACT_FP4_POW2) return 0;
+    return align_up(qii::gemm_inexact_workspace_bytes(M, N, K, (int)variant));
+}
+
+qii_status qii_gemm_nvfp4_inexact(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_dtype c_dt, int64_t ldc,
+                                  qii_inexact_variant variant, void *ws, size_t ws_bytes, void *stream)
+{
+    if (variant != QII_INEXACT_FP8 && variant != QII_INEXACT_FP4_POW2) return fail(QII_INVALID_ARG, "bad variant %d", (int)variant);
+    qii_status st = check_gemm_args(A, B, C, c_dt, ldc);
+    if (st != QII_OK) return st;
+    const int64_t slice = 64;
+    if (A->cols % slice != 0) return fail(QII_BAD_SHAPE, "this variant needs K to be a multiple of %lld", (long long)slice);
+    if (!aligned(A->scales, 8) || !aligned(B->scales, 8) || !aligned(A->codes, 16) || !aligned(B->codes, 16))
+        return fail(QII_INVALID_ARG, "misaligned operand");
+    const size_t need = qii_gemm_inexact_workspace_bytes(A->rows, B->rows, A->cols, variant);
+    if (A->rows * B->rows != 0 && (!ws || ws_bytes < need || !aligned(ws, kSlot)))
+        return fail(QII_WORKSPACE_TOO_SMALL, "qii_gemm_nvfp4_inexact needs %zu bytes of 256-byte aligned workspace", need);
+    hipError_t e = qii::launch_gemm_inexact(*A, *B, C, c_dt == QII_BF16, ldc, (int)variant, ws, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, "gemm (non-exact variant)");
+    return QII_OK;
+}
+
 qii_status qii_microbench(int kind, void *a, void *b, uint64_t n, int blocks, int iters, void *stream)
 {
     if (kind < QII_MB_EMPTY || kind > QII_MB_VALU_CVT_PK32_F16_FP6) return fail(QII_INVALID_ARG, "microbench: unknown kind");

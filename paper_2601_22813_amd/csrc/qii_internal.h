@@ -93,6 +93,10 @@ hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is
 
 // sweeps of the hardware conversions and short division sequences against their value-space
 // rules; counts[0..7] (device) receive the numbers of mismatches (selftest.hip)
+// exploratory non-exact GEMM variants (gemm_inexact.hip); ws as gemm_inexact_workspace_bytes says
+size_t gemm_inexact_workspace_bytes(int64_t M, int64_t N, int64_t K, int variant);
+hipError_t launch_gemm_inexact(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is_bf16, int64_t ldc, int variant,
+                               void *ws, hipStream_t s);
 hipError_t launch_selftest_conversions(unsigned long long *counts, hipStream_t s);
 hipError_t launch_microbench(int kind, void *a, void *b, uint64_t n, int blocks, int iters, hipStream_t s);
 
