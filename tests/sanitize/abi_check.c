@@ -88,6 +88,14 @@ int main(void)
     EXPECT(qii_gemm_nvfp4(&a, &b, P(0x3002), QII_F32, 8, NULL, 0, NULL), QII_INVALID_ARG);
     EXPECT(qii_gemm_nvfp4(NULL, &b, P(0x3000), QII_F32, 8, NULL, 0, NULL), QII_INVALID_ARG);
     EXPECT(qii_gemm_nvfp4_amax(&a, &b, P(0x3000), QII_F32, 8, P(0x5002), NULL, 0, NULL), QII_INVALID_ARG);
+    EXPECT(qii_gemm_nvfp4_inexact(&a, &b, P(0x3000), QII_F32, 8, (qii_inexact_variant)5, P(0x4000), (size_t)1 << 30, NULL), QII_INVALID_ARG);
+    EXPECT(qii_gemm_nvfp4_inexact(&a, &b, P(0x3000), QII_F32, 8, QII_INEXACT_FP8, P(0x4000), (size_t)1 << 30, NULL), QII_BAD_SHAPE);   /* K = 48 */
+    a.cols = b.cols = 64;
+    EXPECT(qii_gemm_nvfp4_inexact(&a, &b, P(0x3000), QII_F32, 8, QII_INEXACT_FP4_POW2, NULL, 0, NULL), QII_WORKSPACE_TOO_SMALL);
+    EXPECT(qii_gemm_nvfp4_inexact(&a, &b, NULL, QII_F32, 8, QII_INEXACT_FP8, P(0x4000), (size_t)1 << 30, NULL), QII_INVALID_ARG);
+    for (int a_ = 0; a_ < nd; ++a_)
+        for (int c_ = 0; c_ < nd; c_ += 3)
+            for (int v = 0; v <= 2; ++v) sink ^= qii_gemm_inexact_workspace_bytes(dims[a_], dims[nd - 1 - a_], dims[c_], (qii_inexact_variant)v);
     /* layer passes: everything is checked before the first launch */
     const int64_t T = 256, d_in = 128, d_out = 384;
     qii_nvfp4 xq = {P(0x10000), P(0x20000), P(0x30000), T, d_in}, wq = {P(0x40000), P(0x50000), P(0x60000), d_out, d_in};
