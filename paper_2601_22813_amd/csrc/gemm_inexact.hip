@@ -17,10 +17,11 @@
 // A pre-pass writes both operands as images in the order of the kernel's LDS stages, per (row tile
 // of 256, slice): 16 KiB of element bytes, row r keeping its 16-byte segment s in slot
 // 4r + (s ^ ((r >> 2) & 3)), and the block scales as E8M0 bytes [row][blocks of the slice].  A slice
-// is 64 elements of K: one instruction step for FP8, two for FP4 (whose image holds the padding).  The kernel
-// streams slices through three LDS stages with linear LDS-direct loads (one barrier per slice) and
-// reads fragments one step ahead; tile shape, wave arrangement, tile order and epilogue are those
-// of the exact kernel.
+// is 64 elements of K: one instruction step for FP8, two for FP4 (whose image holds the padding
+// zeros, so that a lane's operand is one 16-byte read).  The kernel is deliberately plain: the
+// exact kernel's 256 x 256 tile and tile order, but 8 waves of 128 x 64 (two per SIMD, which cover
+// each other's LDS latency: a step reads its operands, waits and multiplies), three LDS stages
+// filled by linear LDS-direct loads two slices ahead, and stores straight from the accumulators.
 #include "gemm_common.h"
 #include "qii_device.h"
 #include "qii_internal.h"
@@ -35,7 +36,7 @@ constexpr int kImgBytes = 16384;     // element bytes of one operand per (row ti
 constexpr int kImgScales = 2048;     // room for its scale bytes (FP8 uses 512, FP4 1024)
 constexpr int kOffIA = 0, kOffIB = kImgBytes, kOffISA = 2 * kImgBytes, kOffISB = 2 * kImgBytes + kImgScales;
 constexpr int kStageI = 2 * kImgBytes + 2 * kImgScales;   // 36 KiB
-constexpr int kSmemI = 3 * kStageI;                        // 108 KiB, reused by the epilogue
+constexpr int kSmemI = 3 * kStageI;                        // 108 KiB
 
 template <int kFmt> struct Fmt;
 template <> struct Fmt<0> {   // FP8 E4M3
@@ -171,9 +172,9 @@ __device__ __forceinline__ void issue_slice_loads_i(uint8_t *stage, const uint8_
 constexpr int kLoadsI = 6;   // LDS-direct loads per thread and slice
 
 // Operands of one step of one wave (128 x 64 of the tile): 4 row blocks of A, 2 of B, as the LDS
-// reads deliver them (FP8: two 16-byte pieces each; FP4: 8 bytes) and their scale bytes.  The
-// matrix instruction takes consecutive registers per operand; they are put together after the wait
-// (FP4: the upper registers are the zero padding).
+// reads deliver them (FP8: two 16-byte pieces each; FP4: one, codes and padding) and their scale
+// bytes.  The matrix instruction takes consecutive registers per operand; they are put together
+// after the wait.
 template <int kFmt> struct FragsI;
 template <> struct FragsI<0> {
     u32x4 alo[4], ahi[4], blo[2], bhi[2];
