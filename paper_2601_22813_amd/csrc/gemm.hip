@@ -540,7 +540,7 @@ __device__ __forceinline__ void mma_step(floatx16 (&acc)[4][4], const Frags &cu,
 #undef QII_MMA
 }
 
-template <bool kBf16Out>
+template <bool kBf16Out, bool kSplit>
 __global__ __launch_bounds__(256, 1) void gemm_kernel_v4(const uint8_t *__restrict__ a_codes,
                                                          const uint8_t *__restrict__ a_tiled,
                                                          const float *__restrict__ a_ts,
@@ -548,14 +548,21 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel_v4(const uint8_t *__restri
                                                          const uint8_t *__restrict__ b_tiled,
                                                          const float *__restrict__ b_ts, int64_t M,
                                                          int64_t N, int64_t K, void *__restrict__ Cout,
-                                                         int64_t ldc, int tiles_m, int tiles_n, uint32_t *amax_out)
+                                                         int64_t ldc, int tiles_m, int tiles_n, uint32_t *amax_out,
+                                                         int ksplit_arg, float *__restrict__ partial)
 {
     extern __shared__ __align__(16) uint8_t smem[];
+    // kSplit (few output tiles, long K): ksplit blocks share an output tile, each taking a
+    // contiguous range of K tiles and leaving its unscaled f32 partial tile in `partial`
+    // ([split][tiles_m * 256][tiles_n * 256]); splitk_reduce_kernel adds them up in a fixed order.
+    // (A separate instantiation: the plain kernel keeps its registers.)
+    const int ksplit = kSplit ? ksplit_arg : 1;
+    const int split = kSplit ? (int)(blockIdx.x % (unsigned)ksplit) : 0;
     // XCD-aware order: consecutive block ids land on different XCDs (8 of them, each with its
     // own L2), so give every XCD a contiguous run of tiles; within the run, tiles are walked in
     // groups of 4 tile rows, column by column, so that the ~32 tiles an XCD works on at once
     // share 4 A panels and 8 B panels (about 3.5 MiB at K = 2048) instead of 1 + 32.
-    int tile = blockIdx.x;
+    int tile = (int)(blockIdx.x / (unsigned)ksplit);
     const int ntiles = tiles_m * tiles_n;
     if ((ntiles & 7) == 0) tile = (tile & 7) * (ntiles >> 3) + (tile >> 3);
     constexpr int kGroupM = 4;
@@ -586,12 +593,15 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel_v4(const uint8_t *__restri
         for (int j = 0; j < 4; ++j) fa.xo[j] = (uint32_t)(((2 * j + kb) ^ (li & 7)) * 16);
     }
 
-    const int ktiles = (int)(K / BK4);
-    issue_tile_loads4(smem, a_codes, a_tiled, b_codes, b_tiled, M, N, K, m0, n0, 0, wave);
+    // this block's K tiles: [kt0, kt0 + ktiles)
+    const int ktotal = (int)(K / BK4);
+    const int kt0 = (int)((int64_t)ktotal * split / ksplit);
+    const int ktiles = (int)((int64_t)ktotal * (split + 1) / ksplit) - kt0;
+    issue_tile_loads4(smem, a_codes, a_tiled, b_codes, b_tiled, M, N, K, m0, n0, kt0, wave);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (ktiles > 1)
-        issue_tile_loads4(smem + kStage4Bytes, a_codes, a_tiled, b_codes, b_tiled, M, N, K, m0, n0, 1, wave);
+        issue_tile_loads4(smem + kStage4Bytes, a_codes, a_tiled, b_codes, b_tiled, M, N, K, m0, n0, kt0 + 1, wave);
 
     // Pipeline over K, in steps of 16 columns of K per lane half (4 steps = one 64-wide slice,
     // 4 slices = one tile).  While step n multiplies, the fragments of step n+1 are dequantized;
@@ -639,7 +649,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel_v4(const uint8_t *__restri
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (kt + 2 < ktiles)
-            issue_tile_loads4(smem + cur_off, a_codes, a_tiled, b_codes, b_tiled, M, N, K, m0, n0, kt + 2, wave);
+            issue_tile_loads4(smem + cur_off, a_codes, a_tiled, b_codes, b_tiled, M, N, K, m0, n0, kt0 + kt + 2, wave);
         // (after the last tile the two reads below fetch a stale stage; the values are never used)
         frag_read_issue<0>(fe, fa, nxt_off);
         mma_step<0>(acc, y, x, fo);
@@ -654,16 +664,86 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel_v4(const uint8_t *__restri
     // the last read block is still in flight: its registers and the stages are reused below
     frag_read_wait(fo);
     __syncthreads();
+    if (kSplit) {
+        const int64_t mp = (int64_t)tiles_m * BM, np = (int64_t)tiles_n * BN;
+        store_tile_through_lds<false>(acc, smem, 1.0f, partial + (int64_t)split * mp * np, np, mp, np, m0, n0, wave, wm, wn, lane, li,
+                                      kb, nullptr);
+        return;
+    }
     store_tile_through_lds<kBf16Out>(acc, smem, (*a_ts) * (*b_ts), Cout, ldc, M, N, m0, n0, wave, wm, wn, lane, li, kb, amax_out);
 }
 
+// C = (x32_A * x32_B) * sum over the splits, in the order of the splits; 4 consecutive columns per
+// thread, at most 512 blocks that stride over the matrix (one atomic per block when max |C| is wanted)
+template <bool kBf16Out>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partial, int ksplit, int64_t M, int64_t N,
+                                                            int64_t mp, int64_t np, const float *__restrict__ a_ts,
+                                                            const float *__restrict__ b_ts, void *__restrict__ Cout, int64_t ldc,
+                                                            uint32_t *amax_out)
+{
+    __shared__ float wave_m[4];
+    const float ts = (*a_ts) * (*b_ts);
+    const int64_t quads = (N + 3) / 4, items = M * quads, stride = (int64_t)gridDim.x * blockDim.x;
+    float cmax = 0.0f;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < items; idx += stride) {
+        const int64_t row = idx / quads, col = (idx % quads) * 4;
+        float4 acc = *reinterpret_cast<const float4 *>(partial + row * np + col);   // (np is a multiple of 256: the quad is inside the buffer)
+        for (int s = 1; s < ksplit; ++s) {
+            const float4 p = *reinterpret_cast<const float4 *>(partial + (int64_t)s * mp * np + row * np + col);
+            acc.x += p.x; acc.y += p.y; acc.z += p.z; acc.w += p.w;
+        }
+        const float v[4] = {acc.x * ts, acc.y * ts, acc.z * ts, acc.w * ts};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (col + e < N) {
+                if (kBf16Out) {
+                    const uint32_t b = f32_to_bf16_bits(v[e]);
+                    reinterpret_cast<uint16_t *>(Cout)[row * ldc + col + e] = (uint16_t)b;
+                    cmax = fmaxf(cmax, fabsf(u2f(b << 16)));
+                } else {
+                    reinterpret_cast<float *>(Cout)[row * ldc + col + e] = v[e];
+                    cmax = fmaxf(cmax, fabsf(v[e]));
+                }
+            }
+    }
+    if (amax_out) {   // uniform
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) cmax = fmaxf(cmax, __shfl_xor(cmax, off));
+        if ((threadIdx.x & 63) == 0) wave_m[threadIdx.x >> 6] = cmax;
+        __syncthreads();
+        if (threadIdx.x == 0) atomicMax(amax_out, f2u(fmaxf(fmaxf(wave_m[0], wave_m[1]), fmaxf(wave_m[2], wave_m[3]))));
+    }
+}
+
 }  // namespace
+
+// Few output tiles and a long K leave most compute units idle (2048 x 2048 x 32768, the weight
+// gradient of a small layer, has 64 tiles for 256 units): then several blocks share a tile.  At
+// least 4 K tiles per block, at most 8 blocks per tile, about one block per compute unit.
+static int splitk_factor(int64_t M, int64_t N, int64_t K)
+{
+    if (K % BK4 != 0) return 1;
+    const int64_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN), ktiles = K / BK4;
+    if (tiles == 0 || tiles > 128) return 1;
+    int64_t s = 256 / tiles;
+    if (s > ktiles / 4) s = ktiles / 4;
+    if (s > 8) s = 8;
+    return s >= 2 ? (int)s : 1;
+}
+
+static size_t scales_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    const int64_t mp = (M + 255) / 256 * 256, np = (N + 255) / 256 * 256;
+    return (size_t)((mp + np) * (K / 16));
+}
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
     if (K % BK4 != 0) return 0;
     const int64_t mp = (M + 255) / 256 * 256, np = (N + 255) / 256 * 256;
-    return (size_t)((mp + np) * (K / 16));
+    const int s = splitk_factor(M, N, K);
+    const size_t sc = scales_workspace_bytes(M, N, K);
+    return s > 1 ? (sc + 255) / 256 * 256 + (size_t)s * mp * np * 4 : sc;
 }
 
 hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is_bf16, int64_t ldc,
@@ -678,25 +758,55 @@ hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is
     if (M == 0 || N == 0) return hipSuccess;
     const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
-    const size_t need = gemm_workspace_bytes(M, N, K);
+    const size_t need = K % BK4 == 0 ? scales_workspace_bytes(M, N, K) : 0;
     if (K % BK4 == 0 && ws && ws_bytes >= need && (reinterpret_cast<uintptr_t>(ws) & 15) == 0 &&
         (reinterpret_cast<uintptr_t>(A.scales) & 15) == 0 && (reinterpret_cast<uintptr_t>(B.scales) & 15) == 0) {
         uint8_t *a_tiled = reinterpret_cast<uint8_t *>(ws);
         uint8_t *b_tiled = a_tiled + (M + 255) / 256 * 256 * (K / 16);
+        // several blocks per tile when the grid would leave most compute units idle and the caller's
+        // workspace has room for their partial tiles (behind the scales, 256-byte aligned)
+        int ksplit = splitk_factor(M, N, K);
+        const size_t poff = (need + 255) / 256 * 256;
+        const int64_t mp = tiles_m * BM, np = tiles_n * BN;
+        if (ksplit > 1 && ws_bytes < poff + (size_t)ksplit * mp * np * 4) ksplit = 1;
+        float *partial = ksplit > 1 ? reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + poff) : nullptr;
+        const dim3 sgrid((unsigned)(tiles_m * tiles_n * ksplit));
         const int64_t na = M * (K / 256), nb = N * (K / 256);
         hipLaunchKernelGGL(retile_scales_kernel, dim3((unsigned)((na + nb + 255) / 256)), dim3(256), 0, s, A.scales,
                            a_tiled, M, B.scales, b_tiled, N, K);
         hipError_t e;
         if (c_is_bf16) {
-            e = allow_dynamic_lds(gemm_kernel_v4<true>, kSmem4);
+            e = allow_dynamic_lds(gemm_kernel_v4<true, false>, kSmem4);
             if (e != hipSuccess) return e;
-            hipLaunchKernelGGL(gemm_kernel_v4<true>, grid, block, kSmem4, s, A.codes, a_tiled, A.tensor_scale,
-                               B.codes, b_tiled, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n, amax_out);
+            e = allow_dynamic_lds(gemm_kernel_v4<true, true>, kSmem4);
+            if (e != hipSuccess) return e;
+            if (ksplit > 1)
+                hipLaunchKernelGGL((gemm_kernel_v4<true, true>), sgrid, block, kSmem4, s, A.codes, a_tiled, A.tensor_scale, B.codes,
+                                   b_tiled, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n, amax_out, ksplit, partial);
+            else
+                hipLaunchKernelGGL((gemm_kernel_v4<true, false>), sgrid, block, kSmem4, s, A.codes, a_tiled, A.tensor_scale, B.codes,
+                                   b_tiled, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n, amax_out, 1, partial);
         } else {
-            e = allow_dynamic_lds(gemm_kernel_v4<false>, kSmem4);
+            e = allow_dynamic_lds(gemm_kernel_v4<false, false>, kSmem4);
             if (e != hipSuccess) return e;
-            hipLaunchKernelGGL(gemm_kernel_v4<false>, grid, block, kSmem4, s, A.codes, a_tiled, A.tensor_scale,
-                               B.codes, b_tiled, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n, amax_out);
+            e = allow_dynamic_lds(gemm_kernel_v4<false, true>, kSmem4);
+            if (e != hipSuccess) return e;
+            if (ksplit > 1)
+                hipLaunchKernelGGL((gemm_kernel_v4<false, true>), sgrid, block, kSmem4, s, A.codes, a_tiled, A.tensor_scale, B.codes,
+                                   b_tiled, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n, amax_out, ksplit, partial);
+            else
+                hipLaunchKernelGGL((gemm_kernel_v4<false, false>), sgrid, block, kSmem4, s, A.codes, a_tiled, A.tensor_scale, B.codes,
+                                   b_tiled, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n, amax_out, 1, partial);
+        }
+        if (ksplit > 1) {
+            const int64_t items = M * ((N + 3) / 4);
+            const dim3 rgrid((unsigned)(items / 256 + 1 < 512 ? items / 256 + 1 : 512));
+            if (c_is_bf16)
+                hipLaunchKernelGGL(splitk_reduce_kernel<true>, rgrid, dim3(256), 0, s, partial, ksplit, M, N, mp, np, A.tensor_scale,
+                                   B.tensor_scale, C, ldc, amax_out);
+            else
+                hipLaunchKernelGGL(splitk_reduce_kernel<false>, rgrid, dim3(256), 0, s, partial, ksplit, M, N, mp, np, A.tensor_scale,
+                                   B.tensor_scale, C, ldc, amax_out);
         }
         return hipGetLastError();
     }

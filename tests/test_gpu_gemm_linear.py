@@ -66,6 +66,40 @@ def test_gemm_ragged_shapes(oracle, M, N, K):
     check(gemm_gpu(qa, qb, torch.bfloat16, ldc=N + 3, use_ws=False), ref, absum, True)
 
 
+@pytest.mark.parametrize("M,N,K", [(512, 512, 8192), (300, 520, 4096), (256, 1024, 2048)])
+def test_gemm_few_tiles_long_k_shares_tiles_between_blocks(oracle, M, N, K):
+    """Shapes with few output tiles and a long K run several blocks per tile (partial tiles in the
+    workspace, added up in a fixed order): same tolerance, same result on a repeated call, and the
+    emitted max |C| is that of the stored values; without room for the partial tiles the plain path runs."""
+    rng = np.random.default_rng(M + N + K)
+    a = (rng.standard_t(3, size=(M, K)) * 0.1).astype(np.float32)
+    b = rng.standard_normal((N, K)).astype(np.float32)
+    qa = oracle.quantize(a, oracle.RTN, rht_group=0)
+    qb = oracle.quantize(b, oracle.MS_EDEN, rht_group=128, seed_sr=4)
+    ref, absum = oracle.gemm(qa, qb, with_abs=True)
+    need = qii.qii_gemm_workspace_bytes(M, N, K)
+    tiles = -(-M // 256) * -(-N // 256)
+    assert need > (M + 255) // 256 * 256 * (K // 16) + (N + 255) // 256 * 256 * (K // 16) + 2 * tiles * 65536 * 4 - 1   # room for >= 2 partial tiles per tile
+    print(f"gemm {M}x{N}x{K}, workspace {need}", flush=True)
+    c1 = gemm_gpu(qa, qb, torch.float32, ldc=N + 8)
+    check(c1, ref, absum, False)
+    assert np.array_equal(c1, gemm_gpu(qa, qb, torch.float32, ldc=N + 8))
+    check(gemm_gpu(qa, qb, torch.bfloat16), ref, absum, True)
+    A, B = nv_to_dev(qa), nv_to_dev(qb)
+    for dtype in (torch.float32, torch.bfloat16):
+        C = torch.empty((M, N), dtype=dtype, device="cuda")
+        amax = torch.full((1,), -1.0, dtype=torch.float32, device="cuda")
+        qii.qii_gemm_nvfp4_amax(A, B, C, amax, ws(need))
+        torch.cuda.synchronize()
+        assert float(amax[0]) == float(C.float().abs().max())
+    # a workspace that only holds the re-tiled scales: one block per tile
+    small = ws((M + 255) // 256 * 256 * (K // 16) + (N + 255) // 256 * 256 * (K // 16))
+    C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    qii.qii_gemm_nvfp4(A, B, C, small)
+    torch.cuda.synchronize()
+    check(C.cpu().numpy().astype(np.float64), ref, absum, False)
+
+
 def test_gemm_unit_scales_is_exact(oracle):
     # every scale byte 1.0 and tensor scale 1: all partial sums are multiples of 1/4 below 2^24,
     # so the f32 result must equal the integer result exactly whatever the accumulation order
