@@ -717,18 +717,32 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 
 }  // namespace
 
-// Few output tiles and a long K leave most compute units idle (2048 x 2048 x 32768, the weight
-// gradient of a small layer, has 64 tiles for 256 units): then several blocks share a tile.  At
-// least 4 K tiles per block, at most 8 blocks per tile, about one block per compute unit.
+// A grid of fewer tiles than compute units leaves many of them idle (2048 x 2048 x 32768, the weight
+// gradient of a small layer, has 64 tiles for 256 units; 3072 x 3072 has 144).  Then several blocks
+// share a tile.  The number of blocks per tile (at most 8, at least 4 K tiles each) minimises a
+// small cost model fitted to measurements: rounds of the grid times the K tiles of a block (about
+// 6 us per K tile, 5 us per round for a tile's first loads and its stores) plus the reduction pass
+// over the partial tiles (written once, read once: about 0.1 us per tile and pass); sharing is used
+// when the model promises at least 12 % (measured: 2048 x 2048 x 32768 615 -> 244 us with 4 blocks
+// per tile, 3072 x 3072 x 16384 340 -> 302 us with 3; 6144 x 2048 x 32768 would gain 5 % for 200 MiB
+// of partial tiles and stays plain).
 static int splitk_factor(int64_t M, int64_t N, int64_t K)
 {
     if (K % BK4 != 0) return 1;
     const int64_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN), ktiles = K / BK4;
-    if (tiles == 0 || tiles > 128) return 1;
-    int64_t s = 256 / tiles;
-    if (s > ktiles / 4) s = ktiles / 4;
-    if (s > 8) s = 8;
-    return s >= 2 ? (int)s : 1;
+    if (tiles == 0 || tiles >= 256) return 1;
+    const double plain_us = 6.0 * (double)ktiles + 5.0;
+    int best = 1;
+    double best_us = 0.88 * plain_us;
+    for (int s = 2; s <= 8 && ktiles / s >= 4; ++s) {
+        const int64_t rounds = (tiles * s + 255) / 256;
+        const double us = (double)rounds * (6.0 * (double)((ktiles + s - 1) / s) + 5.0) + 0.1 * (double)((s + 1) * tiles);
+        if (us < best_us) {
+            best = s;
+            best_us = us;
+        }
+    }
+    return best;
 }
 
 static size_t scales_workspace_bytes(int64_t M, int64_t N, int64_t K)
