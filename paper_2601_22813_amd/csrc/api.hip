@@ -99,8 +99,10 @@ qii_status nvfp4_source(const qii_nvfp4 *in, int transpose, int rht_group, qii::
 qii_status quantize_source(const qii::Source &src, int64_t R, int64_t C, qii_mode mode, int rht_group,
                            uint64_t seed_rht, uint64_t seed_sr, const float *amax_in,
                            const qii_nvfp4 *out, float *amax_slot, float *tbuf, hipStream_t s,
-                           bool slot_zeroed = false)
+                           bool slot_zeroed = false, bool tiled_scales = false)
 {
+    // tiled_scales (post hoc scheme only, C a multiple of 256, out->scales with room for R rounded up
+    // to 256 rows): the scale bytes go out in the layout the main GEMM kernel reads
     if (mode != QII_RTN && mode != QII_SR && mode != QII_MS_EDEN && mode != QII_RTN_46 && mode != QII_MS_EDEN_PH)
         return fail(QII_INVALID_ARG, "bad mode %d", (int)mode);
     qii_status st = check_nvfp4(out, "out");
@@ -124,10 +126,11 @@ qii_status quantize_source(const qii::Source &src, int64_t R, int64_t C, qii_mod
         hipError_t e = qii::launch_quantize(a, s);
         if (e != hipSuccess) return hip_fail(e, "quantize (heavy pass)");
         e = qii::launch_posthoc_scales(tbuf, amax_in ? amax_in : amax_slot, amax_in ? 1 : (int)qii::kAmaxSpread, R, C, seed_sr,
-                                       out->scales, out->tensor_scale, s);
+                                       out->scales, out->tensor_scale, s, tiled_scales);
         if (e != hipSuccess) return hip_fail(e, "quantize (scales pass)");
         return QII_OK;
     }
+    if (tiled_scales) return fail(QII_INVALID_ARG, "tiled scales are written by the post hoc scheme only");
     const float *amax = amax_in;
     if (!amax) {
         if (!amax_slot) return fail(QII_WORKSPACE_TOO_SMALL, "workspace needed to measure the abs-max");
@@ -186,13 +189,13 @@ qii_status quantize_dense(const void *x, qii_dtype dt, int64_t rows, int64_t col
 
 qii_status requantize_saved(const qii_nvfp4 *in, int transpose, qii_mode mode, int rht_group, uint64_t seed_rht,
                             uint64_t seed_sr, const qii_nvfp4 *out, float *slot, float *tbuf, hipStream_t s,
-                            bool slot_zeroed)
+                            bool slot_zeroed, bool tiled_scales = false)
 {
     qii::Source src;
     int64_t R, C;
     qii_status st = nvfp4_source(in, transpose, rht_group, &src, &R, &C);
     if (st != QII_OK) return st;
-    return quantize_source(src, R, C, mode, rht_group, seed_rht, seed_sr, nullptr, out, slot, tbuf, s, slot_zeroed);
+    return quantize_source(src, R, C, mode, rht_group, seed_rht, seed_sr, nullptr, out, slot, tbuf, s, slot_zeroed, tiled_scales);
 }
 
 // quantizer workspace of a backward pass: four abs-max areas plus, for the post hoc scheme, the
@@ -208,16 +211,18 @@ size_t posthoc_region_bytes(int64_t T, int64_t d_in, int64_t d_out, qii_mode mod
     return 4 * kRegion + (e_bytes > r_bytes ? e_bytes : r_bytes);
 }
 
+// an NVFP4 tensor inside a workspace; its scale area has room for the row count rounded up to 256
+// (the tiled scale layout of the main GEMM kernel)
 size_t nvfp4_bytes(int64_t rows, int64_t cols)
 {
-    return align_up((size_t)(rows * cols / 2)) + align_up((size_t)(rows * cols / 16)) + kSlot;
+    return align_up((size_t)(rows * cols / 2)) + align_up((size_t)((rows + 255) / 256 * 256 * cols / 16)) + kSlot;
 }
 
 qii_nvfp4 carve_nvfp4(uint8_t *&p, int64_t rows, int64_t cols)
 {
     qii_nvfp4 t;
     t.codes = p; p += align_up((size_t)(rows * cols / 2));
-    t.scales = p; p += align_up((size_t)(rows * cols / 16));
+    t.scales = p; p += align_up((size_t)((rows + 255) / 256 * 256 * cols / 16));
     t.tensor_scale = reinterpret_cast<float *>(p); p += kSlot;
     t.rows = rows; t.cols = cols;
     return t;
@@ -262,16 +267,17 @@ qii_status scratch_address(void **out)
 qii_status quantize_pair(const qii::Source &src, int64_t rows, int64_t cols, qii_mode mode, uint64_t seed_rht_r,
                          uint64_t seed_sr_r, uint64_t seed_rht_c, uint64_t seed_sr_c, const qii_nvfp4 *out_r,
                          const qii_nvfp4 *out_c, float *slot_r, float *slot_c, float *tbuf_r, float *tbuf_c,
-                         hipStream_t s, bool slots_zeroed)
+                         hipStream_t s, bool slots_zeroed, bool tiled_r = false, bool tiled_c = false)
 {
     qii::Source srct = src;
     srct.transpose = 1;
     if (rows * cols == 0 || !qii::pair_kernel_applies(src, rows, cols)) {
-        qii_status st = quantize_source(src, rows, cols, mode, 128, seed_rht_r, seed_sr_r, nullptr, out_r, slot_r, tbuf_r, s, slots_zeroed);
+        qii_status st = quantize_source(src, rows, cols, mode, 128, seed_rht_r, seed_sr_r, nullptr, out_r, slot_r, tbuf_r, s, slots_zeroed, tiled_r);
         if (st != QII_OK) return st;
-        return quantize_source(srct, cols, rows, mode, 128, seed_rht_c, seed_sr_c, nullptr, out_c, slot_c, tbuf_c, s, slots_zeroed);
+        return quantize_source(srct, cols, rows, mode, 128, seed_rht_c, seed_sr_c, nullptr, out_c, slot_c, tbuf_c, s, slots_zeroed, tiled_c);
     }
     const bool ph = mode == QII_MS_EDEN_PH;
+    if ((tiled_r || tiled_c) && !ph) return fail(QII_INVALID_ARG, "tiled scales are written by the post hoc scheme only");
     hipError_t e = hipSuccess;
     if (!slots_zeroed) {
         e = ph ? qii::launch_fill_u32(reinterpret_cast<uint32_t *>(slot_r), 0u, (int)qii::kAmaxSpread, (int)qii::kAmaxStrideWords, s)
@@ -296,9 +302,9 @@ qii_status quantize_pair(const qii::Source &src, int64_t rows, int64_t cols, qii
     e = qii::launch_quantize_pair(p, s);
     if (e != hipSuccess) return hip_fail(e, "quantize (both orientations)");
     if (ph) {
-        e = qii::launch_posthoc_scales(tbuf_r, slot_r, (int)qii::kAmaxSpread, rows, cols, seed_sr_r, out_r->scales, out_r->tensor_scale, s);
+        e = qii::launch_posthoc_scales(tbuf_r, slot_r, (int)qii::kAmaxSpread, rows, cols, seed_sr_r, out_r->scales, out_r->tensor_scale, s, tiled_r);
         if (e != hipSuccess) return hip_fail(e, "quantize (scales pass)");
-        e = qii::launch_posthoc_scales(tbuf_c, slot_c, (int)qii::kAmaxSpread, cols, rows, seed_sr_c, out_c->scales, out_c->tensor_scale, s);
+        e = qii::launch_posthoc_scales(tbuf_c, slot_c, (int)qii::kAmaxSpread, cols, rows, seed_sr_c, out_c->scales, out_c->tensor_scale, s, tiled_c);
         if (e != hipSuccess) return hip_fail(e, "quantize (scales pass)");
     }
     return QII_OK;
@@ -528,6 +534,24 @@ qii_status qii_gemm_nvfp4_amax(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, 
     return QII_OK;
 }
 
+}  // extern "C"
+
+namespace {
+// the GEMM of a layer pass on operands quantized into the pass's workspace, whose scales may
+// already be in the tiled layout (pretiled: bit 0 for A, bit 1 for B)
+qii_status gemm_internal(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_dtype c_dt, int64_t ldc, void *ws,
+                         size_t ws_bytes, void *stream, int pretiled)
+{
+    const qii_status st = check_gemm_args(A, B, C, c_dt, ldc);
+    if (st != QII_OK) return st;
+    hipError_t e = qii::launch_gemm(*A, *B, C, c_dt == QII_BF16, ldc, nullptr, ws, ws_bytes, (hipStream_t)stream, pretiled);
+    if (e != hipSuccess) return hip_fail(e, "gemm");
+    return QII_OK;
+}
+}  // namespace
+
+extern "C" {
+
 qii_status qii_gemm_nvfp4(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_dtype c_dt,
                           int64_t ldc, void *ws, size_t ws_bytes, void *stream)
 {
@@ -650,18 +674,22 @@ qii_status qii_linear_bwd_mode(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq
     if (e != hipSuccess) return hip_fail(e, "fill");
     // Q(E) and Q(E^T) from one read of dY: rotation sd[0] along d_out for the dX GEMM, sd[1] along
     // the tokens for the dW GEMM (their abs-max areas are the first and third of the four)
+    // The four quantized operands live only in this workspace.  In the post hoc scheme their scale
+    // bytes come from the scales pass, which writes them straight into the layout the main GEMM
+    // kernel reads when the GEMM's inner dimension allows that kernel: no re-tiling launch.
+    const bool tile_dx = ph && d_out % 256 == 0, tile_dw = ph && T % 256 == 0;
     st = quantize_pair(se, T, d_out, mode, sd[0], sd[2], sd[1], sd[4], &Eq, &ETq, slots, slots + 2 * slot_words, tbuf,
-                       tbuf2, s, true);
+                       tbuf2, s, true, tile_dx, tile_dw);
     if (st != QII_OK) return st;
     // dX = Q(E) Q(W^T)^T : inner dimension d_out
-    st = requantize_saved(Wq, 1, mode, 128, sd[0], sd[3], &WTq, slots + slot_words, tbuf, s, true);
+    st = requantize_saved(Wq, 1, mode, 128, sd[0], sd[3], &WTq, slots + slot_words, tbuf, s, true, tile_dx);
     if (st != QII_OK) return st;
-    st = qii_gemm_nvfp4(&Eq, &WTq, dX, g_dt, d_in, gws, gws_bytes, stream);
+    st = gemm_internal(&Eq, &WTq, dX, g_dt, d_in, gws, gws_bytes, stream, tile_dx ? 3 : 0);
     if (st != QII_OK) return st;
     // dW = Q(E^T) Q(X^T)^T : inner dimension T
-    st = requantize_saved(Xq, 1, mode, 128, sd[1], sd[5], &XTq, slots + 3 * slot_words, tbuf, s, true);
+    st = requantize_saved(Xq, 1, mode, 128, sd[1], sd[5], &XTq, slots + 3 * slot_words, tbuf, s, true, tile_dw);
     if (st != QII_OK) return st;
-    return qii_gemm_nvfp4(&ETq, &XTq, dW, g_dt, d_in, gws, gws_bytes, stream);
+    return gemm_internal(&ETq, &XTq, dW, g_dt, d_in, gws, gws_bytes, stream, tile_dw ? 3 : 0);
 }
 
 qii_status qii_selftest_conversions(uint64_t *counts, void *stream)

@@ -761,9 +761,10 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
 }
 
 hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is_bf16, int64_t ldc,
-                       float *amax_c, void *ws, size_t ws_bytes, hipStream_t s)
+                       float *amax_c, void *ws, size_t ws_bytes, hipStream_t s, int pretiled)
 {
     const int64_t M = A.rows, N = B.rows, K = A.cols;
+    if (pretiled && K % BK4 != 0) return hipErrorInvalidValue;
     uint32_t *amax_out = reinterpret_cast<uint32_t *>(amax_c);
     if (amax_out) {   // the running maximum starts at 0 (a kernel, not a memset node: graph capture)
         const hipError_t e = launch_fill_u32(amax_out, 0u, 1, 1, s);
@@ -775,8 +776,10 @@ hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is
     const size_t need = K % BK4 == 0 ? scales_workspace_bytes(M, N, K) : 0;
     if (K % BK4 == 0 && ws && ws_bytes >= need && (reinterpret_cast<uintptr_t>(ws) & 15) == 0 &&
         (reinterpret_cast<uintptr_t>(A.scales) & 15) == 0 && (reinterpret_cast<uintptr_t>(B.scales) & 15) == 0) {
-        uint8_t *a_tiled = reinterpret_cast<uint8_t *>(ws);
-        uint8_t *b_tiled = a_tiled + (M + 255) / 256 * 256 * (K / 16);
+        uint8_t *a_ws = reinterpret_cast<uint8_t *>(ws);
+        uint8_t *b_ws = a_ws + (M + 255) / 256 * 256 * (K / 16);
+        const uint8_t *a_tiled = (pretiled & 1) ? A.scales : a_ws;
+        const uint8_t *b_tiled = (pretiled & 2) ? B.scales : b_ws;
         // several blocks per tile when the grid would leave most compute units idle and the caller's
         // workspace has room for their partial tiles (behind the scales, 256-byte aligned)
         int ksplit = splitk_factor(M, N, K);
@@ -785,9 +788,12 @@ hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is
         if (ksplit > 1 && ws_bytes < poff + (size_t)ksplit * mp * np * 4) ksplit = 1;
         float *partial = ksplit > 1 ? reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + poff) : nullptr;
         const dim3 sgrid((unsigned)(tiles_m * tiles_n * ksplit));
-        const int64_t na = M * (K / 256), nb = N * (K / 256);
-        hipLaunchKernelGGL(retile_scales_kernel, dim3((unsigned)((na + nb + 255) / 256)), dim3(256), 0, s, A.scales,
-                           a_tiled, M, B.scales, b_tiled, N, K);
+        // (an operand whose scales arrive tiled takes no part: zero rows)
+        const int64_t ma = (pretiled & 1) ? 0 : M, nb_rows = (pretiled & 2) ? 0 : N;
+        const int64_t na = ma * (K / 256), nb = nb_rows * (K / 256);
+        if (na + nb > 0)
+            hipLaunchKernelGGL(retile_scales_kernel, dim3((unsigned)((na + nb + 255) / 256)), dim3(256), 0, s, A.scales,
+                               a_ws, ma, B.scales, b_ws, nb_rows, K);
         hipError_t e;
         if (c_is_bf16) {
             e = allow_dynamic_lds(gemm_kernel_v4<true, false>, kSmem4);
@@ -824,6 +830,7 @@ hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is
         }
         return hipGetLastError();
     }
+    if (pretiled) return hipErrorInvalidValue;   // only the main kernel reads tiled scales
     if ((K % 128) == 0) {
         hipError_t e;
         if (c_is_bf16) {

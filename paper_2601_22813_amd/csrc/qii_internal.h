@@ -69,9 +69,12 @@ hipError_t launch_rht(const Source &src, int64_t R, int64_t C, uint64_t seed_rht
                       float *amax /* nullable, must hold 0 */, hipStream_t s);
 hipError_t launch_quantize(const QuantizeArgs &a, hipStream_t s);
 // amax: n_amax words, 256 bytes apart (1: a maximum supplied by the caller; 64: the spread running
-// maximum of the heavy pass, whose maximum is taken)
+// maximum of the heavy pass, whose maximum is taken).  tiled (C a multiple of 256): the scale bytes
+// go out in the layout the main GEMM kernel reads ([row / 256][C / 256][row % 256][16 bytes]; room for
+// the row count rounded up to 256) instead of row-major
 hipError_t launch_posthoc_scales(const float *tbuf, const float *amax, int n_amax, int64_t R, int64_t C,
-                                 uint64_t seed_sr, uint8_t *scales, float *tensor_scale, hipStream_t s);
+                                 uint64_t seed_sr, uint8_t *scales, float *tensor_scale, hipStream_t s,
+                                 bool tiled = false);
 hipError_t launch_dequantize(const uint8_t *codes, const uint8_t *scales, const float *ts,
                              int64_t rows, int64_t cols, float *y, hipStream_t s);
 // tuned kernels for dense sources quantized along their rows (quantize_rows.hip)
@@ -88,8 +91,10 @@ hipError_t launch_quantize_cols(const QuantizeArgs &a, hipStream_t s);
 // bytes of the fast kernel; without it a slower kernel reads the row-major scales directly
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 // amax_c (nullable): device float that receives max |C| over the values as stored
+// pretiled: bit 0 / bit 1 say that A.scales / B.scales already hold the tiled layout (K a multiple
+// of 256, see launch_posthoc_scales), so that operand's re-tiling is skipped
 hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is_bf16, int64_t ldc,
-                       float *amax_c, void *ws, size_t ws_bytes, hipStream_t s);
+                       float *amax_c, void *ws, size_t ws_bytes, hipStream_t s, int pretiled = 0);
 
 // sweeps of the hardware conversions and short division sequences against their value-space
 // rules; counts[0..7] (device) receive the numbers of mismatches (selftest.hip)

@@ -299,7 +299,7 @@ __global__ __launch_bounds__(256) void posthoc_scales_kernel(const float *__rest
                                                              const float *__restrict__ amax_ptr, int n_amax,
                                                              int64_t R, int64_t G, uint64_t seed_sr,
                                                              uint8_t *__restrict__ scales,
-                                                             float *__restrict__ tensor_scale)
+                                                             float *__restrict__ tensor_scale, int64_t tiled_ksn)
 {
     // the tensor maximum: one word supplied by the caller, or the maximum of the words the heavy
     // pass spread its running maximum over
@@ -332,7 +332,11 @@ __global__ __launch_bounds__(256) void posthoc_scales_kernel(const float *__rest
             const float4 t = *reinterpret_cast<const float4 *>(tbuf + row * G + g0);
             const uint32_t b = e4m3_sr(t.x / x32, draw[0][it]) | (e4m3_sr(t.y / x32, draw[1][it]) << 8) |
                                (e4m3_sr(t.z / x32, draw[2][it]) << 16) | (e4m3_sr(t.w / x32, draw[3][it]) << 24);
-            *reinterpret_cast<uint32_t *>(scales + row * G + g0) = b;
+            // tiled_ksn != 0 (G a multiple of 16): the layout the main GEMM kernel reads, 16 bytes per
+            // (row, 256 columns), [row / 256][column / 256][row % 256]
+            uint8_t *dst = tiled_ksn ? scales + (((row >> 8) * tiled_ksn + (g0 >> 4)) * 256 + (row & 255)) * 16 + (g0 & 15)
+                                     : scales + row * G + g0;
+            *reinterpret_cast<uint32_t *>(dst) = b;
         } else {
 #pragma unroll
             for (int j = 0; j < 4; ++j)
@@ -437,12 +441,13 @@ hipError_t launch_quantize(const QuantizeArgs &a, hipStream_t s)
 }
 
 hipError_t launch_posthoc_scales(const float *tbuf, const float *amax, int n_amax, int64_t R, int64_t C,
-                                 uint64_t seed_sr, uint8_t *scales, float *tensor_scale, hipStream_t s)
+                                 uint64_t seed_sr, uint8_t *scales, float *tensor_scale, hipStream_t s, bool tiled)
 {
     const int64_t G = C / 16, threads = ((R + 3) / 4) * ((G + 3) / 4);
     if (threads == 0) return hipSuccess;
+    if (tiled && C % 256 != 0) return hipErrorInvalidValue;
     hipLaunchKernelGGL(posthoc_scales_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, tbuf,
-                       amax, n_amax, R, G, seed_sr, scales, tensor_scale);
+                       amax, n_amax, R, G, seed_sr, scales, tensor_scale, tiled ? C / 256 : (int64_t)0);
     return hipGetLastError();
 }
 

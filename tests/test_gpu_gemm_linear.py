@@ -155,9 +155,11 @@ def test_linear_forward_and_backward(oracle):
         check(dW.cpu().numpy().astype(np.float64), ref, absum, False)
 
 
-def test_linear_backward_with_post_hoc_range_alignment(oracle):
-    """Backward pass of Sec. 5 with the four quantizers in the two-kernel form of Sec. 7."""
-    T, d_in, d_out = 256, 384, 512
+@pytest.mark.parametrize("T,d_in,d_out", [(256, 384, 512), (384, 208, 512), (512, 384, 640), (128, 64, 128)])
+def test_linear_backward_with_post_hoc_range_alignment(oracle, T, d_in, d_out):
+    """Backward pass of Sec. 5 with the four quantizers in the two-kernel form of Sec. 7.  (Where a
+    GEMM's inner dimension, d_out or T, is a multiple of 256 the scales pass writes the scale bytes
+    in the GEMM kernel's tiled layout; the shapes cover both, one and none of the two GEMMs.)"""
     Xb, Wb, Eb = synth.linear_layer_bf16(T, d_in, d_out, seed=8)
     E = to_dev(Eb)
     oXq, oWq = oracle.linear_fwd(Xb, Wb)
