@@ -39,7 +39,9 @@ def test_host_helpers(libqii, oracle):
             assert libqii.qii_derive_seed(seed, i) == oracle.derive_seed(seed, i)
     assert libqii.qii_quantize_workspace_bytes() == 256
     need = libqii.qii_linear_bwd_workspace_bytes(256, 128, 384)
-    payload = (256 * 384 + 128 * 384 + 384 * 256 + 128 * 256) * 9 // 16
+    # four NVFP4 operands: codes, and scale bytes with room for the row count rounded up to 256
+    up = lambda r: (r + 255) // 256 * 256
+    payload = sum(r * c // 2 + up(r) * c // 16 for r, c in ((256, 384), (128, 384), (384, 256), (128, 256)))
     gemm_ws = max(libqii.qii_gemm_workspace_bytes(256, 128, 384), libqii.qii_gemm_workspace_bytes(384, 128, 256))
     assert payload + gemm_ws <= need <= payload + gemm_ws + 16 * 256
     # re-tiled scale bytes of both operands, rows padded to 256; nothing when K is not a multiple of 256
