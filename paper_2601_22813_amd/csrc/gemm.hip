@@ -540,7 +540,39 @@ __device__ __forceinline__ void mma_step(floatx16 (&acc)[4][4], const Frags &cu,
 #undef QII_MMA
 }
 
-template <bool kBf16Out, bool kSplit>
+// Launch position -> origin of the output tile.  XCD-aware order: consecutive block ids land on
+// different XCDs (8 of them, each with its own L2), so every XCD gets a contiguous run of tiles;
+// within the run, tiles are walked in groups of 4 tile rows, column by column, so that the ~32
+// tiles an XCD works on at once share 4 A panels and 8 B panels (about 3.5 MiB at K = 2048)
+// instead of 1 + 32.
+__device__ __forceinline__ void tile_origin(int pos, int tiles_m, int tiles_n, int64_t &m0, int64_t &n0)
+{
+    int tile = pos;
+    const int ntiles = tiles_m * tiles_n;
+    if ((ntiles & 7) == 0) tile = (tile & 7) * (ntiles >> 3) + (tile >> 3);
+    constexpr int kGroupM = 4;
+    const int width = kGroupM * tiles_n, first_m = (tile / width) * kGroupM;
+    const int gm = tiles_m - first_m < kGroupM ? tiles_m - first_m : kGroupM;
+    m0 = (int64_t)(first_m + (tile % width) % gm) * BM;
+    n0 = (int64_t)((tile % width) / gm) * BN;
+}
+
+// Tiles beyond the last full round of the grid are shared between blocks (see stream_plan): the
+// `rem` launch positions from `base` on, numbered so that the blocks of one XCD (a contiguous range
+// of K-tile units, hence of these numbers) work on positions of that XCD's own run of tiles.
+__device__ __forceinline__ int stream_pos(int lt, int rem, int base)
+{
+    return base + ((rem & 7) == 0 ? (lt % (rem >> 3)) * 8 + lt / (rem >> 3) : lt);
+}
+
+// kStream = false: one block per output tile (launch position blockIdx.x).
+// kStream = true: the K tiles of the `sk_rem` tiles from position `sk_base` on form one sequence of
+// units (tile-major) that the gridDim.x blocks cut into equal contiguous ranges; a block runs its
+// range tile segment by tile segment (at most two when a range is shorter than a tile's K) and
+// leaves each segment's unscaled f32 partial tile in slot (block + tile number) of `partial`,
+// which streamk_fixup_kernel adds up in a fixed order.  (A separate instantiation: the plain
+// kernel keeps its registers.)
+template <bool kBf16Out, bool kStream>
 __global__ __launch_bounds__(256, 1) void gemm_kernel_v4(const uint8_t *__restrict__ a_codes,
                                                          const uint8_t *__restrict__ a_tiled,
                                                          const float *__restrict__ a_ts,
@@ -549,30 +581,36 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel_v4(const uint8_t *__restri
                                                          const float *__restrict__ b_ts, int64_t M,
                                                          int64_t N, int64_t K, void *__restrict__ Cout,
                                                          int64_t ldc, int tiles_m, int tiles_n, uint32_t *amax_out,
-                                                         int ksplit_arg, float *__restrict__ partial)
+                                                         int sk_base, int sk_rem, float *__restrict__ partial)
 {
     extern __shared__ __align__(16) uint8_t smem[];
-    // kSplit (few output tiles, long K): ksplit blocks share an output tile, each taking a
-    // contiguous range of K tiles and leaving its unscaled f32 partial tile in `partial`
-    // ([split][tiles_m * 256][tiles_n * 256]); splitk_reduce_kernel adds them up in a fixed order.
-    // (A separate instantiation: the plain kernel keeps its registers.)
-    const int ksplit = kSplit ? ksplit_arg : 1;
-    const int split = kSplit ? (int)(blockIdx.x % (unsigned)ksplit) : 0;
-    // XCD-aware order: consecutive block ids land on different XCDs (8 of them, each with its
-    // own L2), so give every XCD a contiguous run of tiles; within the run, tiles are walked in
-    // groups of 4 tile rows, column by column, so that the ~32 tiles an XCD works on at once
-    // share 4 A panels and 8 B panels (about 3.5 MiB at K = 2048) instead of 1 + 32.
-    int tile = (int)(blockIdx.x / (unsigned)ksplit);
-    const int ntiles = tiles_m * tiles_n;
-    if ((ntiles & 7) == 0) tile = (tile & 7) * (ntiles >> 3) + (tile >> 3);
-    constexpr int kGroupM = 4;
-    const int width = kGroupM * tiles_n, first_m = (tile / width) * kGroupM;
-    const int gm = tiles_m - first_m < kGroupM ? tiles_m - first_m : kGroupM;
-    const int64_t m0 = (int64_t)(first_m + (tile % width) % gm) * BM, n0 = (int64_t)((tile % width) / gm) * BN;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int li = lane & 31, kb = lane >> 5;
+
+    const int ktotal = (int)(K / BK4);
+    // this block's range of units [u, u_end) and its number among the blocks (kStream)
+    int64_t u = 0, u_end = 0;
+    int blk = 0;
+    if (kStream) {
+        const int G = (int)gridDim.x;
+        blk = (G & 7) == 0 ? (int)(blockIdx.x & 7) * (G >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+        const int64_t U = (int64_t)sk_rem * ktotal;
+        u = U * blk / G;
+        u_end = U * (blk + 1) / G;
+    }
+    for (;;) {
+    // this segment: K tiles [kt0, kt0 + ktiles) of the tile at launch position pos
+    int pos = (int)blockIdx.x, kt0 = 0, ktiles = ktotal, lt = 0;
+    if (kStream) {
+        lt = (int)(u / ktotal);
+        kt0 = (int)(u % ktotal);
+        ktiles = (int)(u_end - u) < ktotal - kt0 ? (int)(u_end - u) : ktotal - kt0;
+        pos = stream_pos(lt, sk_rem, sk_base);
+    }
+    int64_t m0, n0;
+    tile_origin(pos, tiles_m, tiles_n, m0, n0);
 
     floatx16 acc[4][4];
 #pragma unroll
@@ -593,10 +631,6 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel_v4(const uint8_t *__restri
         for (int j = 0; j < 4; ++j) fa.xo[j] = (uint32_t)(((2 * j + kb) ^ (li & 7)) * 16);
     }
 
-    // this block's K tiles: [kt0, kt0 + ktiles)
-    const int ktotal = (int)(K / BK4);
-    const int kt0 = (int)((int64_t)ktotal * split / ksplit);
-    const int ktiles = (int)((int64_t)ktotal * (split + 1) / ksplit) - kt0;
     issue_tile_loads4(smem, a_codes, a_tiled, b_codes, b_tiled, M, N, K, m0, n0, kt0, wave);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -664,44 +698,60 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel_v4(const uint8_t *__restri
     // the last read block is still in flight: its registers and the stages are reused below
     frag_read_wait(fo);
     __syncthreads();
-    if (kSplit) {
-        const int64_t mp = (int64_t)tiles_m * BM, np = (int64_t)tiles_n * BN;
-        store_tile_through_lds<false>(acc, smem, 1.0f, partial + (int64_t)split * mp * np, np, mp, np, m0, n0, wave, wm, wn, lane, li,
-                                      kb, nullptr);
-        return;
+    if (!kStream) {
+        store_tile_through_lds<kBf16Out>(acc, smem, (*a_ts) * (*b_ts), Cout, ldc, M, N, m0, n0, wave, wm, wn, lane, li, kb, amax_out);
+        break;
     }
-    store_tile_through_lds<kBf16Out>(acc, smem, (*a_ts) * (*b_ts), Cout, ldc, M, N, m0, n0, wave, wm, wn, lane, li, kb, amax_out);
+    store_tile_through_lds<false>(acc, smem, 1.0f, partial + (int64_t)(blk + lt) * (BM * BN), BN, BM, BN, 0, 0, wave, wm, wn, lane,
+                                  li, kb, nullptr);
+    u += ktiles;
+    if (u >= u_end) break;
+    __syncthreads();   // every wave is done with its staging tile before the next segment's loads land in LDS
+    }
 }
 
-// C = (x32_A * x32_B) * sum over the splits, in the order of the splits; 4 consecutive columns per
-// thread, at most 512 blocks that stride over the matrix (one atomic per block when max |C| is wanted)
+// C = (x32_A * x32_B) * sum of a shared tile's partial tiles, in the order of their K ranges.  One
+// block per 16 rows of a tile, 4 consecutive columns per thread and pass; the blocks that took part
+// in tile lt are those whose unit ranges meet [lt * ktotal, (lt + 1) * ktotal), their slots
+// (block + lt) are consecutive.  One atomic per block when max |C| is wanted.
 template <bool kBf16Out>
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partial, int ksplit, int64_t M, int64_t N,
-                                                            int64_t mp, int64_t np, const float *__restrict__ a_ts,
-                                                            const float *__restrict__ b_ts, void *__restrict__ Cout, int64_t ldc,
-                                                            uint32_t *amax_out)
+__global__ __launch_bounds__(256) void streamk_fixup_kernel(const float *__restrict__ partial, int sk_base, int sk_rem, int G,
+                                                            int ktotal, int tiles_m, int tiles_n, int64_t M, int64_t N,
+                                                            const float *__restrict__ a_ts, const float *__restrict__ b_ts,
+                                                            void *__restrict__ Cout, int64_t ldc, uint32_t *amax_out)
 {
     __shared__ float wave_m[4];
+    const int lt = (int)(blockIdx.x >> 4), strip = (int)(blockIdx.x & 15);
+    const int64_t U = (int64_t)sk_rem * ktotal;
+    const int64_t ufirst = (int64_t)lt * ktotal, ulast = ufirst + ktotal - 1;
+    // the block whose range [U b / G, U (b + 1) / G) holds unit u is floor(((u + 1) G - 1) / U)
+    const int b_first = (int)(((ufirst + 1) * G - 1) / U), b_last = (int)(((ulast + 1) * G - 1) / U);
+    int64_t m0, n0;
+    tile_origin(stream_pos(lt, sk_rem, sk_base), tiles_m, tiles_n, m0, n0);
     const float ts = (*a_ts) * (*b_ts);
-    const int64_t quads = (N + 3) / 4, items = M * quads, stride = (int64_t)gridDim.x * blockDim.x;
     float cmax = 0.0f;
-    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < items; idx += stride) {
-        const int64_t row = idx / quads, col = (idx % quads) * 4;
-        float4 acc = *reinterpret_cast<const float4 *>(partial + row * np + col);   // (np is a multiple of 256: the quad is inside the buffer)
-        for (int s = 1; s < ksplit; ++s) {
-            const float4 p = *reinterpret_cast<const float4 *>(partial + (int64_t)s * mp * np + row * np + col);
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+        const int row = strip * 16 + pass * 4 + (int)(threadIdx.x >> 6), col = (int)(threadIdx.x & 63) * 4;
+        const float *src = partial + (int64_t)(b_first + lt) * (BM * BN) + row * BN + col;
+        float4 acc = *reinterpret_cast<const float4 *>(src);
+        for (int b = b_first + 1; b <= b_last; ++b) {
+            src += BM * BN;
+            const float4 p = *reinterpret_cast<const float4 *>(src);
             acc.x += p.x; acc.y += p.y; acc.z += p.z; acc.w += p.w;
         }
+        const int64_t grow = m0 + row, gcol = n0 + col;
+        if (grow >= M) continue;
         const float v[4] = {acc.x * ts, acc.y * ts, acc.z * ts, acc.w * ts};
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            if (col + e < N) {
+            if (gcol + e < N) {
                 if (kBf16Out) {
                     const uint32_t b = f32_to_bf16_bits(v[e]);
-                    reinterpret_cast<uint16_t *>(Cout)[row * ldc + col + e] = (uint16_t)b;
+                    reinterpret_cast<uint16_t *>(Cout)[grow * ldc + gcol + e] = (uint16_t)b;
                     cmax = fmaxf(cmax, fabsf(u2f(b << 16)));
                 } else {
-                    reinterpret_cast<float *>(Cout)[row * ldc + col + e] = v[e];
+                    reinterpret_cast<float *>(Cout)[grow * ldc + gcol + e] = v[e];
                     cmax = fmaxf(cmax, fabsf(v[e]));
                 }
             }
@@ -717,32 +767,50 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 
 }  // namespace
 
-// A grid of fewer tiles than compute units leaves many of them idle (2048 x 2048 x 32768, the weight
-// gradient of a small layer, has 64 tiles for 256 units; 3072 x 3072 has 144).  Then several blocks
-// share a tile.  The number of blocks per tile (at most 8, at least 4 K tiles each) minimises a
-// small cost model fitted to measurements: rounds of the grid times the K tiles of a block (about
-// 6 us per K tile, 5 us per round for a tile's first loads and its stores) plus the reduction pass
-// over the partial tiles (written once, read once: about 0.1 us per tile and pass); sharing is used
-// when the model promises at least 12 % (measured: 2048 x 2048 x 32768 615 -> 244 us with 4 blocks
-// per tile, 3072 x 3072 x 16384 340 -> 302 us with 3; 6144 x 2048 x 32768 would gain 5 % for 200 MiB
-// of partial tiles and stays plain).
-static int splitk_factor(int64_t M, int64_t N, int64_t K)
+// The grid of the main kernel runs in rounds of 256 tiles (one block per compute unit).  A last round
+// with few tiles leaves most units idle for a whole tile's time (2048 x 2048 x 32768, the weight
+// gradient of a small layer, is 64 tiles; 2048 x 11264 is 352: the second round runs at 37 %).  Then
+// the full rounds run as they are and the remaining tiles are shared: their K tiles form one sequence
+// of units that `grid` blocks (at most 256, at least 4 units each) cut into equal ranges, partial
+// tiles go to the workspace and a second kernel adds them up.
+//
+// The plan follows a cost model fitted to kernel traces (microseconds): a K tile takes 5.8 when all
+// 256 units work and 4.6 when at most 176 do (the part is power-limited: fewer active units run at
+// a higher clock, so filling idle units gains less than their number suggests); a tile costs 5 more
+// for its first loads and its stores; a sharing block 26 more (all blocks store their 256 KiB
+// partial tiles at the same moment), 38 when its range spans two tiles; the second kernel 5 + 0.05
+// per partial tile.  Sharing is used where the model promises at least 7 %.  Measured on one
+// box, plain -> shared: 2048 x 2048 x 32768 600 -> 230, 3072 x 3072 x 16384 307 -> 276, 11264 x 2048 x
+// 16384 654 -> 575; 6144 x 2048 x 32768 would go 655 -> 618 for 112 MiB of partial tiles and 2048 x
+// 5632 x 16384 298 -> 320: both stay plain.
+struct StreamPlan {
+    int full;   // launch positions run one block per tile
+    int rem;    // positions after them whose tiles are shared (0: none)
+    int grid;   // blocks that share them
+};
+
+static StreamPlan stream_plan(int64_t M, int64_t N, int64_t K)
 {
-    if (K % BK4 != 0) return 1;
     const int64_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN), ktiles = K / BK4;
-    if (tiles == 0 || tiles >= 256) return 1;
-    const double plain_us = 6.0 * (double)ktiles + 5.0;
-    int best = 1;
-    double best_us = 0.88 * plain_us;
-    for (int s = 2; s <= 8 && ktiles / s >= 4; ++s) {
-        const int64_t rounds = (tiles * s + 255) / 256;
-        const double us = (double)rounds * (6.0 * (double)((ktiles + s - 1) / s) + 5.0) + 0.1 * (double)((s + 1) * tiles);
-        if (us < best_us) {
-            best = s;
-            best_us = us;
-        }
-    }
-    return best;
+    StreamPlan plan{(int)tiles, 0, 0};
+    if (K % BK4 != 0 || tiles == 0 || tiles > (1 << 24) || ktiles < 8) return plan;
+    const int64_t rounds = tiles / 256, rem = tiles % 256;
+    if (rem == 0) return plan;
+    const int64_t units = rem * ktiles;
+    int64_t grid = units / 4 < 256 ? units / 4 : 256;
+    if (grid >= 8) grid &= ~(int64_t)7;
+    if (grid <= rem) return plan;
+    const double full_us = (double)rounds * (5.8 * (double)ktiles + 5.0);
+    const double kt_us = 4.6 + (rem > 176 ? 1.2 * (double)(rem - 176) / 80.0 : 0.0);
+    const double plain_us = full_us + kt_us * (double)ktiles + 5.0;
+    const int64_t per = (units + grid - 1) / grid;
+    const bool one_segment = ktiles % per == 0 && units % grid == 0;
+    const double shared_us = full_us + 5.8 * (double)per + (one_segment ? 26.0 : 38.0) + 5.0 + 0.05 * (double)(grid + rem);
+    if (shared_us >= 0.93 * plain_us) return plan;
+    plan.full = (int)(rounds * 256);
+    plan.rem = (int)rem;
+    plan.grid = (int)grid;
+    return plan;
 }
 
 static size_t scales_workspace_bytes(int64_t M, int64_t N, int64_t K)
@@ -754,10 +822,34 @@ static size_t scales_workspace_bytes(int64_t M, int64_t N, int64_t K)
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
     if (K % BK4 != 0) return 0;
-    const int64_t mp = (M + 255) / 256 * 256, np = (N + 255) / 256 * 256;
-    const int s = splitk_factor(M, N, K);
+    const StreamPlan plan = stream_plan(M, N, K);
     const size_t sc = scales_workspace_bytes(M, N, K);
-    return s > 1 ? (sc + 255) / 256 * 256 + (size_t)s * mp * np * 4 : sc;
+    return plan.rem ? (sc + 255) / 256 * 256 + (size_t)(plan.grid + plan.rem) * BM * BN * 4 : sc;
+}
+
+template <bool kBf16Out>
+static hipError_t launch_main_kernel(const qii_nvfp4 &A, const uint8_t *a_tiled, const qii_nvfp4 &B, const uint8_t *b_tiled, void *C,
+                                     int64_t ldc, int tiles_m, int tiles_n, uint32_t *amax_out, const StreamPlan &plan,
+                                     float *partial, hipStream_t s)
+{
+    const int64_t M = A.rows, N = B.rows, K = A.cols;
+    hipError_t e = allow_dynamic_lds(gemm_kernel_v4<kBf16Out, false>, kSmem4);
+    if (e != hipSuccess) return e;
+    e = allow_dynamic_lds(gemm_kernel_v4<kBf16Out, true>, kSmem4);
+    if (e != hipSuccess) return e;
+    if (plan.full > 0)
+        hipLaunchKernelGGL((gemm_kernel_v4<kBf16Out, false>), dim3((unsigned)plan.full), dim3(256), kSmem4, s, A.codes, a_tiled,
+                           A.tensor_scale, B.codes, b_tiled, B.tensor_scale, M, N, K, C, ldc, tiles_m, tiles_n, amax_out, 0, 0,
+                           partial);
+    if (plan.rem > 0) {
+        hipLaunchKernelGGL((gemm_kernel_v4<kBf16Out, true>), dim3((unsigned)plan.grid), dim3(256), kSmem4, s, A.codes, a_tiled,
+                           A.tensor_scale, B.codes, b_tiled, B.tensor_scale, M, N, K, C, ldc, tiles_m, tiles_n, amax_out, plan.full,
+                           plan.rem, partial);
+        hipLaunchKernelGGL(streamk_fixup_kernel<kBf16Out>, dim3((unsigned)plan.rem * 16), dim3(256), 0, s, partial, plan.full,
+                           plan.rem, plan.grid, (int)(K / BK4), tiles_m, tiles_n, M, N, A.tensor_scale, B.tensor_scale, C, ldc,
+                           amax_out);
+    }
+    return hipGetLastError();
 }
 
 hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is_bf16, int64_t ldc,
@@ -780,55 +872,20 @@ hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is
         uint8_t *b_ws = a_ws + (M + 255) / 256 * 256 * (K / 16);
         const uint8_t *a_tiled = (pretiled & 1) ? A.scales : a_ws;
         const uint8_t *b_tiled = (pretiled & 2) ? B.scales : b_ws;
-        // several blocks per tile when the grid would leave most compute units idle and the caller's
-        // workspace has room for their partial tiles (behind the scales, 256-byte aligned)
-        int ksplit = splitk_factor(M, N, K);
+        // the tiles of an incomplete last round are shared between blocks when the caller's workspace
+        // has room for their partial tiles (behind the scales, 256-byte aligned)
+        StreamPlan plan = stream_plan(M, N, K);
         const size_t poff = (need + 255) / 256 * 256;
-        const int64_t mp = tiles_m * BM, np = tiles_n * BN;
-        if (ksplit > 1 && ws_bytes < poff + (size_t)ksplit * mp * np * 4) ksplit = 1;
-        float *partial = ksplit > 1 ? reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + poff) : nullptr;
-        const dim3 sgrid((unsigned)(tiles_m * tiles_n * ksplit));
+        if (plan.rem && ws_bytes < poff + (size_t)(plan.grid + plan.rem) * BM * BN * 4) plan = StreamPlan{(int)(tiles_m * tiles_n), 0, 0};
+        float *partial = plan.rem ? reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + poff) : nullptr;
         // (an operand whose scales arrive tiled takes no part: zero rows)
         const int64_t ma = (pretiled & 1) ? 0 : M, nb_rows = (pretiled & 2) ? 0 : N;
         const int64_t na = ma * (K / 256), nb = nb_rows * (K / 256);
         if (na + nb > 0)
             hipLaunchKernelGGL(retile_scales_kernel, dim3((unsigned)((na + nb + 255) / 256)), dim3(256), 0, s, A.scales,
                                a_ws, ma, B.scales, b_ws, nb_rows, K);
-        hipError_t e;
-        if (c_is_bf16) {
-            e = allow_dynamic_lds(gemm_kernel_v4<true, false>, kSmem4);
-            if (e != hipSuccess) return e;
-            e = allow_dynamic_lds(gemm_kernel_v4<true, true>, kSmem4);
-            if (e != hipSuccess) return e;
-            if (ksplit > 1)
-                hipLaunchKernelGGL((gemm_kernel_v4<true, true>), sgrid, block, kSmem4, s, A.codes, a_tiled, A.tensor_scale, B.codes,
-                                   b_tiled, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n, amax_out, ksplit, partial);
-            else
-                hipLaunchKernelGGL((gemm_kernel_v4<true, false>), sgrid, block, kSmem4, s, A.codes, a_tiled, A.tensor_scale, B.codes,
-                                   b_tiled, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n, amax_out, 1, partial);
-        } else {
-            e = allow_dynamic_lds(gemm_kernel_v4<false, false>, kSmem4);
-            if (e != hipSuccess) return e;
-            e = allow_dynamic_lds(gemm_kernel_v4<false, true>, kSmem4);
-            if (e != hipSuccess) return e;
-            if (ksplit > 1)
-                hipLaunchKernelGGL((gemm_kernel_v4<false, true>), sgrid, block, kSmem4, s, A.codes, a_tiled, A.tensor_scale, B.codes,
-                                   b_tiled, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n, amax_out, ksplit, partial);
-            else
-                hipLaunchKernelGGL((gemm_kernel_v4<false, false>), sgrid, block, kSmem4, s, A.codes, a_tiled, A.tensor_scale, B.codes,
-                                   b_tiled, B.tensor_scale, M, N, K, C, ldc, (int)tiles_m, (int)tiles_n, amax_out, 1, partial);
-        }
-        if (ksplit > 1) {
-            const int64_t items = M * ((N + 3) / 4);
-            const dim3 rgrid((unsigned)(items / 256 + 1 < 512 ? items / 256 + 1 : 512));
-            if (c_is_bf16)
-                hipLaunchKernelGGL(splitk_reduce_kernel<true>, rgrid, dim3(256), 0, s, partial, ksplit, M, N, mp, np, A.tensor_scale,
-                                   B.tensor_scale, C, ldc, amax_out);
-            else
-                hipLaunchKernelGGL(splitk_reduce_kernel<false>, rgrid, dim3(256), 0, s, partial, ksplit, M, N, mp, np, A.tensor_scale,
-                                   B.tensor_scale, C, ldc, amax_out);
-        }
-        return hipGetLastError();
+        return c_is_bf16 ? launch_main_kernel<true>(A, a_tiled, B, b_tiled, C, ldc, (int)tiles_m, (int)tiles_n, amax_out, plan, partial, s)
+                         : launch_main_kernel<false>(A, a_tiled, B, b_tiled, C, ldc, (int)tiles_m, (int)tiles_n, amax_out, plan, partial, s);
     }
     if (pretiled) return hipErrorInvalidValue;   // only the main kernel reads tiled scales
     if ((K % 128) == 0) {

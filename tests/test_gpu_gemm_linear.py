@@ -66,11 +66,14 @@ def test_gemm_ragged_shapes(oracle, M, N, K):
     check(gemm_gpu(qa, qb, torch.bfloat16, ldc=N + 3, use_ws=False), ref, absum, True)
 
 
-@pytest.mark.parametrize("M,N,K", [(512, 512, 8192), (300, 520, 4096), (256, 1024, 2048)])
-def test_gemm_few_tiles_long_k_shares_tiles_between_blocks(oracle, M, N, K):
-    """Shapes with few output tiles and a long K run several blocks per tile (partial tiles in the
-    workspace, added up in a fixed order): same tolerance, same result on a repeated call, and the
-    emitted max |C| is that of the stored values; without room for the partial tiles the plain path runs."""
+@pytest.mark.parametrize("M,N,K", [(512, 512, 8192), (300, 520, 4096), (1280, 256, 6144), (256, 256, 4096), (6100, 2800, 4096)])
+def test_gemm_shares_the_tiles_of_an_incomplete_round(oracle, M, N, K):
+    """Tiles beyond the last full round of 256 (all of them when there are fewer) are shared between
+    blocks: contiguous ranges of K tiles, partial tiles in the workspace, added up in a fixed order.
+    Same tolerance, same result on a repeated call, and the emitted max |C| is that of the stored
+    values; without room for the partial tiles the plain path runs.  The shapes cover 4 / 6 / 5 / 1
+    tiles (block counts 32, 24, 24, 4; an odd tile count with ranges that span two tiles; ragged
+    edges) and 264 tiles (one full round, then 8 shared tiles)."""
     rng = np.random.default_rng(M + N + K)
     a = (rng.standard_t(3, size=(M, K)) * 0.1).astype(np.float32)
     b = rng.standard_normal((N, K)).astype(np.float32)
@@ -78,8 +81,8 @@ def test_gemm_few_tiles_long_k_shares_tiles_between_blocks(oracle, M, N, K):
     qb = oracle.quantize(b, oracle.MS_EDEN, rht_group=128, seed_sr=4)
     ref, absum = oracle.gemm(qa, qb, with_abs=True)
     need = qii.qii_gemm_workspace_bytes(M, N, K)
-    tiles = -(-M // 256) * -(-N // 256)
-    assert need > (M + 255) // 256 * 256 * (K // 16) + (N + 255) // 256 * 256 * (K // 16) + 2 * tiles * 65536 * 4 - 1   # room for >= 2 partial tiles per tile
+    rem = (-(-M // 256) * -(-N // 256)) % 256
+    assert need > (M + 255) // 256 * 256 * (K // 16) + (N + 255) // 256 * 256 * (K // 16) + 2 * rem * 65536 * 4 - 1   # room for >= 2 partial tiles per shared tile
     print(f"gemm {M}x{N}x{K}, workspace {need}", flush=True)
     c1 = gemm_gpu(qa, qb, torch.float32, ldc=N + 8)
     check(c1, ref, absum, False)
