@@ -40,7 +40,7 @@ VALU_F32_PEAK_TFLOPS = 157.3
 BYTES_PER_ELEM_POSTHOC = 2 + 0.5 + 0.25 + 0.25 + 0.0625
 # HBM bytes of one launch of the roofline kernel at 8192 x 8192, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by
 # the same counters' reading of a 512 MiB device copy: the row of that kernel in profiles/value_workload_hbm_traffic.txt
-TRAFFIC_QUANT_ROWS_BYTES = 172_162_000   # (that row, rounded to the kilobyte)
+TRAFFIC_QUANT_ROWS_BYTES = 172_160_000   # (that row to five digits: repeated runs differ by a few KB)
 
 
 # Weight shapes [d_in, d_out] of Llama-like models (App. D, table of linear shapes), 8 x 2048 tokens.
