@@ -39,7 +39,7 @@ VALU_F32_PEAK_TFLOPS = 157.3
 # post hoc scheme: bf16 in, FP4 + one f32 per group out; then that f32 in, E4M3 scale out
 BYTES_PER_ELEM_POSTHOC = 2 + 0.5 + 0.25 + 0.25 + 0.0625
 # HBM bytes of one launch of the roofline kernel at 8192 x 8192, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by
-# the same counters' reading of a 512 MiB device copy: the row of that kernel in profiles/value_workload_hbm_traffic.txt
+# the same counters' reading of a 512 MiB device copy: the row of that kernel in profiles/quantize_8192x8192_hbm_traffic.txt
 TRAFFIC_QUANT_ROWS_BYTES = 172_160_000   # (that row to five digits: repeated runs differ by a few KB)
 
 
@@ -326,8 +326,8 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=16384)
     ap.add_argument("--d-in", type=int, default=2048)
     ap.add_argument("--d-out", type=int, default=8192)
-    ap.add_argument("--parts", choices=["all", "value", "quantize", "linear"], default="all",
-                    help="run only the two launches behind `value`, only the quantize-only parts or only the layer parts of a step (for profiles in "
+    ap.add_argument("--parts", choices=["all", "roofline", "quantize", "linear"], default="all",
+                    help="run only the two abs-max-supplied launches behind `roofline` and `roofline_cols`, only the quantize-only parts or only the layer parts of a step (for profiles in "
                          "which every launch of a kernel has the same tensor size); the JSON line then reports "
                          "the skipped parts as null timings")
     ap.add_argument("--no-extra-configs", action="store_true",
@@ -409,7 +409,7 @@ def main() -> int:
              "linear_bwd_ph", "linear_fwd_46_amax"]
     kernel_ms = {k: [] for k in names}
 
-    do_v = args.parts in ("all", "value", "quantize")     # the two single-pass launches behind `value`
+    do_v = args.parts in ("all", "roofline", "quantize")     # the two single-pass launches behind `roofline` / `roofline_cols`
     do_q, do_l = args.parts in ("all", "quantize"), args.parts in ("all", "linear")
 
     kBatch = 4
@@ -594,7 +594,7 @@ def main() -> int:
             # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by what the same
             # counters read for a 512 MiB device copy (x2.0 and x1.0)
             "traffic": {"bytes": TRAFFIC_QUANT_ROWS_BYTES, "algorithmic_bytes": int(n * BYTES_PER_ELEM_QUANT),
-                        "valid_for": "8192x8192 bf16", "source": "profiles/value_workload_hbm_traffic.txt"} if (R, C) == (8192, 8192) else None,
+                        "valid_for": "8192x8192 bf16", "source": "profiles/quantize_8192x8192_hbm_traffic.txt"} if (R, C) == (8192, 8192) else None,
         },
         # the same for the columns kernel (transposed source), the slower of the two
         "roofline_cols": {
