@@ -47,6 +47,17 @@ def test_host_helpers(libqii, oracle):
     # re-tiled scale bytes of both operands, rows padded to 256; nothing when K is not a multiple of 256
     assert libqii.qii_gemm_workspace_bytes(300, 200, 512) == (512 + 256) * 512 // 16
     assert libqii.qii_gemm_workspace_bytes(300, 200, 384) == 0
+    # whole rounds of 256 tiles need the scale bytes only; an incomplete last round whose tiles are
+    # shared between blocks adds one 256 KiB partial tile per sharing block and shared tile
+    scales = lambda M, N, K: (up(M) + up(N)) * K // 16
+    assert libqii.qii_gemm_workspace_bytes(16384, 8192, 2048) == scales(16384, 8192, 2048)       # 2048 tiles
+    assert libqii.qii_gemm_workspace_bytes(4096, 4096, 32768) == scales(4096, 4096, 32768)       # 256 tiles
+    extra = libqii.qii_gemm_workspace_bytes(2048, 2048, 32768) - scales(2048, 2048, 32768)       # 64 tiles, long K
+    assert extra == (256 + 64) * 256 * 256 * 4
+    extra = libqii.qii_gemm_workspace_bytes(11264, 2048, 16384) - scales(11264, 2048, 16384)     # 352 tiles: 96 shared
+    assert extra == (256 + 96) * 256 * 256 * 4
+    assert libqii.qii_gemm_workspace_bytes(2048, 5632, 16384) == scales(2048, 5632, 16384)       # 176 tiles: stays plain
+    assert libqii.qii_gemm_workspace_bytes(512, 512, 1024) == scales(512, 512, 1024)             # short K: stays plain
     L = libqii.lib()
     assert L.qii_status_string(0) == b"QII_OK" and L.qii_status_string(2) == b"QII_BAD_SHAPE"
 
