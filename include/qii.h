@@ -184,8 +184,11 @@ qii_status qii_dequantize_nvfp4(const qii_nvfp4 *in, float *y, void *stream);
  * dtype QII_F32 or QII_BF16 (rounded to nearest even from the f32 accumulator).
  * K = A.cols = B.cols is any multiple of 16 (NVFP4's own rule).  ws (nullable):
  * qii_gemm_workspace_bytes bytes, 16-byte aligned; with it (and K a multiple of 256) the fast
- * kernel runs, which first copies the scale bytes into a tile-contiguous layout; without it a
- * slower kernel is used.  Either way every product is formed exactly and accumulated in f32.
+ * kernel runs, which first copies the scale bytes into a tile-contiguous layout and, when the
+ * number of 256 x 256 output tiles leaves the last round of the grid mostly idle, shares those
+ * tiles between blocks (f32 partial tiles in ws, added in a fixed order: results do not depend on
+ * timing).  Without ws a slower kernel is used; with a ws too small for the partial tiles, one
+ * block per tile.  Either way every product is formed exactly and accumulated in f32.
  * errors: QII_INVALID_ARG / QII_BAD_SHAPE before anything is launched; C is then untouched. */
 qii_status qii_gemm_nvfp4(const qii_nvfp4 *A, const qii_nvfp4 *B, void *C, qii_dtype c_dt,
                           int64_t ldc, void *ws, size_t ws_bytes, void *stream);
