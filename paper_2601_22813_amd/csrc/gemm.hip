@@ -702,7 +702,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel_v4(const uint8_t *__restri
         store_tile_through_lds<kBf16Out>(acc, smem, (*a_ts) * (*b_ts), Cout, ldc, M, N, m0, n0, wave, wm, wn, lane, li, kb, amax_out);
         break;
     }
-    store_tile_through_lds<false>(acc, smem, 1.0f, partial + (int64_t)(blk + lt) * (BM * BN), BN, BM, BN, 0, 0, wave, wm, wn, lane,
+    store_tile_through_lds<false, false>(acc, smem, 1.0f, partial + (int64_t)(blk + lt) * (BM * BN), BN, BM, BN, 0, 0, wave, wm, wn, lane,
                                   li, kb, nullptr);
     u += ktiles;
     if (u >= u_end) break;
@@ -778,10 +778,10 @@ __global__ __launch_bounds__(256) void streamk_fixup_kernel(const float *__restr
 // 256 units work and 4.6 when at most 176 do (the part is power-limited: fewer active units run at
 // a higher clock, so filling idle units gains less than their number suggests); a tile costs 5 more
 // for its first loads and its stores; a sharing block 26 more (all blocks store their 256 KiB
-// partial tiles at the same moment), 38 when its range spans two tiles; the second kernel 5 + 0.05
-// per partial tile.  Sharing is used where the model promises at least 7 %.  Measured on one
-// box, plain -> shared: 2048 x 2048 x 32768 600 -> 230, 3072 x 3072 x 16384 307 -> 276, 11264 x 2048 x
-// 16384 654 -> 575; 6144 x 2048 x 32768 would go 655 -> 618 for 112 MiB of partial tiles and 2048 x
+// partial tiles at the same moment), 38 when its range spans two tiles; the second kernel 0.05 per
+// partial tile (they are stored with plain stores, not streaming ones, and mostly still in cache).  Sharing is used where the model promises at least 7 %.  Measured on one
+// box, plain -> shared: 2048 x 2048 x 32768 600 -> 226, 3072 x 3072 x 16384 307 -> 267, 11264 x 2048 x
+// 16384 654 -> 573; 6144 x 2048 x 32768 would go 655 -> 618 for 112 MiB of partial tiles and 2048 x
 // 5632 x 16384 298 -> 320: both stay plain.
 struct StreamPlan {
     int full;   // launch positions run one block per tile
@@ -805,7 +805,7 @@ static StreamPlan stream_plan(int64_t M, int64_t N, int64_t K)
     const double plain_us = full_us + kt_us * (double)ktiles + 5.0;
     const int64_t per = (units + grid - 1) / grid;
     const bool one_segment = ktiles % per == 0 && units % grid == 0;
-    const double shared_us = full_us + 5.8 * (double)per + (one_segment ? 26.0 : 38.0) + 5.0 + 0.05 * (double)(grid + rem);
+    const double shared_us = full_us + 5.8 * (double)per + (one_segment ? 26.0 : 38.0) + 0.05 * (double)(grid + rem);
     if (shared_us >= 0.93 * plain_us) return plan;
     plan.full = (int)(rounds * 256);
     plan.rem = (int)rem;

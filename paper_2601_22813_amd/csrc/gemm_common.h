@@ -33,7 +33,7 @@ __device__ __forceinline__ void emit_tile_max(float cmax, uint32_t *amax_out)
 // 8*(r/4) + 4*(lane/32) + r%4, column lane%32.  One 32-row band of the wave's 128x128 tile
 // at a time goes through a per-wave LDS tile (row pitch padded by 16 bytes) and leaves as
 // 16-byte pieces of full rows.  The caller guarantees that nobody reads the stages any more.
-template <bool kBf16Out>
+template <bool kBf16Out, bool kStreaming = true>
 __device__ __forceinline__ void store_tile_through_lds(floatx16 (&acc)[4][4], uint8_t *smem, float ts,
                                                        void *Cout, int64_t ldc, int64_t M, int64_t N,
                                                        int64_t m0, int64_t n0, int wave, int wm, int wn,
@@ -82,7 +82,9 @@ __device__ __forceinline__ void store_tile_through_lds(floatx16 (&acc)[4][4], ui
                 uint8_t *dst = reinterpret_cast<uint8_t *>(Cout) + (grow * ldc + gcol) * esz;
                 if (gcol + 16 / esz <= N && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
                     // C is written once and not read again here: a streaming (non-temporal) store
-                    __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4 *>(dst));
+                    // (kStreaming = false: a partial tile that the next kernel reads back)
+                    if (kStreaming) __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4 *>(dst));
+                    else *reinterpret_cast<u32x4 *>(dst) = u32x4{v.x, v.y, v.z, v.w};
                 } else {
                     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
