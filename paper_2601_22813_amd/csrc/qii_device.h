@@ -44,6 +44,15 @@ __host__ __device__ inline U4 philox_seeded(uint64_t seed, uint32_t c0, uint32_t
     return philox4x32_10(c0, c1, c2, c3, (uint32_t)seed, (uint32_t)(seed >> 32));
 }
 
+// ---------------------------------------------------------------- streaming stores
+// 16 bytes of codes: written once by a quantizer and not read again by it, so a non-temporal store
+// (the lines do not linger dirty in L2, where the next kernel's traffic would have to push them out)
+typedef uint32_t qii_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store_codes16(uint8_t *dst, uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3)
+{
+    __builtin_nontemporal_store(qii_u32x4{c0, c1, c2, c3}, reinterpret_cast<qii_u32x4 *>(dst));
+}
+
 // ---------------------------------------------------------------- bit casts
 __device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
 __device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }

@@ -80,6 +80,13 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t row_rsrc(const void *base, int
 }
 
 constexpr uint32_t kNoStore = 0xFFFFFFF0u;   // a lane offset beyond every descriptor
+// Cache policy of the code stores.  With rotation (the backward pass's quantizers) they are
+// non-temporal: the lines do not linger dirty in L2, where the next kernel's traffic would have to
+// push them out (-1 % and -3 % on the two 8192 x 8192 kernels, and the kernel that follows starts
+// on a clean cache).  Without rotation (the forward pass) the GEMM reads the codes right away and
+// ran 1.2 % slower when they had to come back from memory, so those stores stay ordinary.
+template <bool kRht>
+constexpr int code_store_policy() { return kRht ? 2 : 0; }
 
 template <bool kBf16>
 __device__ __forceinline__ void load_raw(Raw<kBf16> &r, const RowsArgs &a, int row, uint32_t voff)
@@ -150,13 +157,13 @@ __device__ __forceinline__ void quantize_quad(const RowsArgs &a, const LaneSetup
             // heavy pass of the post hoc scheme: codes, corrected pseudo-scale, running maximum
             float gmax;
             const float t = posthoc_group16(v, packed, gmax);
-            __builtin_amdgcn_raw_buffer_store_b64(u32x2{packed[0], packed[1]}, rc, so.codes, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(u32x2{packed[0], packed[1]}, rc, so.codes, 0, code_store_policy<kRht>());
             __builtin_amdgcn_raw_buffer_store_b32(f2u(t), row_rsrc(a.tbuf, (int64_t)row * G * 4, row_ok, (int)(G * 4)), so.t4, 0, 0);
             if (L.col_ok && row_ok) m = fmaxf(m, gmax);
             continue;
         }
         const uint32_t b = quantize_group16<kMode, kFast, true>(v, tc, draw[it], a.seed_sr, row, L.g, packed, inv_tab);
-        __builtin_amdgcn_raw_buffer_store_b64(u32x2{packed[0], packed[1]}, rc, so.codes, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b64(u32x2{packed[0], packed[1]}, rc, so.codes, 0, code_store_policy<kRht>());
         const __amdgpu_buffer_rsrc_t rs = row_rsrc(a.scales, (int64_t)row * G, row_ok, (int)G);
         if (kRht || G % 8 == 0) {   // whole octets (always so with rotation): one 8-byte store per chunk
             const uint2 sc = gather_scale_bytes(b, L.blk);
