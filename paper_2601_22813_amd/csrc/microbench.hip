@@ -59,6 +59,9 @@ __global__ __launch_bounds__(256) void mb_write(uint4 *__restrict__ b, uint64_t 
 // takes 4 rows x 1024 columns, a lane one 16-element group of each (2 x 16 bytes in, 8 bytes of
 // codes out, and the lane holding block 0 of an octet 8 bytes of scales), short-lived blocks of 4
 // waves, columns fastest over the grid.  b: codes (R*C/2 bytes) then scales (R*C/16 bytes).
+typedef uint32_t mb_u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t mb_u32x4 __attribute__((ext_vector_type(4)));
+
 __global__ __launch_bounds__(256) void mb_quant_traffic(const uint4 *__restrict__ a, uint8_t *__restrict__ b,
                                                         uint32_t R, uint32_t C)
 {
@@ -79,7 +82,8 @@ __global__ __launch_bounds__(256) void mb_quant_traffic(const uint4 *__restrict_
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const uint2 c = make_uint2(v[r][0].x ^ v[r][0].z ^ v[r][1].x ^ v[r][1].z, v[r][0].y ^ v[r][0].w ^ v[r][1].y ^ v[r][1].w);
-        *reinterpret_cast<uint2 *>(codes + ((uint64_t)(row0 + r) * C + 16u * g) / 2) = c;
+        // (non-temporal, as in the kernel)
+        __builtin_nontemporal_store(mb_u32x2{c.x, c.y}, reinterpret_cast<mb_u32x2 *>(codes + ((uint64_t)(row0 + r) * C + 16u * g) / 2));
         if ((lane & 7) == 0)
             *reinterpret_cast<uint2 *>(scales + ((uint64_t)(row0 + r) * C + 16u * g) / 16) = make_uint2(c.x + 1u, c.y + 1u);
     }
@@ -120,7 +124,8 @@ __global__ __launch_bounds__(256) void mb_quant_traffic_cols(const uint32_t *__r
             c.z ^= v[4 * i + 2] >> (16 * e);
             c.w ^= v[4 * i + 3] >> (16 * e);
         }
-        *reinterpret_cast<uint4 *>(codes + (uint64_t)(j0 + e) * (S / 2) + chunk * 64 + 16 * q) = c;
+        // (non-temporal, as in the kernel)
+        __builtin_nontemporal_store(mb_u32x4{c.x, c.y, c.z, c.w}, reinterpret_cast<mb_u32x4 *>(codes + (uint64_t)(j0 + e) * (S / 2) + chunk * 64 + 16 * q));
         if (q == 0) *reinterpret_cast<uint2 *>(scales + (uint64_t)(j0 + e) * (S / 16) + chunk * 8) = make_uint2(c.x, c.y);
     }
 }
