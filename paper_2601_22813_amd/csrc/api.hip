@@ -99,8 +99,10 @@ qii_status nvfp4_source(const qii_nvfp4 *in, int transpose, int rht_group, qii::
 qii_status quantize_source(const qii::Source &src, int64_t R, int64_t C, qii_mode mode, int rht_group,
                            uint64_t seed_rht, uint64_t seed_sr, const float *amax_in,
                            const qii_nvfp4 *out, float *amax_slot, float *tbuf, hipStream_t s,
-                           bool slot_zeroed = false, bool tiled_scales = false)
+                           bool slot_zeroed = false, bool tiled_scales = false, uint8_t *tiled_copy = nullptr)
 {
+    // tiled_copy (modes other than the post hoc scheme, no rotation, a dense source read along its rows,
+    // C a multiple of 256): the scale bytes are written there a second time, in the GEMM kernel's layout
     // tiled_scales (post hoc scheme only, C a multiple of 256, out->scales with room for R rounded up
     // to 256 rows): the scale bytes go out in the layout the main GEMM kernel reads
     if (mode != QII_RTN && mode != QII_SR && mode != QII_MS_EDEN && mode != QII_RTN_46 && mode != QII_MS_EDEN_PH)
@@ -146,6 +148,7 @@ qii_status quantize_source(const qii::Source &src, int64_t R, int64_t C, qii_mod
     a.seed_rht = seed_rht; a.seed_sr = seed_sr; a.amax = amax;
     a.codes = out->codes; a.scales = out->scales; a.tensor_scale = out->tensor_scale;
     a.tbuf = nullptr; a.amax_accum = nullptr;
+    a.scales_tiled = tiled_copy;
     hipError_t e = qii::launch_quantize(a, s);
     if (e != hipSuccess) return hip_fail(e, "quantize");
     return QII_OK;
@@ -607,11 +610,19 @@ qii_status qii_linear_fwd_amax(const void *X, const void *W, qii_dtype dt, int64
         hipError_t e = qii::launch_fill_u32(reinterpret_cast<uint32_t *>(slots), 0u, 2, slot_words, s);
         if (e != hipSuccess) return hip_fail(e, "fill");
     }
-    st = quantize_source(sx, T, d_in, mode, 0, 0, 0, amax_x, Xq, slots, nullptr, s, true);
+    // When the GEMM will take its main kernel (d_in a multiple of 256) the two quantizers also write
+    // their scale bytes straight into the GEMM workspace in that kernel's tiled layout: no re-tiling launch.
+    uint8_t *gws = p + 2 * kSlot;
+    const bool tile = d_in % 256 == 0 && T * d_out > 0 && qii::rows_kernels_apply(sx, T, d_in) && qii::rows_kernels_apply(sw, d_out, d_in);
+    uint8_t *x_tiled = tile ? gws : nullptr, *w_tiled = tile ? gws + (T + 255) / 256 * 256 * (d_in / 16) : nullptr;
+    st = quantize_source(sx, T, d_in, mode, 0, 0, 0, amax_x, Xq, slots, nullptr, s, true, false, x_tiled);
     if (st != QII_OK) return st;
-    st = quantize_source(sw, d_out, d_in, mode, 0, 0, 0, amax_w, Wq, slots + slot_words, nullptr, s, true);
+    st = quantize_source(sw, d_out, d_in, mode, 0, 0, 0, amax_w, Wq, slots + slot_words, nullptr, s, true, false, w_tiled);
     if (st != QII_OK) return st;
-    return qii_gemm_nvfp4_amax(Xq, Wq, Y, y_dt, d_out, amax_y, p + 2 * kSlot, ws_bytes - 2 * kSlot, stream);
+    // (the GEMM's arguments were checked above, before the first launch)
+    hipError_t e = qii::launch_gemm(*Xq, *Wq, Y, y_dt == QII_BF16, d_out, amax_y, gws, ws_bytes - 2 * kSlot, s, tile ? 12 : 0);
+    if (e != hipSuccess) return hip_fail(e, "gemm");
+    return QII_OK;
 }
 
 qii_status qii_linear_fwd(const void *X, const void *W, qii_dtype dt, int64_t T, int64_t d_in,

@@ -866,11 +866,13 @@ hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is
     const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
     const size_t need = K % BK4 == 0 ? scales_workspace_bytes(M, N, K) : 0;
-    if (K % BK4 == 0 && ws && ws_bytes >= need && (reinterpret_cast<uintptr_t>(ws) & 15) == 0 &&
-        (reinterpret_cast<uintptr_t>(A.scales) & 15) == 0 && (reinterpret_cast<uintptr_t>(B.scales) & 15) == 0) {
+    // (the re-tiling kernel reads the row-major scale bytes 16 at a time)
+    const bool a_ok = (pretiled & 4) || (reinterpret_cast<uintptr_t>(A.scales) & 15) == 0;
+    const bool b_ok = (pretiled & 8) || (reinterpret_cast<uintptr_t>(B.scales) & 15) == 0;
+    if (K % BK4 == 0 && ws && ws_bytes >= need && (reinterpret_cast<uintptr_t>(ws) & 15) == 0 && a_ok && b_ok) {
         uint8_t *a_ws = reinterpret_cast<uint8_t *>(ws);
         uint8_t *b_ws = a_ws + (M + 255) / 256 * 256 * (K / 16);
-        const uint8_t *a_tiled = (pretiled & 1) ? A.scales : a_ws;
+        const uint8_t *a_tiled = (pretiled & 1) ? A.scales : a_ws;   // (bits 2, 3: a_ws / b_ws are already filled)
         const uint8_t *b_tiled = (pretiled & 2) ? B.scales : b_ws;
         // the tiles of an incomplete last round are shared between blocks when the caller's workspace
         // has room for their partial tiles (behind the scales, 256-byte aligned)
@@ -879,7 +881,7 @@ hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is
         if (plan.rem && ws_bytes < poff + (size_t)(plan.grid + plan.rem) * BM * BN * 4) plan = StreamPlan{(int)(tiles_m * tiles_n), 0, 0};
         float *partial = plan.rem ? reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + poff) : nullptr;
         // (an operand whose scales arrive tiled takes no part: zero rows)
-        const int64_t ma = (pretiled & 1) ? 0 : M, nb_rows = (pretiled & 2) ? 0 : N;
+        const int64_t ma = (pretiled & 5) ? 0 : M, nb_rows = (pretiled & 10) ? 0 : N;
         const int64_t na = ma * (K / 256), nb = nb_rows * (K / 256);
         if (na + nb > 0)
             hipLaunchKernelGGL(retile_scales_kernel, dim3((unsigned)((na + nb + 255) / 256)), dim3(256), 0, s, A.scales,

@@ -38,6 +38,9 @@ struct QuantizeArgs {
     // bytes apart, a region of 16 KiB) at amax_accum (nullable: the caller supplies the maximum itself); launch_posthoc_scales finishes
     float *tbuf;
     uint32_t *amax_accum;
+    // a second copy of the scale bytes in the main GEMM kernel's tiled layout (nullable; only where
+    // rows_kernels_apply, no rotation, C a multiple of 256; room for R rounded up to 256 rows)
+    uint8_t *scales_tiled = nullptr;
 };
 
 // One read of a dense matrix producing Q(x) (side r: rows x cols) and Q(x^T) (side c: cols x rows),
@@ -92,7 +95,8 @@ hipError_t launch_quantize_cols(const QuantizeArgs &a, hipStream_t s);
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 // amax_c (nullable): device float that receives max |C| over the values as stored
 // pretiled: bit 0 / bit 1 say that A.scales / B.scales already hold the tiled layout (K a multiple
-// of 256, see launch_posthoc_scales), so that operand's re-tiling is skipped
+// of 256, see launch_posthoc_scales), bit 2 / bit 3 that A's / B's tiled scale bytes are already in
+// their place in ws (QuantizeArgs::scales_tiled); either way that operand's re-tiling is skipped
 hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is_bf16, int64_t ldc,
                        float *amax_c, void *ws, size_t ws_bytes, hipStream_t s, int pretiled = 0);
 

@@ -422,6 +422,7 @@ hipError_t launch_quantize(const QuantizeArgs &a, hipStream_t s)
 {
     if (a.R == 0 || a.C == 0) return hipSuccess;
     if (rows_kernels_apply(a.src, a.R, a.C)) return launch_quantize_rows(a, s);
+    if (a.scales_tiled) return hipErrorInvalidValue;   // only the rows kernels write the tiled copy
     if (cols_kernels_apply(a.src, a.R, a.C)) return launch_quantize_cols(a, s);
     const dim3 grid((unsigned)grid_for(a.R, a.C, 256)), block(256);
     return with_loader(a.src, [&](auto load) {

@@ -32,6 +32,7 @@ struct RowsArgs {
     uint32_t *amax_out;  // abs-max kernel (one word), and the heavy pass of the post hoc scheme
                          // (kAmaxSpread words, nullable there)
     float *tbuf;         // post hoc scheme: corrected pseudo-scales [R][C/16]
+    uint8_t *tiled;      // nullable: a second copy of the scale bytes, [row / 256][C / 256][row % 256][16]
     int wpr;             // waves of a block that sit side by side on a row: 1, 2 or 4
     int gy;              // blocks side by side on a row; the grid is one-dimensional, columns fastest
 };
@@ -130,6 +131,7 @@ struct StoreOffsets {
     uint32_t scale8;   // the gathered 8 scale bytes of a chunk: the lane holding block 0 stores them
     uint32_t scale1;   // one scale byte per lane (rows whose group count is not a multiple of 8)
     uint32_t t4;       // post hoc scheme: one f32 per group
+    uint32_t tiled8;   // the chunk's 8 scale bytes within the tiled copy, relative to (row tile, row)
 };
 
 // One quad of rows for one lane: the four rows' raw words are in registers (requested at the very
@@ -168,6 +170,12 @@ __device__ __forceinline__ void quantize_quad(const RowsArgs &a, const LaneSetup
         if (kRht || G % 8 == 0) {   // whole octets (always so with rotation): one 8-byte store per chunk
             const uint2 sc = gather_scale_bytes(b, L.blk);
             __builtin_amdgcn_raw_buffer_store_b64(u32x2{sc.x, sc.y}, rs, so.scale8, 0, 0);
+            if (!kRht && a.tiled) {   // uniform: the forward pass's copy for the GEMM (C a multiple of 256)
+                const int64_t ksn = a.C / 256;
+                const __amdgpu_buffer_rsrc_t rt = row_rsrc(a.tiled, ((int64_t)(row >> 8) * ksn * 256 + (row & 255)) * 16, row_ok,
+                                                           (int)(ksn * 4096 - (row & 255) * 16));
+                __builtin_amdgcn_raw_buffer_store_b64(u32x2{sc.x, sc.y}, rt, so.tiled8, 0, 0);
+            }
         } else {
             __builtin_amdgcn_raw_buffer_store_b8((uint8_t)b, rs, so.scale1, 0, 0);
         }
@@ -197,12 +205,14 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowsArgs a)
     so.scale8 = (L.col_ok && L.blk == 0) ? (uint32_t)L.g : kNoStore;
     so.scale1 = L.col_ok ? (uint32_t)L.g : kNoStore;
     so.t4 = L.col_ok ? (uint32_t)L.g * 4u : kNoStore;
+    so.tiled8 = (L.col_ok && L.blk == 0) ? (uint32_t)(L.g >> 4) * 4096u + (uint32_t)((L.g >> 3) & 1) * 8u : kNoStore;
     if (tc.zero) {  // uniform: an all-zero tensor is emitted as zero bytes
         for (int it = 0; it < 4; ++it) {
             const int64_t row = (int64_t)L.quad * 4 + it;
             if (L.col_ok && row < a.R) {
                 *reinterpret_cast<uint2 *>(a.codes + (row * a.C + L.g * 16) / 2) = make_uint2(0u, 0u);
                 a.scales[row * G + L.g] = 0;
+                if (!kRht && a.tiled) a.tiled[(((row >> 8) * (a.C / 256) + (L.g >> 4)) * 256 + (row & 255)) * 16 + (L.g & 15)] = 0;
             }
         }
         return;
@@ -298,6 +308,7 @@ RowsArgs make_args(const Source &src, int64_t R, int64_t C, uint64_t seed_rht, u
     a.seed_sr = seed_sr;
     a.amax = nullptr; a.codes = nullptr; a.scales = nullptr; a.tensor_scale = nullptr; a.amax_out = nullptr;
     a.tbuf = nullptr;
+    a.tiled = nullptr;
     a.wpr = rows_wpr(C);
     const int64_t nch = (C / 16 + 7) / 8;
     a.gy = (int)((nch + 8 * a.wpr - 1) / (8 * a.wpr));
@@ -331,6 +342,10 @@ hipError_t launch_quantize_rows(const QuantizeArgs &q, hipStream_t s)
     RowsArgs a = make_args(q.src, q.R, q.C, q.seed_rht, q.seed_sr);
     a.amax = q.amax; a.codes = q.codes; a.scales = q.scales; a.tensor_scale = q.tensor_scale;
     a.tbuf = q.tbuf; a.amax_out = q.amax_accum;
+    if (q.scales_tiled) {
+        if (q.rht || q.C % 256 != 0 || q.mode == QII_MS_EDEN_PH) return hipErrorInvalidValue;
+        a.tiled = q.scales_tiled;
+    }
     const dim3 grid = rows_grid(q.R, q.C, 0), block(256);
     const bool bf = q.src.kind == kSrcBF16;
 #define QII_ROWS(BF, MODE, RHT) hipLaunchKernelGGL((quantize_rows_kernel<BF, MODE, RHT>), grid, block, 0, s, a)

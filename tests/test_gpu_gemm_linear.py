@@ -210,6 +210,30 @@ def test_linear_forward_with_four_over_six(oracle):
     assert torch.equal(Y2, Y)
 
 
+@pytest.mark.parametrize("T,d_in,d_out,zero_x", [(320, 768, 272, False), (320, 384, 272, False), (320, 768, 272, True)])
+def test_linear_forward_scale_layouts(oracle, T, d_in, d_out, zero_x):
+    """With d_in a multiple of 256 the forward quantizers also write their scale bytes in the GEMM
+    kernel's tiled layout (ragged row counts here: 320 and 272 rows in tiles of 256); otherwise the
+    GEMM reads the row-major bytes.  Saved operands and Y must match either way, also for an all-zero
+    X, whose quantizer takes a separate path."""
+    Xb, Wb, _ = synth.linear_layer_bf16(T, d_in, d_out, seed=11)
+    if zero_x:
+        Xb = np.zeros_like(Xb)
+    X, W = to_dev(Xb), to_dev(Wb)
+    for mode, omode in ((qii.RTN, oracle.RTN), (qii.RTN_46, oracle.RTN_46)):
+        Xq, Wq = qii.NVFP4Tensor.empty(T, d_in), qii.NVFP4Tensor.empty(d_out, d_in)
+        Y = torch.full((T, d_out), 7.0, dtype=torch.float32, device="cuda")
+        qii.qii_linear_fwd_mode(X, W, mode, Y, Xq, Wq, ws(qii.qii_linear_fwd_workspace_bytes(T, d_in, d_out)))
+        oXq, oWq = oracle.linear_fwd(Xb, Wb, mode=omode)
+        assert_nv_equal(Xq, oXq, "saved X")
+        assert_nv_equal(Wq, oWq, "saved W")
+        ref, absum = oracle.gemm(oXq, oWq, with_abs=True)
+        torch.cuda.synchronize()
+        check(Y.cpu().numpy().astype(np.float64), ref, absum, False)
+        if zero_x:
+            assert float(Y.abs().max()) == 0.0
+
+
 def test_layer_passes_replay_from_a_hip_graph(oracle):
     """Nothing in the library allocates, synchronises or uses memset nodes, so a forward + backward
     pass can be captured once and replayed; every replay (with eager work and synchronisations in
