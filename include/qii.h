@@ -318,6 +318,22 @@ typedef enum QII_ENUM_INT {
 } qii_microbench_kind;
 qii_status qii_microbench(int kind, void *a, void *b, uint64_t n, int blocks, int iters, void *stream);
 
+/* Test aids for the GEMM's shared last round (host computations, no device work): the index
+ * arithmetic the kernels use, callable on a CPU so that it can be checked by brute force.
+ * qii_gemm_sharing_plan: plan[0] = launch positions run one block per output tile, plan[1] = tiles
+ *   after them that are shared between blocks (0: none), plan[2] = number of sharing blocks, for a
+ *   GEMM of M x N x K whose workspace has qii_gemm_workspace_bytes.
+ * qii_gemm_sharing_segments: the tile segments of the block with hardware id block_id when `grid`
+ *   blocks share `rem` tiles of `ktotal` K tiles each; out receives 5 numbers per segment (block
+ *   number, shared tile, first K tile, K tiles, partial-tile slot); returns the number of segments
+ *   (at most 4 are written; -1 if there would be more; QII-style errors do not apply: arguments must
+ *   satisfy 0 < rem, 8 <= ktotal, 0 < grid, 0 <= block_id < grid).
+ * qii_gemm_sharing_tile_slots: out[0], out[1] = first and last slot that are added up for shared
+ *   tile lt, in this order.                                                               */
+void qii_gemm_sharing_plan(int64_t M, int64_t N, int64_t K, int32_t plan[3]);
+int qii_gemm_sharing_segments(int rem, int ktotal, int grid, int block_id, int32_t *out);
+void qii_gemm_sharing_tile_slots(int rem, int ktotal, int grid, int lt, int32_t out[2]);
+
 /* Host helpers.                                                                        */
 uint64_t qii_derive_seed(uint64_t seed, uint32_t i); /* backward sub-seed i (0..5)      */
 const char *qii_status_string(qii_status s);

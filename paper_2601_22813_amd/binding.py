@@ -27,6 +27,7 @@ EXPORTS = [
     "qii_derive_seed", "qii_status_string", "qii_last_error", "qii_version", "qii_selftest_conversions", "qii_microbench", "qii_gemm_nvfp4_inexact", "qii_gemm_inexact_workspace_bytes",
     "qii_quantize_nvfp4_noalloc", "qii_gemm_nvfp4_amax", "qii_linear_fwd_amax",
     "qii_quantize_pair_nvfp4", "qii_quantize_pair_workspace_bytes",
+    "qii_gemm_sharing_plan", "qii_gemm_sharing_segments", "qii_gemm_sharing_tile_slots",
 ]
 
 

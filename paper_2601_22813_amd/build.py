@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqii.so")
 SOURCES = ["api.hip", "quantize.hip", "quantize_rows.hip", "quantize_cols.hip", "quantize_pair.hip", "gemm.hip", "gemm_inexact.hip", "selftest.hip", "microbench.hip"]
-HEADERS = ["qii_device.h", "qii_internal.h", "quantize_core.h", "quantize_lanes.h", "gemm_common.h", os.path.join("..", "..", "include", "qii.h")]
+HEADERS = ["qii_device.h", "qii_internal.h", "quantize_core.h", "quantize_lanes.h", "gemm_common.h", "gemm_sharing_map.h", os.path.join("..", "..", "include", "qii.h")]
 
 # -ffp-contract=off: the quantizers take integer decisions from binary32 arithmetic whose
 # every rounding is part of the contract with the parity oracle; fused operations appear

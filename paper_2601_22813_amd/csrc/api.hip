@@ -703,6 +703,26 @@ qii_status qii_linear_bwd_mode(const void *dY, qii_dtype dt, const qii_nvfp4 *Xq
     return gemm_internal(&ETq, &XTq, dW, g_dt, d_in, gws, gws_bytes, stream, tile_dw ? 3 : 0);
 }
 
+void qii_gemm_sharing_plan(int64_t M, int64_t N, int64_t K, int32_t plan[3])
+{
+    plan[0] = plan[1] = plan[2] = 0;
+    if (M <= 0 || N <= 0 || K <= 0) return;
+    qii::gemm_sharing_plan(M, N, K, plan);
+}
+
+int qii_gemm_sharing_segments(int rem, int ktotal, int grid, int block_id, int32_t *out)
+{
+    if (rem <= 0 || ktotal < 8 || grid <= 0 || block_id < 0 || block_id >= grid || !out) return -1;
+    return qii::gemm_sharing_segments(rem, ktotal, grid, block_id, out);
+}
+
+void qii_gemm_sharing_tile_slots(int rem, int ktotal, int grid, int lt, int32_t out[2])
+{
+    out[0] = out[1] = -1;
+    if (rem <= 0 || ktotal < 8 || grid <= 0 || lt < 0 || lt >= rem) return;
+    qii::gemm_sharing_tile_slots(rem, ktotal, grid, lt, out);
+}
+
 qii_status qii_selftest_conversions(uint64_t *counts, void *stream)
 {
     if (!counts || !aligned(counts, 8)) return fail(QII_INVALID_ARG, "counts must be 8 device uint64, 8-byte aligned");

@@ -20,6 +20,7 @@
 // lanes 32..63 supply k 32..63, four MFMAs walk the four dwords of a lane's 16 bytes
 // (the order of k inside the contraction is free as long as A and B agree).
 #include "gemm_common.h"
+#include "gemm_sharing_map.h"
 #include "qii_device.h"
 #include "qii_internal.h"
 
@@ -557,14 +558,6 @@ __device__ __forceinline__ void tile_origin(int pos, int tiles_m, int tiles_n, i
     n0 = (int64_t)((tile % width) / gm) * BN;
 }
 
-// Tiles beyond the last full round of the grid are shared between blocks (see stream_plan): the
-// `rem` launch positions from `base` on, numbered so that the blocks of one XCD (a contiguous range
-// of K-tile units, hence of these numbers) work on positions of that XCD's own run of tiles.
-__device__ __forceinline__ int stream_pos(int lt, int rem, int base)
-{
-    return base + ((rem & 7) == 0 ? (lt % (rem >> 3)) * 8 + lt / (rem >> 3) : lt);
-}
-
 // kStream = false: one block per output tile (launch position blockIdx.x).
 // kStream = true: the K tiles of the `sk_rem` tiles from position `sk_base` on form one sequence of
 // units (tile-major) that the gridDim.x blocks cut into equal contiguous ranges; a block runs its
@@ -595,19 +588,15 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel_v4(const uint8_t *__restri
     int blk = 0;
     if (kStream) {
         const int G = (int)gridDim.x;
-        blk = (G & 7) == 0 ? (int)(blockIdx.x & 7) * (G >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
-        const int64_t U = (int64_t)sk_rem * ktotal;
-        u = U * blk / G;
-        u_end = U * (blk + 1) / G;
+        blk = sharing_block_number((int)blockIdx.x, G);
+        sharing_block_units((int64_t)sk_rem * ktotal, G, blk, u, u_end);
     }
     for (;;) {
     // this segment: K tiles [kt0, kt0 + ktiles) of the tile at launch position pos
     int pos = (int)blockIdx.x, kt0 = 0, ktiles = ktotal, lt = 0;
     if (kStream) {
-        lt = (int)(u / ktotal);
-        kt0 = (int)(u % ktotal);
-        ktiles = (int)(u_end - u) < ktotal - kt0 ? (int)(u_end - u) : ktotal - kt0;
-        pos = stream_pos(lt, sk_rem, sk_base);
+        sharing_segment(u, u_end, ktotal, lt, kt0, ktiles);
+        pos = sharing_position(lt, sk_rem, sk_base);
     }
     int64_t m0, n0;
     tile_origin(pos, tiles_m, tiles_n, m0, n0);
@@ -702,7 +691,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel_v4(const uint8_t *__restri
         store_tile_through_lds<kBf16Out>(acc, smem, (*a_ts) * (*b_ts), Cout, ldc, M, N, m0, n0, wave, wm, wn, lane, li, kb, amax_out);
         break;
     }
-    store_tile_through_lds<false, false>(acc, smem, 1.0f, partial + (int64_t)(blk + lt) * (BM * BN), BN, BM, BN, 0, 0, wave, wm, wn, lane,
+    store_tile_through_lds<false, false>(acc, smem, 1.0f, partial + (int64_t)sharing_slot(blk, lt) * (BM * BN), BN, BM, BN, 0, 0, wave, wm, wn, lane,
                                   li, kb, nullptr);
     u += ktiles;
     if (u >= u_end) break;
@@ -724,16 +713,15 @@ __global__ __launch_bounds__(256) void streamk_fixup_kernel(const float *__restr
     const int lt = (int)(blockIdx.x >> 4), strip = (int)(blockIdx.x & 15);
     const int64_t U = (int64_t)sk_rem * ktotal;
     const int64_t ufirst = (int64_t)lt * ktotal, ulast = ufirst + ktotal - 1;
-    // the block whose range [U b / G, U (b + 1) / G) holds unit u is floor(((u + 1) G - 1) / U)
-    const int b_first = (int)(((ufirst + 1) * G - 1) / U), b_last = (int)(((ulast + 1) * G - 1) / U);
+    const int b_first = sharing_block_of_unit(ufirst, U, G), b_last = sharing_block_of_unit(ulast, U, G);
     int64_t m0, n0;
-    tile_origin(stream_pos(lt, sk_rem, sk_base), tiles_m, tiles_n, m0, n0);
+    tile_origin(sharing_position(lt, sk_rem, sk_base), tiles_m, tiles_n, m0, n0);
     const float ts = (*a_ts) * (*b_ts);
     float cmax = 0.0f;
 #pragma unroll
     for (int pass = 0; pass < 4; ++pass) {
         const int row = strip * 16 + pass * 4 + (int)(threadIdx.x >> 6), col = (int)(threadIdx.x & 63) * 4;
-        const float *src = partial + (int64_t)(b_first + lt) * (BM * BN) + row * BN + col;
+        const float *src = partial + (int64_t)sharing_slot(b_first, lt) * (BM * BN) + row * BN + col;
         float4 acc = *reinterpret_cast<const float4 *>(src);
         for (int b = b_first + 1; b <= b_last; ++b) {
             src += BM * BN;
@@ -825,6 +813,36 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
     const StreamPlan plan = stream_plan(M, N, K);
     const size_t sc = scales_workspace_bytes(M, N, K);
     return plan.rem ? (sc + 255) / 256 * 256 + (size_t)(plan.grid + plan.rem) * BM * BN * 4 : sc;
+}
+
+// test aids (host only): the sharing plan of a shape and the mapping the kernels use
+void gemm_sharing_plan(int64_t M, int64_t N, int64_t K, int32_t plan[3])
+{
+    const StreamPlan p = stream_plan(M, N, K);
+    plan[0] = p.full; plan[1] = p.rem; plan[2] = p.grid;
+}
+
+int gemm_sharing_segments(int rem, int ktotal, int grid, int block_id, int32_t *out)
+{
+    const int blk = sharing_block_number(block_id, grid);
+    int64_t u, u_end;
+    sharing_block_units((int64_t)rem * ktotal, grid, blk, u, u_end);
+    int n = 0;
+    while (u < u_end && n < 4) {
+        int lt, kt0, ktiles;
+        sharing_segment(u, u_end, ktotal, lt, kt0, ktiles);
+        out[5 * n] = blk; out[5 * n + 1] = lt; out[5 * n + 2] = kt0; out[5 * n + 3] = ktiles; out[5 * n + 4] = sharing_slot(blk, lt);
+        u += ktiles;
+        ++n;
+    }
+    return u < u_end ? -1 : n;
+}
+
+void gemm_sharing_tile_slots(int rem, int ktotal, int grid, int lt, int32_t out[2])
+{
+    const int64_t U = (int64_t)rem * ktotal;
+    out[0] = sharing_slot(sharing_block_of_unit((int64_t)lt * ktotal, U, grid), lt);
+    out[1] = sharing_slot(sharing_block_of_unit((int64_t)lt * ktotal + ktotal - 1, U, grid), lt);
 }
 
 template <bool kBf16Out>

@@ -100,6 +100,14 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemm(const qii_nvfp4 &A, const qii_nvfp4 &B, void *C, int c_is_bf16, int64_t ldc,
                        float *amax_c, void *ws, size_t ws_bytes, hipStream_t s, int pretiled = 0);
 
+// host-only test aids for the shared last round of the main GEMM kernel (gemm_sharing_map.h):
+// plan = {positions run one block per tile, shared tiles, sharing blocks}; the segments of a
+// hardware block id as {block number, shared tile, first K tile, K tiles, slot} (returns their
+// number, -1 beyond 4); the first and last partial-tile slot the fix-up kernel adds up for a tile
+void gemm_sharing_plan(int64_t M, int64_t N, int64_t K, int32_t plan[3]);
+int gemm_sharing_segments(int rem, int ktotal, int grid, int block_id, int32_t *out);
+void gemm_sharing_tile_slots(int rem, int ktotal, int grid, int lt, int32_t out[2]);
+
 // sweeps of the hardware conversions and short division sequences against their value-space
 // rules; counts[0..7] (device) receive the numbers of mismatches (selftest.hip)
 // exploratory non-exact GEMM variants (gemm_inexact.hip); ws as gemm_inexact_workspace_bytes says

@@ -45,6 +45,32 @@ int main(void)
                 for (int m = 0; m <= 5; ++m) sink ^= qii_linear_bwd_mode_workspace_bytes(dims[a], dims[b], dims[c], (qii_mode)m);
             }
         }
+    /* the GEMM's sharing plan and its index arithmetic (host-side test aids): every planned shape's segments stay in range */
+    for (int a = 0; a < nd; ++a)
+        for (int b = 0; b < nd; ++b)
+            for (int c = 0; c < nd; ++c) {
+                int32_t plan[3], seg[20], sl[2];
+                qii_gemm_sharing_plan(dims[a], dims[b], dims[c], plan);
+                if (plan[1] <= 0) continue;
+                const int ktotal = (int)(dims[c] / 256);
+                for (int id = 0; id < plan[2]; id += 1 + plan[2] / 7) {
+                    const int n = qii_gemm_sharing_segments(plan[1], ktotal, plan[2], id, seg);
+                    if (n < 1 || n > 2) ++fails;
+                    for (int i = 0; i < n; ++i)
+                        if (seg[5 * i + 1] < 0 || seg[5 * i + 1] >= plan[1] || seg[5 * i + 4] < 0 || seg[5 * i + 4] >= plan[1] + plan[2]) ++fails;
+                }
+                for (int lt = 0; lt < plan[1]; lt += 1 + plan[1] / 5) {
+                    qii_gemm_sharing_tile_slots(plan[1], ktotal, plan[2], lt, sl);
+                    if (sl[0] < 0 || sl[1] < sl[0] || sl[1] >= plan[1] + plan[2]) ++fails;
+                }
+            }
+    {
+        int32_t seg[20], sl[2];
+        if (qii_gemm_sharing_segments(0, 8, 8, 0, seg) != -1 || qii_gemm_sharing_segments(4, 8, 8, 8, seg) != -1 ||
+            qii_gemm_sharing_segments(4, 7, 8, 0, seg) != -1 || qii_gemm_sharing_segments(4, 8, 8, 0, NULL) != -1) ++fails;
+        qii_gemm_sharing_tile_slots(4, 8, 8, 4, sl);
+        if (sl[0] != -1) ++fails;
+    }
     /* quantizer argument checks */
     qii_nvfp4 out = {P(0x1000), P(0x1000), P(0x1000), 4, 120};
     EXPECT(qii_quantize_nvfp4(P(0x1000), QII_BF16, 4, 120, 120, 0, QII_RTN, 0, 0, 0, NULL, &out, NULL, 0, NULL), QII_BAD_SHAPE);
